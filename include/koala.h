@@ -1,0 +1,184 @@
+/*
+ * koala.h - C ABI of the draft-then-verify hot path of multi-layer-draft-head
+ * speculative decoding on one AMD MI355X (gfx950).
+ *
+ * One iteration (paper section 2.2): a K-layer draft head proposes candidate
+ * tokens arranged in a static tree (Eq. 2; EAGLE-style or Medusa-style head,
+ * section 3.1), the target model scores all of them in one pass (Eq. 3), and
+ * the longest root path whose tokens equal the target's greedy choices is kept
+ * together with the target's own next token (sections 2.2 and 4.1).
+ *
+ * General rules
+ *  - "device" pointers are HIP device memory owned by the caller; "host"
+ *    pointers are ordinary host memory.  The library allocates no device
+ *    memory: all scratch lives in the caller's workspace (koala_bind).
+ *  - Tensors are dense, row-major, 16-byte aligned.  Weights and KV caches are
+ *    stored in the model dtype (fp32 or bfloat16); features, logits and scores
+ *    are always fp32; token ids, node ids and lengths are int32.
+ *  - Linear layers are [out_features, in_features] and have no bias.
+ *  - Every compute call only enqueues work on the given hipStream_t (passed as
+ *    void*); it never synchronises and never reads results back.  Calls on one
+ *    context must be issued on one stream, or otherwise ordered by the caller.
+ *  - Arguments are validated on the host before anything is launched; a call
+ *    that returns an error has had no effect on device memory.  Errors are
+ *    returned as negative koala_status values; koala_last_error() gives text.
+ *  - Limits: at most 64 tree nodes per sequence, at most 64 catch-up rows (m),
+ *    head_dim 64 or 128, hidden = n_heads * head_dim; for bfloat16 hidden and
+ *    ffn must be multiples of 64.
+ */
+#ifndef KOALA_H
+#define KOALA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct koala_ctx koala_ctx; /* opaque, host-side */
+
+typedef enum {
+    KOALA_OK = 0,
+    KOALA_E_NULL = -1,        /* a required pointer is NULL */
+    KOALA_E_SHAPE = -2,       /* inconsistent sizes, malformed tree, batch/m out of range */
+    KOALA_E_ALIGN = -3,       /* a device pointer is not 16-byte aligned */
+    KOALA_E_CAPACITY = -4,    /* KV capacity cannot hold context + tree rows */
+    KOALA_E_UNSUPPORTED = -5, /* dtype / head_dim / draft kind not implemented */
+    KOALA_E_WORKSPACE = -6,   /* workspace missing or too small, or context not bound */
+    KOALA_E_DEVICE = -7       /* a HIP call or kernel launch failed */
+} koala_status;
+
+enum { KOALA_FP32 = 0, KOALA_BF16 = 1 };
+enum { KOALA_DRAFT_EAGLE = 0, KOALA_DRAFT_MEDUSA = 1 };
+enum { KOALA_MAX_NODES = 64, KOALA_MAX_M = 64 };
+
+/* Llama-style decoder stack of the target model (section 4.1). */
+typedef struct {
+    int hidden, n_heads, head_dim, ffn, vocab, n_layers;
+    float rms_eps, rope_base;
+    int dtype; /* KOALA_FP32 or KOALA_BF16: storage type of weights and KV caches */
+} koala_shape;
+
+/* Draft head (section 3.1).  EAGLE-style: Linear over [embedding ; feature]
+ * followed by K decoder layers of the target's shape, sharing the target's
+ * embedding and LM head.  Medusa-style: medusa_heads heads, head j being K
+ * residual blocks x <- x + SiLU(W x) followed by the shared LM head; head j
+ * fills tree depth j+1, so medusa_heads must be >= tree depth. */
+typedef struct {
+    int kind;         /* KOALA_DRAFT_EAGLE or KOALA_DRAFT_MEDUSA */
+    int K;            /* layers per head, >= 1 */
+    int medusa_heads; /* Medusa only */
+    int max_m;        /* largest m passed to koala_draft_expand (1..KOALA_MAX_M) */
+} koala_draft_shape;
+
+/* Static candidate tree; host arrays, copied by koala_create.  Node 0 is the
+ * root (the newest committed token); parent[0] = -1 and parent[i] < i; nodes
+ * are ordered by depth.  rank[i] says which of its parent's top-k tokens node i
+ * receives (0 = most likely); siblings have distinct ranks below
+ * topk_per_depth[depth(i) - 1]. */
+typedef struct {
+    int n_nodes, depth;
+    const int32_t *parent;         /* host int32[n_nodes] */
+    const int32_t *rank;           /* host int32[n_nodes] */
+    const int32_t *topk_per_depth; /* host int32[depth] */
+} koala_tree;
+
+/* Device weight pointers, borrowed until koala_destroy or the next koala_bind.
+ *   embed, lm_head  [vocab, hidden];  final_norm [hidden]
+ *   layer_w: host array of 6 * n_layers device pointers, per layer
+ *       in_norm [hidden], wqkv [3*hidden, hidden] (rows: all of W_q, then W_k, then W_v),
+ *       wo [hidden, hidden], post_norm [hidden],
+ *       wgu [2*ffn, hidden] with rows interleaved (row 2f = gate_f, row 2f+1 = up_f),
+ *       wdown [hidden, ffn]
+ *   EAGLE: fc [hidden, 2*hidden] acting on [embedding ; feature];
+ *          draft_w: host array of 6 * K pointers, same per-layer order as layer_w
+ *   Medusa: fc = NULL; draft_w: host array of medusa_heads * K pointers,
+ *          draft_w[j*K + k] = W_{j,k} [hidden, hidden] */
+typedef struct {
+    const void *embed, *lm_head, *final_norm;
+    const void *const *layer_w;
+    const void *fc;
+    const void *const *draft_w;
+} koala_weights;
+
+/* KV caches, device, model dtype, layout [layer][batch][n_heads][capacity][head_dim]
+ * (target: n_layers layers; EAGLE draft: K layers; Medusa: draft_k = draft_v = NULL).
+ * Keys are stored already rotated.  ctx_len: device int32[max_batch]; ctx_len[b]
+ * = number of committed rows C_b of sequence b in the target cache.  Rows
+ * C_b .. C_b + n_nodes - 1 are scratch for the tree, so capacity must always be
+ * >= C_b + n_nodes (the caller's responsibility: C_b lives on the device). */
+typedef struct {
+    void *target_k, *target_v, *draft_k, *draft_v;
+    int capacity;
+    int32_t *ctx_len;
+} koala_kv;
+
+/* Create a context for a model shape, draft head and tree.  Host only. */
+koala_status koala_create(const koala_shape *shape, const koala_draft_shape *draft,
+                          const koala_tree *tree, int max_batch, koala_ctx **out);
+
+/* Bytes of device workspace koala_bind needs for this context. */
+koala_status koala_workspace_bytes(const koala_ctx *ctx, size_t *out);
+
+/* Attach weights, KV caches and a device workspace (>= koala_workspace_bytes,
+ * 256-byte aligned).  Copies the tree tables into the workspace with a
+ * synchronous host-to-device copy.  The workspace contents belong to the
+ * library until koala_destroy. */
+koala_status koala_bind(koala_ctx *ctx, const koala_weights *w, const koala_kv *kv,
+                        void *workspace, size_t workspace_bytes);
+
+/* Draft step (Eq. 2).  For each sequence b < batch:
+ *   feat_in  device fp32 [batch, m, hidden]: target features (hidden state after
+ *            the final RMSNorm) of the m newest committed positions C_b-m .. C_b-1;
+ *   tok_in   device int32 [batch, m]: the token following each of them;
+ *            tok_in[b, m-1] is the newest committed token = tree root.
+ * EAGLE: the draft cache must hold rows 0 .. C_b-m-1; rows C_b-m .. C_b-1 are
+ * computed first (row i pairs feature i with token i+1 at position i), then the
+ * tree is expanded depth by depth: every node that has children is run through
+ * the head at position C_b-1+depth, attending to the draft context and its own
+ * ancestors, and its top-k tokens (descending logit, ties to the lower id) go
+ * to its children by rank.  Draft-cache rows >= C_b are scratch afterwards.
+ * Medusa: only feat_in[b, m-1] is used.
+ *   tree_tokens device int32 [batch, n_nodes] (out): token of every node, root included;
+ *   tree_scores device fp32 [batch, n_nodes] (out, may be NULL): draft logit of
+ *            each node's token under its parent (root: 0). */
+koala_status koala_draft_expand(koala_ctx *ctx, void *hip_stream, int batch,
+                                const float *feat_in, const int32_t *tok_in, int m,
+                                int32_t *tree_tokens, float *tree_scores);
+
+/* Verification (Eq. 3).  Runs the target on all n_nodes rows of each sequence:
+ * node i is at position C_b + depth(i), its key/value are written to cache slot
+ * C_b + i of every layer, and it attends to the C_b context rows plus itself
+ * and its ancestors.
+ *   tree_tokens device int32 [batch, n_nodes];
+ *   feat_out    device fp32 [batch, n_nodes, hidden] (out): features after the final RMSNorm;
+ *   logits_out  device fp32 [batch, n_nodes, vocab] (out, may be NULL);
+ *   greedy_out  device int32 [batch, n_nodes] (out): argmax of each row's logits,
+ *               lowest id among equal maxima. */
+koala_status koala_tree_verify(koala_ctx *ctx, void *hip_stream, int batch,
+                               const int32_t *tree_tokens, float *feat_out, float *logits_out,
+                               int32_t *greedy_out);
+
+/* Greedy acceptance (sections 2.2, 4.1).  Starting at the root, repeatedly step
+ * to the lowest-numbered child whose token equals greedy[current]; stop when
+ * there is none.
+ *   accept_len  device int32 [batch] (out): number of accepted drafted tokens a, 0..depth;
+ *   accept_path device int32 [batch, depth+1] (out): node ids root..last accepted, then -1;
+ *   next_token  device int32 [batch] (out): greedy[last accepted node];
+ *   commit != 0: additionally, in every target layer, copy the key/value rows of
+ *               the path nodes to slots C_b .. C_b+a and set ctx_len[b] += a+1. */
+koala_status koala_accept_prefix(koala_ctx *ctx, void *hip_stream, int batch,
+                                 const int32_t *tree_tokens, const int32_t *greedy,
+                                 int32_t *accept_len, int32_t *accept_path, int32_t *next_token,
+                                 int commit);
+
+/* Text of the last error on this context ("" if none); valid until the next call. */
+const char *koala_last_error(const koala_ctx *ctx);
+
+void koala_destroy(koala_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KOALA_H */

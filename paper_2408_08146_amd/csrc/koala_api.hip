@@ -1,0 +1,391 @@
+// C ABI of the draft-then-verify library: argument validation, workspace layout and the
+// sequence of kernel launches for each entry point.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+
+#include "koala_internal.h"
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+koala_status fail(koala_ctx *c, koala_status st, const char *msg) {
+    if (c) c->err = msg;
+    return st;
+}
+
+inline bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
+
+// Walks the workspace; with base == nullptr it only measures.
+struct Carver {
+    char *base;
+    size_t off;
+    template <typename T>
+    T *take(size_t n) {
+        T *p = base ? (T *)(base + off) : nullptr;
+        off += up(n * sizeof(T));
+        return p;
+    }
+};
+
+int attn_nsplit(const koala_ctx *c) {
+    // enough (split, head, sequence) workgroups to cover the chip a few times over
+    int ns = 1024 / std::max(1, c->shape.n_heads * 1);
+    return std::max(1, std::min((int)KOALA_NSPLIT_MAX, ns));
+}
+
+size_t carve(koala_ctx *c, char *base) {
+    Carver w{base, 0};
+    const koala_shape &s = c->shape;
+    const int T = c->T, D = c->D, R = c->max_rows, H = s.hidden, F = s.ffn, V = s.vocab;
+    const int half = s.head_dim / 2, ns = attn_nsplit(c);
+    (void)w.take<double>(half);  // inv_freq, first in the workspace
+    c->tt.parent = w.take<int32_t>(T);
+    c->tt.depth = w.take<int32_t>(T);
+    c->tt.rank = w.take<int32_t>(T);
+    c->tt.anc_mask = w.take<uint64_t>(T);
+    c->tt.exp_index = w.take<int32_t>(T);
+    c->tt.draft_mask = w.take<uint64_t>(T);
+    c->tt.level_nodes = w.take<int32_t>((size_t)(D + 1) * 64);
+    c->tt.child_first = nullptr;
+    c->tt.child_count = nullptr;
+    c->meta.row_b = w.take<int32_t>(R);
+    c->meta.row_pos = w.take<int32_t>(R);
+    c->meta.row_slot = w.take<int32_t>(R);
+    c->meta.row_nvis = w.take<int32_t>(R);
+    c->meta.row_base = w.take<int32_t>(R);
+    c->meta.row_mask = w.take<uint64_t>(R);
+    c->meta.kv_end = w.take<int32_t>(c->max_batch);
+    c->meta.rope_cos = w.take<float>((size_t)R * half);
+    c->meta.rope_sin = w.take<float>((size_t)R * half);
+    c->x = w.take<float>((size_t)R * H);
+    c->act = w.take<float>((size_t)R * std::max(2 * H, F));
+    c->qkv = w.take<float>((size_t)R * 3 * H);
+    c->qrot = w.take<float>((size_t)R * H);
+    c->attn_out = w.take<float>((size_t)R * H);
+    c->gu = w.take<float>((size_t)R * 2 * F);
+    c->o_part = w.take<float>((size_t)R * H * ns);
+    c->ml = w.take<float>((size_t)R * s.n_heads * ns * 2);
+    c->logits = w.take<float>((size_t)R * V);
+    c->fhat = w.take<float>((size_t)c->max_batch * T * H);
+    c->topk_val = w.take<float>((size_t)R * KOALA_TOPK_MAX);
+    c->topk_idx = w.take<int32_t>((size_t)R * KOALA_TOPK_MAX);
+    c->tok_tmp = w.take<int32_t>(R);
+    c->act_bf16 = nullptr;
+    c->splitk = nullptr;
+    return w.off;
+}
+
+template <typename T>
+hipError_t upload(T *dst, const std::vector<T> &src) {
+    return hipMemcpy(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+// One Llama decoder layer over `rows` rows (rows_per_seq per sequence) whose metadata is in c->meta.
+// lw: in_norm, wqkv, wo, post_norm, wgu, wdown.  x (c->x) is updated in place.
+void decoder_layer(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, const void *const *lw,
+                   void *kc, void *vc) {
+    const koala_shape &s = c->shape;
+    const bool bf = s.dtype == KOALA_BF16;
+    const int rows = batch * rows_per_seq, H = s.hidden, F = s.ffn;
+    kg::rmsnorm(st, bf, c->x, lw[0], c->act, rows, H, s.rms_eps);
+    kg::gemm(st, bf, c->act, H, lw[1], c->qkv, 3 * H, rows, 3 * H, H, false);
+    kg::rope_append(st, bf, c->qkv, c->meta, c->qrot, kc, vc, rows, H, s.n_heads, s.head_dim, c->kv.capacity, 0);
+    kg::attention(st, bf, c->qrot, c->meta, kc, vc, c->o_part, c->ml, c->attn_out, batch, rows_per_seq, s.n_heads,
+                  s.head_dim, c->kv.capacity, attn_nsplit(c));
+    kg::gemm(st, bf, c->attn_out, H, lw[2], c->x, H, rows, H, H, true);
+    kg::rmsnorm(st, bf, c->x, lw[3], c->act, rows, H, s.rms_eps);
+    kg::gemm(st, bf, c->act, H, lw[4], c->gu, 2 * F, rows, 2 * F, H, false);
+    kg::silu_mul(st, c->gu, c->act, rows, F);
+    kg::gemm(st, bf, c->act, F, lw[5], c->x, H, rows, H, F, true);
+}
+
+size_t elt(const koala_ctx *c) { return c->shape.dtype == KOALA_BF16 ? 2 : 4; }
+
+size_t layer_stride_bytes(const koala_ctx *c) {
+    return (size_t)c->max_batch * c->shape.n_heads * c->kv.capacity * c->shape.head_dim * elt(c);
+}
+
+koala_status check_call(koala_ctx *c, int batch) {
+    if (!c) return KOALA_E_NULL;
+    c->err.clear();
+    if (!c->bound) return fail(c, KOALA_E_WORKSPACE, "context is not bound (call koala_bind first)");
+    if (batch < 1 || batch > c->max_batch) return fail(c, KOALA_E_SHAPE, "batch must be in 1..max_batch");
+    return KOALA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+koala_status koala_create(const koala_shape *shape, const koala_draft_shape *draft, const koala_tree *tree,
+                          int max_batch, koala_ctx **out) {
+    if (!shape || !draft || !tree || !out) return KOALA_E_NULL;
+    *out = nullptr;
+    if (!tree->parent || !tree->rank || (tree->depth > 0 && !tree->topk_per_depth)) return KOALA_E_NULL;
+    const koala_shape &s = *shape;
+    if (s.hidden <= 0 || s.n_heads <= 0 || s.head_dim <= 0 || s.ffn <= 0 || s.vocab <= 0 || s.n_layers <= 0 ||
+        s.hidden != s.n_heads * s.head_dim || max_batch < 1 || s.hidden % 4 || s.ffn % 4 || !(s.rms_eps >= 0.f) ||
+        !(s.rope_base > 0.f))
+        return KOALA_E_SHAPE;
+    if (s.dtype != KOALA_FP32 && s.dtype != KOALA_BF16) return KOALA_E_UNSUPPORTED;
+    if (s.head_dim != 64 && s.head_dim != 128) return KOALA_E_UNSUPPORTED;
+    if (s.dtype == KOALA_BF16 && (s.hidden % 64 || s.ffn % 64)) return KOALA_E_UNSUPPORTED;
+    if (draft->kind != KOALA_DRAFT_EAGLE && draft->kind != KOALA_DRAFT_MEDUSA) return KOALA_E_UNSUPPORTED;
+    if (draft->K < 1 || draft->max_m < 1 || draft->max_m > KOALA_MAX_M) return KOALA_E_SHAPE;
+    const int T = tree->n_nodes, D = tree->depth;
+    if (T < 1 || T > KOALA_MAX_NODES || D < 0 || D >= T + (T == 1)) return KOALA_E_SHAPE;
+    if (draft->kind == KOALA_DRAFT_MEDUSA && draft->medusa_heads < D) return KOALA_E_SHAPE;
+
+    koala_ctx *c = new koala_ctx();
+    c->shape = s;
+    c->draft = *draft;
+    c->T = T;
+    c->D = D;
+    c->max_batch = max_batch;
+    c->max_rows = max_batch * std::max(std::max(T, draft->max_m), std::max(1, draft->medusa_heads));
+    c->bound = false;
+    c->ws = nullptr;
+    c->parent.assign(tree->parent, tree->parent + T);
+    c->rank.assign(tree->rank, tree->rank + T);
+    c->topk.assign(tree->topk_per_depth, tree->topk_per_depth + D);
+    c->depth.assign(T, 0);
+    c->anc_mask.assign(T, 0);
+    bool ok = c->parent[0] == -1;
+    int maxd = 0;
+    for (int i = 0; ok && i < T; ++i) {
+        if (i > 0) {
+            const int p = c->parent[i];
+            if (p < 0 || p >= i) { ok = false; break; }
+            c->depth[i] = c->depth[p] + 1;
+            if (c->depth[i] < c->depth[i - 1]) ok = false;  // nodes ordered by depth
+            c->anc_mask[i] = c->anc_mask[p];
+            if (c->depth[i] > D) { ok = false; break; }
+            const int k = c->topk[c->depth[i] - 1];
+            if (c->rank[i] < 0 || c->rank[i] >= k) ok = false;
+            for (int j = 1; j < i; ++j)
+                if (c->parent[j] == p && c->rank[j] == c->rank[i]) ok = false;
+        }
+        c->anc_mask[i] |= 1ull << i;
+        maxd = std::max(maxd, c->depth[i]);
+    }
+    for (int d = 0; ok && d < D; ++d)
+        if (c->topk[d] < 1 || c->topk[d] > KOALA_TOPK_MAX) ok = false;
+    if (!ok || maxd != D) {
+        delete c;
+        return KOALA_E_SHAPE;
+    }
+    // nodes with children ("expanded"), per depth; non-root ones get a draft-cache slot index
+    std::vector<char> has_child(T, 0);
+    for (int i = 1; i < T; ++i) has_child[c->parent[i]] = 1;
+    c->exp_index.assign(T, -1);
+    c->draft_mask.assign(T, 0);
+    c->level_exp.assign(D + 1, {});
+    c->n_exp = 0;
+    for (int i = 0; i < T; ++i) {
+        if (!has_child[i]) continue;
+        c->level_exp[c->depth[i]].push_back(i);
+        if (i == 0) continue;
+        c->exp_index[i] = c->n_exp++;
+        c->draft_mask[i] = c->draft_mask[c->parent[i]] | (1ull << c->exp_index[i]);
+    }
+    *out = c;
+    return KOALA_OK;
+}
+
+koala_status koala_workspace_bytes(const koala_ctx *ctx, size_t *out) {
+    if (!ctx || !out) return KOALA_E_NULL;
+    *out = carve(const_cast<koala_ctx *>(ctx), nullptr);
+    if (ctx->bound) carve(const_cast<koala_ctx *>(ctx), ctx->ws);  // restore the live pointers
+    return KOALA_OK;
+}
+
+koala_status koala_bind(koala_ctx *c, const koala_weights *w, const koala_kv *kv, void *workspace, size_t bytes) {
+    if (!c) return KOALA_E_NULL;
+    c->err.clear();
+    if (!w || !kv || !workspace) return fail(c, KOALA_E_NULL, "weights, kv and workspace must not be NULL");
+    const bool eagle = c->draft.kind == KOALA_DRAFT_EAGLE;
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->layer_w || !w->draft_w || (eagle && !w->fc))
+        return fail(c, KOALA_E_NULL, "a weight pointer is NULL");
+    if (!kv->target_k || !kv->target_v || !kv->ctx_len || (eagle && (!kv->draft_k || !kv->draft_v)))
+        return fail(c, KOALA_E_NULL, "a KV-cache pointer is NULL");
+    const int n_lw = 6 * c->shape.n_layers;
+    const int n_dw = eagle ? 6 * c->draft.K : c->draft.medusa_heads * c->draft.K;
+    for (int i = 0; i < n_lw; ++i)
+        if (!w->layer_w[i]) return fail(c, KOALA_E_NULL, "a target layer weight pointer is NULL");
+    for (int i = 0; i < n_dw; ++i)
+        if (!w->draft_w[i]) return fail(c, KOALA_E_NULL, "a draft weight pointer is NULL");
+    bool al = aligned16(w->embed) && aligned16(w->lm_head) && aligned16(w->final_norm) && aligned16(w->fc) &&
+              aligned16(kv->target_k) && aligned16(kv->target_v) && aligned16(kv->draft_k) &&
+              aligned16(kv->draft_v) && (((uintptr_t)workspace) % ALIGN == 0);
+    for (int i = 0; i < n_lw; ++i) al = al && aligned16(w->layer_w[i]);
+    for (int i = 0; i < n_dw; ++i) al = al && aligned16(w->draft_w[i]);
+    if (!al) return fail(c, KOALA_E_ALIGN, "device pointers must be 16-byte aligned (workspace: 256)");
+    if (kv->capacity < c->T + 1) return fail(c, KOALA_E_CAPACITY, "KV capacity smaller than the tree");
+    const size_t need = carve(c, nullptr);
+    if (bytes < need) {
+        if (c->bound) carve(c, c->ws);
+        return fail(c, KOALA_E_WORKSPACE, "workspace too small");
+    }
+    c->w = *w;
+    c->layer_w.assign(w->layer_w, w->layer_w + n_lw);
+    c->draft_w.assign(w->draft_w, w->draft_w + n_dw);
+    c->w.layer_w = c->layer_w.data();
+    c->w.draft_w = c->draft_w.data();
+    c->kv = *kv;
+    c->ws = (char *)workspace;
+    c->ws_bytes = bytes;
+    carve(c, c->ws);
+
+    const int T = c->T, D = c->D, half = c->shape.head_dim / 2;
+    std::vector<double> inv_freq(half);
+    for (int i = 0; i < half; ++i)
+        inv_freq[i] = pow((double)c->shape.rope_base, -2.0 * (double)i / (double)c->shape.head_dim);
+    std::vector<int32_t> levels((size_t)(D + 1) * 64, -1);
+    for (int d = 0; d <= D; ++d)
+        for (size_t i = 0; i < c->level_exp[d].size(); ++i) levels[(size_t)d * 64 + i] = c->level_exp[d][i];
+    hipError_t e = hipMemcpy(c->ws, inv_freq.data(), half * sizeof(double), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = upload(c->tt.parent, c->parent);
+    if (e == hipSuccess) e = upload(c->tt.depth, c->depth);
+    if (e == hipSuccess) e = upload(c->tt.rank, c->rank);
+    if (e == hipSuccess) e = upload(c->tt.anc_mask, c->anc_mask);
+    if (e == hipSuccess) e = upload(c->tt.exp_index, c->exp_index);
+    if (e == hipSuccess) e = upload(c->tt.draft_mask, c->draft_mask);
+    if (e == hipSuccess) e = upload(c->tt.level_nodes, levels);
+    if (e != hipSuccess) {
+        c->bound = false;
+        c->err = std::string("table upload failed: ") + hipGetErrorString(e);
+        return KOALA_E_DEVICE;
+    }
+    (void)T;
+    c->bound = true;
+    return KOALA_OK;
+}
+
+koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const int32_t *tree_tokens,
+                               float *feat_out, float *logits_out, int32_t *greedy_out) {
+    koala_status st0 = check_call(c, batch);
+    if (st0 != KOALA_OK) return st0;
+    if (!tree_tokens || !feat_out || !greedy_out) return fail(c, KOALA_E_NULL, "tree_tokens, feat_out, greedy_out required");
+    if (!aligned16(tree_tokens) || !aligned16(feat_out) || !aligned16(logits_out) || !aligned16(greedy_out))
+        return fail(c, KOALA_E_ALIGN, "device pointers must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const koala_shape &s = c->shape;
+    const bool bf = s.dtype == KOALA_BF16;
+    const int T = c->T, rows = batch * T, H = s.hidden, V = s.vocab;
+    kg::setup_verify(st, c, batch);
+    kg::embed_rows(st, bf, tree_tokens, c->w.embed, c->x, rows, H);
+    const size_t ls = layer_stride_bytes(c);
+    for (int l = 0; l < s.n_layers; ++l)
+        decoder_layer(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,
+                      (char *)c->kv.target_v + ls * l);
+    kg::rmsnorm(st, bf, c->x, c->w.final_norm, feat_out, rows, H, s.rms_eps);
+    float *logits = logits_out ? logits_out : c->logits;
+    kg::gemm(st, bf, feat_out, H, c->w.lm_head, logits, V, rows, V, H, false);
+    kg::topk_rows(st, logits, V, rows, V, 1, greedy_out, nullptr);
+    KOALA_CHECK_LAUNCH(c);
+    return KOALA_OK;
+}
+
+koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const float *feat_in,
+                                const int32_t *tok_in, int m, int32_t *tree_tokens, float *tree_scores) {
+    koala_status st0 = check_call(c, batch);
+    if (st0 != KOALA_OK) return st0;
+    if (!feat_in || !tok_in || !tree_tokens) return fail(c, KOALA_E_NULL, "feat_in, tok_in, tree_tokens required");
+    if (m < 1 || m > c->draft.max_m) return fail(c, KOALA_E_SHAPE, "m must be in 1..max_m");
+    if (!aligned16(feat_in) || !aligned16(tok_in) || !aligned16(tree_tokens) || !aligned16(tree_scores))
+        return fail(c, KOALA_E_ALIGN, "device pointers must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const koala_shape &s = c->shape;
+    const bool bf = s.dtype == KOALA_BF16;
+    const int T = c->T, D = c->D, H = s.hidden, V = s.vocab, K = c->draft.K;
+    int kmax = 1;
+    for (int d = 0; d < D; ++d) kmax = std::max(kmax, c->topk[d]);
+    kg::set_root(st, tok_in, m, tree_tokens, tree_scores, batch, T);
+
+    if (c->draft.kind == KOALA_DRAFT_MEDUSA) {
+        // head j works on row block j of c->x: rows j*batch .. j*batch + batch - 1
+        for (int j = 0; j < D; ++j)
+            kg::gather_last_rows(st, feat_in, c->x + (size_t)j * batch * H, (size_t)H, batch, m, H);
+        for (int j = 0; j < D; ++j) {
+            float *xj = c->x + (size_t)j * batch * H;
+            for (int k = 0; k < K; ++k) {
+                kg::gemm(st, bf, xj, H, c->w.draft_w[j * K + k], c->gu, H, batch, H, H, false);
+                kg::resblock_update(st, xj, c->gu, batch * H);
+            }
+        }
+        if (D > 0) {
+            kg::gemm(st, bf, c->x, H, c->w.lm_head, c->logits, V, D * batch, V, H, false);
+            kg::topk_rows(st, c->logits, V, D * batch, V, kmax, c->topk_idx, c->topk_val);
+            kg::fill_medusa(st, c->topk_idx, c->topk_val, kmax, c->tt, tree_tokens, tree_scores, batch, T, D);
+        }
+        KOALA_CHECK_LAUNCH(c);
+        return KOALA_OK;
+    }
+
+    // EAGLE-style: catch-up rows first, then one pass per tree depth that has expanded nodes
+    const size_t ls = layer_stride_bytes(c);
+    int rows = batch * m;
+    kg::setup_catchup(st, c, batch, m);
+    kg::fc_input(st, bf, tok_in, c->w.embed, feat_in, c->act, rows, H);
+    kg::gemm(st, bf, c->act, 2 * H, c->w.fc, c->x, H, rows, H, 2 * H, false);
+    for (int k = 0; k < K; ++k)
+        decoder_layer(c, st, batch, m, c->w.draft_w + 6 * k, (char *)c->kv.draft_k + ls * k,
+                      (char *)c->kv.draft_v + ls * k);
+    if (D > 0) {
+        // root's predicted feature -> fhat[b][0]; its logits decide the depth-1 tokens
+        kg::gather_last_rows(st, c->x, c->fhat, (size_t)T * H, batch, m, H);
+        kg::gemm(st, bf, c->fhat, T * H, c->w.lm_head, c->logits, V, batch, V, H, false);
+        kg::topk_rows(st, c->logits, V, batch, V, c->topk[0], c->topk_idx, c->topk_val);
+        kg::fill_children(st, c->topk_idx, c->topk_val, c->topk[0], c->tt.level_nodes, 1, c->tt, 0, tree_tokens,
+                          tree_scores, batch, T);
+    }
+    for (int d = 1; d < D; ++d) {
+        const int nl = (int)c->level_exp[d].size();
+        if (nl == 0) continue;
+        const int32_t *lv = c->tt.level_nodes + (size_t)d * 64;
+        rows = batch * nl;
+        kg::setup_level(st, c, batch, d, nl);
+        kg::level_inputs(st, bf, tree_tokens, c->w.embed, c->fhat, lv, c->tt.parent, c->act, batch, nl, T, H);
+        kg::gemm(st, bf, c->act, 2 * H, c->w.fc, c->x, H, rows, H, 2 * H, false);
+        for (int k = 0; k < K; ++k)
+            decoder_layer(c, st, batch, nl, c->w.draft_w + 6 * k, (char *)c->kv.draft_k + ls * k,
+                          (char *)c->kv.draft_v + ls * k);
+        kg::store_fhat(st, c->x, c->fhat, lv, batch, nl, T, H);
+        kg::gemm(st, bf, c->x, H, c->w.lm_head, c->logits, V, rows, V, H, false);
+        kg::topk_rows(st, c->logits, V, rows, V, c->topk[d], c->topk_idx, c->topk_val);
+        kg::fill_children(st, c->topk_idx, c->topk_val, c->topk[d], lv, nl, c->tt, d, tree_tokens, tree_scores,
+                          batch, T);
+    }
+    KOALA_CHECK_LAUNCH(c);
+    return KOALA_OK;
+}
+
+koala_status koala_accept_prefix(koala_ctx *c, void *hip_stream, int batch, const int32_t *tree_tokens,
+                                 const int32_t *greedy, int32_t *accept_len, int32_t *accept_path,
+                                 int32_t *next_token, int commit) {
+    koala_status st0 = check_call(c, batch);
+    if (st0 != KOALA_OK) return st0;
+    if (!tree_tokens || !greedy || !accept_len || !accept_path || !next_token)
+        return fail(c, KOALA_E_NULL, "all accept_prefix pointers are required");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const koala_shape &s = c->shape;
+    kg::accept_scan(st, c->tt, c->T, c->D, tree_tokens, greedy, accept_len, accept_path, next_token, batch);
+    if (commit) {
+        kg::kv_commit(st, s.dtype == KOALA_BF16, c->kv.target_k, c->kv.target_v, c->kv.ctx_len, accept_len,
+                      accept_path, c->D, s.n_layers, c->max_batch, batch, s.n_heads, c->kv.capacity, s.head_dim);
+        kg::advance_ctx(st, c->kv.ctx_len, accept_len, batch);
+    }
+    KOALA_CHECK_LAUNCH(c);
+    return KOALA_OK;
+}
+
+const char *koala_last_error(const koala_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+void koala_destroy(koala_ctx *ctx) { delete ctx; }
+
+}  // extern "C"

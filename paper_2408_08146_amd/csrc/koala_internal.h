@@ -1,0 +1,121 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string>
+#include <vector>
+
+#include "koala.h"
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
+
+enum { KOALA_NSPLIT_MAX = 16, KOALA_TOPK_MAX = 16 };
+
+// Per-row metadata of one pass (verify, draft catch-up, or one draft tree level).
+// Row r of the pass belongs to sequence row_b[r]; its key/value go to cache slot
+// row_slot[r]; it has rotary position row_pos[r]; it attends to cache slots
+// [0, row_nvis[r]) and to slot row_base[r] + j for every set bit j of row_mask[r].
+struct RowMeta {
+    int32_t *row_b, *row_pos, *row_slot, *row_nvis, *row_base;
+    uint64_t *row_mask;
+    int32_t *kv_end;   // [batch]: one past the last slot any row of the sequence may see
+    float *rope_cos, *rope_sin;  // [rows][head_dim/2]
+};
+
+// Device tables describing the static tree (uploaded at bind).
+struct TreeTables {
+    int32_t *parent, *depth, *rank;   // [T]
+    uint64_t *anc_mask;               // [T] bit j: j is the node or one of its ancestors
+    int32_t *exp_index;               // [T] index among expanded non-root nodes, or -1
+    uint64_t *draft_mask;             // [T] bit e: expanded non-root ancestor-or-self with index e
+    int32_t *level_nodes;             // [D][64] expanded nodes of each depth (-1 padded)
+    int32_t *child_first, *child_count;  // unused by kernels that scan; kept for clarity
+};
+
+struct koala_ctx {
+    koala_shape shape;
+    koala_draft_shape draft;
+    int T, D, max_batch, max_rows;  // max_rows = max_batch * max(T, max_m)
+    std::vector<int32_t> parent, rank, topk, depth, exp_index;
+    std::vector<uint64_t> anc_mask, draft_mask;
+    std::vector<std::vector<int32_t>> level_exp;  // expanded nodes per depth
+    int n_exp;                                    // expanded non-root nodes
+    std::string err;
+
+    bool bound;
+    koala_weights w;
+    std::vector<const void *> layer_w, draft_w;
+    koala_kv kv;
+    char *ws;
+    size_t ws_bytes;
+
+    // workspace carve-up (device pointers)
+    TreeTables tt;
+    RowMeta meta;
+    float *x, *act, *qkv, *qrot, *attn_out, *gu, *o_part, *ml, *logits, *fhat, *topk_val;
+    int32_t *topk_idx, *tok_tmp;
+    void *act_bf16;  // packed bf16 activations for the MFMA path
+    float *splitk;   // split-K partial sums of the MFMA path
+};
+
+#define KOALA_CHECK_LAUNCH(ctx)                                              \
+    do {                                                                     \
+        hipError_t e__ = hipGetLastError();                                  \
+        if (e__ != hipSuccess) {                                             \
+            (ctx)->err = std::string("kernel launch failed: ") + hipGetErrorString(e__); \
+            return KOALA_E_DEVICE;                                           \
+        }                                                                    \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------------
+// launchers implemented in kernels_generic.hip (is_bf16 selects the storage type of weights/KV)
+// ---------------------------------------------------------------------------------------------
+namespace kg {
+
+void setup_verify(hipStream_t s, const koala_ctx *c, int batch);
+void setup_catchup(hipStream_t s, const koala_ctx *c, int batch, int m);
+void setup_level(hipStream_t s, const koala_ctx *c, int batch, int d, int n_level);
+
+void embed_rows(hipStream_t s, bool bf16, const int32_t *tok, const void *E, float *x, int rows, int H);
+void fc_input(hipStream_t s, bool bf16, const int32_t *tok, const void *E, const float *feat,
+              float *act, int rows, int H);
+void rmsnorm(hipStream_t s, bool bf16, const float *x, const void *g, float *out, int rows, int H, float eps);
+// Y[M,N] (ldy) = or += A[M,K] (lda) * W[N,K]^T
+void gemm(hipStream_t s, bool bf16, const float *A, int lda, const void *W, float *Y, int ldy,
+          int M, int N, int K, bool accumulate);
+void rope_append(hipStream_t s, bool bf16, const float *qkv, const RowMeta &meta, float *qrot,
+                 void *kcache, void *vcache, int rows, int H, int n_heads, int head_dim,
+                 int capacity, int max_batch_stride_rows);
+void attention(hipStream_t s, bool bf16, const float *qrot, const RowMeta &meta, const void *kcache,
+               const void *vcache, float *o_part, float *ml, float *attn_out, int batch,
+               int rows_per_seq, int n_heads, int head_dim, int capacity, int nsplit);
+void silu_mul(hipStream_t s, const float *gu, float *act, int rows, int F);
+void resblock_update(hipStream_t s, float *x, const float *y, int n);
+void topk_rows(hipStream_t s, const float *logits, int ld, int rows, int V, int k, int32_t *idx, float *val);
+void copy_f32(hipStream_t s, float *dst, const float *src, size_t n);
+
+// draft bookkeeping
+void gather_last_rows(hipStream_t s, const float *x, float *dst, size_t dst_stride, int batch, int m, int H);
+void store_fhat(hipStream_t s, const float *x, float *fhat, const int32_t *level_nodes, int batch,
+                int n_level, int T, int H);
+void level_inputs(hipStream_t s, bool bf16, const int32_t *tree_tokens, const void *E, const float *fhat,
+                  const int32_t *level_nodes, const int32_t *parent, float *act, int batch,
+                  int n_level, int T, int H);
+void set_root(hipStream_t s, const int32_t *tok_in, int m, int32_t *tree_tokens, float *scores, int batch, int T);
+void fill_children(hipStream_t s, const int32_t *topk_idx, const float *topk_val, int kmax,
+                   const int32_t *level_nodes, int n_level, const TreeTables &tt, int d,
+                   int32_t *tree_tokens, float *scores, int batch, int T);
+void fill_medusa(hipStream_t s, const int32_t *topk_idx, const float *topk_val, int kmax,
+                 const TreeTables &tt, int32_t *tree_tokens, float *scores, int batch, int T, int heads);
+
+void accept_scan(hipStream_t s, const TreeTables &tt, int T, int D, const int32_t *tree_tokens,
+                 const int32_t *greedy, int32_t *accept_len, int32_t *accept_path, int32_t *next_token,
+                 int batch);
+void kv_commit(hipStream_t s, bool bf16, void *kcache, void *vcache, const int32_t *ctx_len,
+               const int32_t *accept_len, const int32_t *accept_path, int D, int n_layers,
+               int max_batch, int batch, int n_heads, int capacity, int head_dim);
+void advance_ctx(hipStream_t s, int32_t *ctx_len, const int32_t *accept_len, int batch);
+
+}  // namespace kg

@@ -1,0 +1,56 @@
+"""Put named weight tensors into the device layout the library expects
+(pure data movement: concatenation, row interleaving, dtype views)."""
+from __future__ import annotations
+
+import numpy as np
+
+
+def _dev(provider, name, device, dtype):
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(provider.bits(name).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(provider.f32(name))).to(device)
+
+
+def _layer(provider, prefix, l, device, dtype):
+    import torch
+    g = lambda n: _dev(provider, f"{prefix}layers.{l}.{n}", device, dtype)
+    wqkv = torch.cat([g("wq"), g("wk"), g("wv")], dim=0).contiguous()
+    gate, up = g("wgate"), g("wup")
+    wgu = torch.stack([gate, up], dim=1).reshape(2 * gate.shape[0], gate.shape[1]).contiguous()
+    return (g("in_norm"), wqkv, g("wo"), g("post_norm"), wgu, g("wdown"))
+
+
+def pack_target_weights(provider, cfg, device="cuda"):
+    dt = cfg["dtype"]
+    return dict(embed=_dev(provider, "embed", device, dt), lm_head=_dev(provider, "lm_head", device, dt),
+                final_norm=_dev(provider, "final_norm", device, dt),
+                layers=[_layer(provider, "", l, device, dt) for l in range(cfg["n_layers"])])
+
+
+def pack_eagle_weights(provider, cfg, device="cuda"):
+    dt = cfg["dtype"]
+    layers = [_layer(provider, "draft.", k, device, dt) for k in range(cfg["K"])]
+    return dict(fc=_dev(provider, "draft.fc", device, dt), draft=[t for layer in layers for t in layer])
+
+
+def pack_medusa_weights(provider, cfg, device="cuda"):
+    dt = cfg["dtype"]
+    return dict(fc=None, draft=[_dev(provider, f"medusa.{j}.{k}", device, dt)
+                                for j in range(cfg["medusa_heads"]) for k in range(cfg["K"])])
+
+
+def alloc_kv(cfg, max_batch, capacity, device="cuda", draft_layers=0):
+    """Zeroed KV caches [layer][batch][n_heads][capacity][head_dim] and ctx_len int32[max_batch]."""
+    import torch
+    td = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    shp = (cfg["n_layers"], max_batch, cfg["n_heads"], capacity, cfg["head_dim"])
+    kv = dict(target_k=torch.zeros(shp, dtype=td, device=device),
+              target_v=torch.zeros(shp, dtype=td, device=device),
+              draft_k=None, draft_v=None, capacity=capacity,
+              ctx_len=torch.zeros(max_batch, dtype=torch.int32, device=device))
+    if draft_layers:
+        dshp = (draft_layers,) + shp[1:]
+        kv["draft_k"] = torch.zeros(dshp, dtype=td, device=device)
+        kv["draft_v"] = torch.zeros(dshp, dtype=td, device=device)
+    return kv
