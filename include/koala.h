@@ -24,7 +24,18 @@
  *    returned as negative koala_status values; koala_last_error() gives text.
  *  - Limits: at most 64 tree nodes per sequence, at most 64 catch-up rows (m),
  *    head_dim 64 or 128, hidden = n_heads * head_dim; for bfloat16 hidden and
- *    ffn must be multiples of 64.
+ *    ffn must be multiples of 128.
+ *
+ * Matrix storage.  For KOALA_FP32 every matrix [N, K] is plain row-major.  For
+ * KOALA_BF16 every Linear weight (wqkv, wo, wgu, wdown, lm_head, fc, Medusa
+ * blocks) is stored "fragment-major", the order in which a gfx950 wave feeds a
+ * 16x16x32 bf16 MFMA, so that the weight stream is read from HBM as contiguous
+ * 1 KiB pieces.  With Npad = N rounded up to a multiple of 64 (extra rows zero)
+ * and K a multiple of 64, element (n, k) lives at bf16 index
+ *     (((((n/64) * (K/64) + k/64) * 4 + (n%64)/16) * 2 + (k%64)/32) * 64
+ *        + (n%16) + 16*((k%32)/8)) * 8 + k%8,
+ * i.e. tiles of 64 rows x 64 k, each tile being 8 fragments of 64 lanes x 8
+ * values.  The embedding table and the RMSNorm gains stay row-major / linear.
  */
 #ifndef KOALA_H
 #define KOALA_H

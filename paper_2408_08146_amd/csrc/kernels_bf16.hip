@@ -1,0 +1,373 @@
+// bf16 weight-streaming path for gfx950.
+//
+// Every projection of the draft-then-verify iteration has only a handful of activation rows
+// (the tree nodes) against a large weight matrix, so it is bound by how fast the weights
+// stream out of HBM.  The kernels here are built around that:
+//   * weights are stored fragment-major (see koala.h): one wave load instruction reads 1 KiB of
+//     contiguous memory and lands exactly in the A operand of a 16x16x32 bf16 MFMA;
+//   * activations are split into bf16 hi + lo parts (x = hi + lo to ~16 mantissa bits), also
+//     in fragment order, so results stay at fp32-class accuracy while using the bf16 MFMA;
+//   * K is split over workgroups; partial sums go to a scratch buffer that the consumer
+//     kernel adds up in a fixed order (deterministic, no float atomics).
+#include "koala_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+__device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t f2bf(float v) {  // round to nearest even
+    uint32_t u = __float_as_uint(v);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Packed GEMM.  Wp: [Npad/64][K/64] tiles of 64 rows x 64 k, each tile = 8 fragments
+// (t = row/16, s = k/32) of 64 lanes x 16 B; lane = (row%16) + 16*((k%32)/8).
+// Xf: [K/32][MTT][hi,lo][64 lanes] x 16 B; lane = (m%16) + 16*((k%32)/8); a launch handles the MT
+//     activation tiles mt0 .. mt0+MT-1 of the MTT present.
+// P:  [S][MTT*16][Npad] fp32 partial sums; split sp covers 128-k chunks [sp*nch/S, (sp+1)*nch/S).
+// Workgroup = 4 waves; wave w owns row block wb*4 + w (64 rows); the X chunk is shared in LDS.
+// ---------------------------------------------------------------------------------------------
+template <int MT>
+__global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
+                                                     float *__restrict__ P, int Npad, int K, int S, int nwb,
+                                                     int MTT, int mt0) {
+    extern __shared__ u32x4 xs[];            // [2][XCH]
+    constexpr int XCH = 4 * MT * 2 * 64;     // 16-byte units of X per 128-k chunk
+    constexpr int XPT = XCH / 256;           // per thread
+    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
+    const int wb = blockIdx.x % nwb, sp = blockIdx.x / nwb;
+    const int nch = K / 128;
+    const int c_begin = (int)((long long)sp * nch / S), c_end = (int)((long long)(sp + 1) * nch / S);
+    const int nchunks = c_end - c_begin;
+    const int rb = wb * 4 + wave;
+    const bool active = rb < Npad / 64;
+    const u32x4 *wsrc = Wp + ((size_t)(active ? rb : 0) * (K / 64) + (size_t)c_begin * 2) * 512 + l;
+    // 16-byte unit u of chunk c lives at xsrc + (c*4 + u / (MT*128)) * MTT*128 + u % (MT*128)
+    const u32x4 *xsrc = Xf + (size_t)c_begin * 4 * MTT * 128 + (size_t)mt0 * 128;
+    auto xaddr = [&](int c, int u) { return xsrc + ((size_t)c * 4 + u / (MT * 128)) * (MTT * 128) + u % (MT * 128); };
+    f32x4 acc[4][MT];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[t][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    u32x4 wr[2][8];
+    u32x4 xr[XPT];
+    const int nb = nchunks * 2;
+    auto wload = [&](int b, int slot) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) wr[slot][j] = __builtin_nontemporal_load(wsrc + (size_t)b * 512 + j * 64);
+    };
+    if (nchunks > 0) {
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) xs[threadIdx.x + 256 * i] = *xaddr(0, threadIdx.x + 256 * i);
+        if (active) {
+            wload(0, 0);
+            wload(1, 1);
+        }
+    }
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        const bool more = c + 1 < nchunks;
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < XPT; ++i) xr[i] = *xaddr(c + 1, threadIdx.x + 256 * i);
+        }
+        const u32x4 *xc = xs + (c & 1) * XCH;
+        if (active) {
+#pragma unroll
+            for (int bb = 0; bb < 2; ++bb) {
+                bf16x8 a[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) a[j] = __builtin_bit_cast(bf16x8, wr[bb][j]);
+                if (2 * c + bb + 2 < nb) wload(2 * c + bb + 2, bb);
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const u32x4 *xk = xc + (bb * 2 + s) * (MT * 2 * 64);
+                    bf16x8 xh[MT], xl[MT];
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        xh[m] = __builtin_bit_cast(bf16x8, xk[(m * 2 + 0) * 64 + l]);
+                        xl[m] = __builtin_bit_cast(bf16x8, xk[(m * 2 + 1) * 64 + l]);
+                    }
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int m = 0; m < MT; ++m)
+                            acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t * 2 + s], xh[m], acc[t][m], 0, 0, 0);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int m = 0; m < MT; ++m)
+                            acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t * 2 + s], xl[m], acc[t][m], 0, 0, 0);
+                }
+            }
+        }
+        if (more) {
+            u32x4 *xn = xs + ((c + 1) & 1) * XCH;
+#pragma unroll
+            for (int i = 0; i < XPT; ++i) xn[threadIdx.x + 256 * i] = xr[i];
+        }
+        __syncthreads();
+    }
+    if (active) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const int row = (mt0 + m) * 16 + li, n = rb * 64 + 16 * t + 4 * lg;
+                *(f32x4 *)(P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = acc[t][m];
+            }
+    }
+}
+
+// sum of the split-K partials of element (row, col)
+__device__ __forceinline__ float psum(const float *P, int S, int Mp, int ld, int row, int col) {
+    float v = 0.f;
+    for (int s = 0; s < S; ++s) v += P[((size_t)s * Mp + row) * ld + col];
+    return v;
+}
+
+// store 8 consecutive k of row m (k0 % 8 == 0) as hi/lo fragments
+__device__ __forceinline__ void store_frag8(u32x4 *Xf, int MT, int m, int k0, const float *y) {
+    uint32_t hi[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        hi[e] = f2bf(y[e]);
+        lo[e] = f2bf(y[e] - bf2f(hi[e]));
+    }
+    const int ks = k0 >> 5, lane = (m & 15) + 16 * ((k0 & 31) >> 3), mt = m >> 4;
+    u32x4 h, w;
+    h.x = hi[0] | (hi[1] << 16); h.y = hi[2] | (hi[3] << 16); h.z = hi[4] | (hi[5] << 16); h.w = hi[6] | (hi[7] << 16);
+    w.x = lo[0] | (lo[1] << 16); w.y = lo[2] | (lo[3] << 16); w.z = lo[4] | (lo[5] << 16); w.w = lo[6] | (lo[7] << 16);
+    u32x4 *dst = Xf + ((size_t)(ks * MT + mt) * 2) * 64 + lane;
+    dst[0] = h;
+    dst[64] = w;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row preparation: (optional) add split-K partials into the fp32 rows, (optional) RMSNorm,
+// write fp32 and/or hi/lo fragments.  One block per (padded) row; rows >= M write zero fragments.
+// mode_in: 0 v = x; 1 v = x + sum(P), x <- v; 2 v = sum(P), x <- v.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_prep_rows(float *x, int ldx, const float *P, int S, int Mp_in, int ldp,
+                                                   int mode_in, const bf16_t *gain, float eps, float *out32,
+                                                   int ldo, u32x4 *Xf, int MT, int M, int K) {
+    __shared__ float red[4];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    if (m >= M) {
+        if (Xf) {
+            const float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int g = tid; g < K / 8; g += 256) store_frag8(Xf, MT, m, g * 8, z);
+        }
+        return;
+    }
+    float *xr = x + (size_t)m * ldx;
+    float ss = 0.f;
+    for (int j = tid; j < K; j += 256) {
+        float v;
+        if (mode_in == 0) v = xr[j];
+        else {
+            v = psum(P, S, Mp_in, ldp, m, j);
+            if (mode_in == 1) v += xr[j];
+            xr[j] = v;
+        }
+        ss += v * v;
+    }
+    float inv = 1.f;
+    if (gain) {
+        for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+        if ((tid & 63) == 0) red[tid >> 6] = ss;
+        __syncthreads();
+        inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)K + eps);
+    }
+    __syncthreads();   // x row fully written before it is re-read below
+    for (int g = tid; g < K / 8; g += 256) {
+        float y[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int j = g * 8 + e;
+            y[e] = gain ? xr[j] * inv * bf2f(gain[j]) : xr[j];
+        }
+        if (out32) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) out32[(size_t)m * ldo + g * 8 + e] = y[e];
+        }
+        if (Xf) store_frag8(Xf, MT, m, g * 8, y);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// RoPE + KV append from the QKV partials.  grid (rows, n_heads), block head_dim/2.
+// ---------------------------------------------------------------------------------------------
+__global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowMeta meta, float *qrot, bf16_t *kc,
+                                bf16_t *vc, int H, int n_heads, int DH, int cap) {
+    const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x, half = DH / 2;
+    const int b = meta.row_b[r], slot = meta.row_slot[r];
+    const float c = meta.rope_cos[(size_t)r * half + i], s = meta.rope_sin[(size_t)r * half + i];
+    const float q0 = psum(P, S, Mp, ldp, r, h * DH + i), q1 = psum(P, S, Mp, ldp, r, h * DH + half + i);
+    const float k0 = psum(P, S, Mp, ldp, r, H + h * DH + i), k1 = psum(P, S, Mp, ldp, r, H + h * DH + half + i);
+    const float v0 = psum(P, S, Mp, ldp, r, 2 * H + h * DH + i), v1 = psum(P, S, Mp, ldp, r, 2 * H + h * DH + half + i);
+    qrot[(size_t)r * H + h * DH + i] = q0 * c - q1 * s;
+    qrot[(size_t)r * H + h * DH + half + i] = q1 * c + q0 * s;
+    const size_t o = (((size_t)b * n_heads + h) * cap + slot) * DH;
+    kc[o + i] = (bf16_t)f2bf(k0 * c - k1 * s);
+    kc[o + half + i] = (bf16_t)f2bf(k1 * c + k0 * s);
+    vc[o + i] = (bf16_t)f2bf(v0);
+    vc[o + half + i] = (bf16_t)f2bf(v1);
+}
+
+// merge the attention splits and write the result as hi/lo fragments (K = H). grid: padded rows.
+__global__ __launch_bounds__(256) void k_attn_combine_frag(const float *o_part, const float *ml, u32x4 *Xf, int MT,
+                                                           int M, int n_heads, int nsplit, int DH, int H) {
+    const int r = blockIdx.x;
+    for (int g = threadIdx.x; g < H / 8; g += 256) {
+        float y[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (r < M) {
+            const int h = (g * 8) / DH, d0 = (g * 8) % DH;
+            const float *p = ml + ((size_t)r * n_heads + h) * nsplit * 2;
+            float Mx = -INFINITY;
+            for (int s = 0; s < nsplit; ++s) Mx = fmaxf(Mx, p[2 * s]);
+            float den = 0.f;
+            for (int s = 0; s < nsplit; ++s) {
+                const float ms = p[2 * s];
+                if (ms == -INFINITY) continue;
+                const float w = __expf(ms - Mx);
+                den += w * p[2 * s + 1];
+                const float *o = o_part + (((size_t)r * n_heads + h) * nsplit + s) * DH + d0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) y[e] += w * o[e];
+            }
+            const float inv = 1.0f / den;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] *= inv;
+        }
+        store_frag8(Xf, MT, r, g * 8, y);
+    }
+}
+
+// SiLU(gate) * up from the gate/up partials (rows interleaved: col 2f = gate, 2f+1 = up) -> fragments (K = F)
+__global__ __launch_bounds__(256) void k_silu_frag(const float *P, int S, int Mp, int ldp, u32x4 *Xf, int MT, int M,
+                                                   int F) {
+    const int r = blockIdx.x;
+    for (int g = threadIdx.x; g < F / 8; g += 256) {
+        float y[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (r < M) {
+            float gu[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) gu[e] = 0.f;
+            for (int s = 0; s < S; ++s) {
+                const f32x4 *src = (const f32x4 *)(P + ((size_t)s * Mp + r) * ldp + (size_t)g * 16);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 v = src[q];
+                    gu[4 * q] += v.x; gu[4 * q + 1] += v.y; gu[4 * q + 2] += v.z; gu[4 * q + 3] += v.w;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float a = gu[2 * e];
+                y[e] = a / (1.0f + __expf(-a)) * gu[2 * e + 1];
+            }
+        }
+        store_frag8(Xf, MT, r, g * 8, y);
+    }
+}
+
+// Medusa residual block: x += SiLU(sum of partials)
+__global__ void k_resblock_p(float *x, int ldx, const float *P, int S, int Mp, int ldp, int M, int H) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)M * H) return;
+    const int r = (int)(i / H), j = (int)(i % H);
+    const float v = psum(P, S, Mp, ldp, r, j);
+    x[(size_t)r * ldx + j] += v / (1.0f + __expf(-v));
+}
+
+// logits[r][v] = sum of partials for v < V
+__global__ void k_reduce_out(const float *P, int S, int Mp, int ldp, float *out, int ldo, int M, int N) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)M * N) return;
+    const int r = (int)(i / N), j = (int)(i % N);
+    out[(size_t)r * ldo + j] = psum(P, S, Mp, ldp, r, j);
+}
+
+inline int cdiv(size_t a, size_t b) { return (int)((a + b - 1) / b); }
+
+}  // namespace
+
+// =====================================================================================================
+namespace kb {
+
+int gemm_splits(int Npad, int K) {
+    const int nwb = (Npad / 64 + 3) / 4, nch = K / 128;
+    int target = 384;
+    if (const char *e = getenv("KOALA_GEMM_WGS")) target = atoi(e) > 0 ? atoi(e) : target;
+    int S = (target + nwb / 2) / nwb;
+    S = S < 1 ? 1 : S;
+    S = S > 16 ? 16 : S;
+    S = S > nch ? nch : S;
+    return S;
+}
+
+static bool g_attr_done[3] = {false, false, false};
+
+void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S) {
+    const int nwb = (Npad / 64 + 3) / 4;
+    const dim3 grid(nwb * S);
+#define KOALA_GEMM(MTV, IDX)                                                                                     \
+    {                                                                                                            \
+        const size_t sm = (size_t)2 * 4 * MTV * 2 * 64 * 16;                                                     \
+        if (!g_attr_done[IDX]) {                                                                                 \
+            (void)hipFuncSetAttribute((const void *)k_gemm_packed<MTV>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                      (int)sm);                                                                  \
+            g_attr_done[IDX] = true;                                                                             \
+        }                                                                                                        \
+        k_gemm_packed<MTV><<<grid, 256, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, S, nwb, MTT, \
+                                                  mt0);                                                          \
+    }
+    // MTT is 1, 2 or a multiple of 4: groups of at most four activation tiles per launch
+    for (int mt0 = 0; mt0 < MTT; mt0 += 4) {
+        const int g = MTT - mt0 >= 4 ? 4 : MTT - mt0;
+        if (g == 1) KOALA_GEMM(1, 0)
+        else if (g == 2) KOALA_GEMM(2, 1)
+        else KOALA_GEMM(4, 2)
+    }
+#undef KOALA_GEMM
+}
+
+void prep_rows(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp_in, int ldp, int mode_in,
+               const void *gain, float eps, float *out32, int ldo, void *Xf, int MT, int M, int K) {
+    const int blocks = Xf ? MT * 16 : M;
+    k_prep_rows<<<blocks, 256, 0, st>>>(x, ldx, P, S, Mp_in, ldp, mode_in, (const bf16_t *)gain, eps, out32, ldo,
+                                        (u32x4 *)Xf, MT, M, K);
+}
+
+void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const RowMeta &meta, float *qrot,
+                 void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap) {
+    k_rope_append_p<<<dim3(rows, n_heads), head_dim / 2, 0, st>>>(P, S, Mp, ldp, meta, qrot, (bf16_t *)kc,
+                                                                  (bf16_t *)vc, H, n_heads, head_dim, cap);
+}
+
+void attn_combine_frag(hipStream_t st, const float *o_part, const float *ml, void *Xf, int MT, int M, int n_heads,
+                       int nsplit, int head_dim) {
+    k_attn_combine_frag<<<MT * 16, 256, 0, st>>>(o_part, ml, (u32x4 *)Xf, MT, M, n_heads, nsplit, head_dim,
+                                                 n_heads * head_dim);
+}
+
+void silu_frag(hipStream_t st, const float *P, int S, int Mp, int ldp, void *Xf, int MT, int M, int F) {
+    k_silu_frag<<<MT * 16, 256, 0, st>>>(P, S, Mp, ldp, (u32x4 *)Xf, MT, M, F);
+}
+
+void resblock_p(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int M, int H) {
+    k_resblock_p<<<cdiv((size_t)M * H, 256), 256, 0, st>>>(x, ldx, P, S, Mp, ldp, M, H);
+}
+
+void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *out, int ldo, int M, int N) {
+    k_reduce_out<<<cdiv((size_t)M * N, 256), 256, 0, st>>>(P, S, Mp, ldp, out, ldo, M, N);
+}
+
+}  // namespace kb

@@ -498,8 +498,9 @@ void attention(hipStream_t s, bool bf16, const float *qrot, const RowMeta &meta,
         if (bf16) KOALA_ATTN(bf16_t, 64); else KOALA_ATTN(float, 64);
     }
 #undef KOALA_ATTN
-    k_attn_combine<<<dim3(batch * rows_per_seq, n_heads), head_dim, 0, s>>>(o_part, ml, attn_out, n_heads, nsplit,
-                                                                           head_dim, H);
+    if (attn_out)
+        k_attn_combine<<<dim3(batch * rows_per_seq, n_heads), head_dim, 0, s>>>(o_part, ml, attn_out, n_heads,
+                                                                               nsplit, head_dim, H);
 }
 
 void silu_mul(hipStream_t s, const float *gu, float *act, int rows, int F) {

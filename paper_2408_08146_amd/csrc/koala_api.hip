@@ -75,8 +75,20 @@ size_t carve(koala_ctx *c, char *base) {
     c->topk_val = w.take<float>((size_t)R * KOALA_TOPK_MAX);
     c->topk_idx = w.take<int32_t>((size_t)R * KOALA_TOPK_MAX);
     c->tok_tmp = w.take<int32_t>(R);
-    c->act_bf16 = nullptr;
-    c->splitk = nullptr;
+    c->xf = nullptr;
+    c->part = nullptr;
+    c->xf_bytes = c->part_bytes = 0;
+    if (s.dtype == KOALA_BF16) {
+        const int MTmax = kb::mt_of(R);
+        c->xf_bytes = kb::xf_bytes(std::max(2 * H, F), MTmax);
+        const int shapes[6][2] = {{3 * H, H}, {H, H}, {2 * F, H}, {H, F}, {kb::pad64(V), H}, {H, 2 * H}};
+        size_t worst = 0;
+        for (auto &sh : shapes)
+            worst = std::max(worst, (size_t)kb::gemm_splits(kb::pad64(sh[0]), sh[1]) * kb::pad64(sh[0]));
+        c->part_bytes = worst * MTmax * 16 * sizeof(float);
+        c->xf = w.take<char>(c->xf_bytes);
+        c->part = w.take<float>(c->part_bytes / sizeof(float));
+    }
     return w.off;
 }
 
@@ -102,6 +114,49 @@ void decoder_layer(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, co
     kg::gemm(st, bf, c->act, H, lw[4], c->gu, 2 * F, rows, 2 * F, H, false);
     kg::silu_mul(st, c->gu, c->act, rows, F);
     kg::gemm(st, bf, c->act, F, lw[5], c->x, H, rows, H, F, true);
+}
+
+// Split-K GEMM on the fragment buffer: partial sums of X * W^T into c->part; returns the split count.
+int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) {
+    const int Npad = kb::pad64(N), S = kb::gemm_splits(Npad, K);
+    kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S);
+    return S;
+}
+
+// bf16 decoder layer.  On entry c->pend_* may describe partial sums (of the previous down
+// projection or of the EAGLE fc) still to be folded into x; on exit the down projection's are pending.
+void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, const void *const *lw,
+                        void *kc, void *vc) {
+    const koala_shape &s = c->shape;
+    const int rows = batch * rows_per_seq, H = s.hidden, F = s.ffn, MT = kb::mt_of(rows), Mp = MT * 16;
+    const int ns = attn_nsplit(c);
+    kb::prep_rows(st, c->x, H, c->part, c->pend_S, Mp, c->pend_ld, c->pend_S ? c->pend_mode : 0, lw[0], s.rms_eps,
+                  nullptr, 0, c->xf, MT, rows, H);
+    int S = bf_gemm(c, st, lw[1], 3 * H, H, MT);
+    kb::rope_append(st, c->part, S, Mp, 3 * H, c->meta, c->qrot, kc, vc, rows, H, s.n_heads, s.head_dim,
+                    c->kv.capacity);
+    kg::attention(st, true, c->qrot, c->meta, kc, vc, c->o_part, c->ml, nullptr, batch, rows_per_seq, s.n_heads,
+                  s.head_dim, c->kv.capacity, ns);
+    kb::attn_combine_frag(st, c->o_part, c->ml, c->xf, MT, rows, s.n_heads, ns, s.head_dim);
+    S = bf_gemm(c, st, lw[2], H, H, MT);
+    kb::prep_rows(st, c->x, H, c->part, S, Mp, H, 1, lw[3], s.rms_eps, nullptr, 0, c->xf, MT, rows, H);
+    S = bf_gemm(c, st, lw[4], 2 * F, H, MT);
+    kb::silu_frag(st, c->part, S, Mp, 2 * F, c->xf, MT, rows, F);
+    S = bf_gemm(c, st, lw[5], H, F, MT);
+    c->pend_S = S;
+    c->pend_ld = H;
+    c->pend_mode = 1;
+}
+
+// logits of `rows` rows whose fp32 inputs are at a[r*lda ..]: fragments -> LM head -> reduce -> top-k
+void bf_lm_head_topk(koala_ctx *c, hipStream_t st, float *a, int lda, int rows, float *logits, int k,
+                     int32_t *idx, float *val) {
+    const koala_shape &s = c->shape;
+    const int MT = kb::mt_of(rows), Vp = kb::pad64(s.vocab);
+    kb::prep_rows(st, a, lda, nullptr, 0, 0, 0, 0, nullptr, 0.f, nullptr, 0, c->xf, MT, rows, s.hidden);
+    const int S = bf_gemm(c, st, c->w.lm_head, s.vocab, s.hidden, MT);
+    kb::reduce_out(st, c->part, S, MT * 16, Vp, logits, s.vocab, rows, s.vocab);
+    kg::topk_rows(st, logits, s.vocab, rows, s.vocab, k, idx, val);
 }
 
 size_t elt(const koala_ctx *c) { return c->shape.dtype == KOALA_BF16 ? 2 : 4; }
@@ -134,7 +189,7 @@ koala_status koala_create(const koala_shape *shape, const koala_draft_shape *dra
         return KOALA_E_SHAPE;
     if (s.dtype != KOALA_FP32 && s.dtype != KOALA_BF16) return KOALA_E_UNSUPPORTED;
     if (s.head_dim != 64 && s.head_dim != 128) return KOALA_E_UNSUPPORTED;
-    if (s.dtype == KOALA_BF16 && (s.hidden % 64 || s.ffn % 64)) return KOALA_E_UNSUPPORTED;
+    if (s.dtype == KOALA_BF16 && (s.hidden % 128 || s.ffn % 128)) return KOALA_E_UNSUPPORTED;
     if (draft->kind != KOALA_DRAFT_EAGLE && draft->kind != KOALA_DRAFT_MEDUSA) return KOALA_E_UNSUPPORTED;
     if (draft->K < 1 || draft->max_m < 1 || draft->max_m > KOALA_MAX_M) return KOALA_E_SHAPE;
     const int T = tree->n_nodes, D = tree->depth;
@@ -280,11 +335,27 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
     kg::setup_verify(st, c, batch);
     kg::embed_rows(st, bf, tree_tokens, c->w.embed, c->x, rows, H);
     const size_t ls = layer_stride_bytes(c);
+    float *logits = logits_out ? logits_out : c->logits;
+    if (bf) {
+        const int MT = kb::mt_of(rows), Mp = MT * 16;
+        c->pend_S = 0;
+        for (int l = 0; l < s.n_layers; ++l)
+            decoder_layer_bf16(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,
+                               (char *)c->kv.target_v + ls * l);
+        // last down projection folded in, final RMSNorm -> features (fp32) and fragments for the LM head
+        kb::prep_rows(st, c->x, H, c->part, c->pend_S, Mp, c->pend_ld, 1, c->w.final_norm, s.rms_eps, feat_out, H,
+                      c->xf, MT, rows, H);
+        c->pend_S = 0;
+        const int S = bf_gemm(c, st, c->w.lm_head, V, H, MT);
+        kb::reduce_out(st, c->part, S, Mp, kb::pad64(V), logits, V, rows, V);
+        kg::topk_rows(st, logits, V, rows, V, 1, greedy_out, nullptr);
+        KOALA_CHECK_LAUNCH(c);
+        return KOALA_OK;
+    }
     for (int l = 0; l < s.n_layers; ++l)
         decoder_layer(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,
                       (char *)c->kv.target_v + ls * l);
     kg::rmsnorm(st, bf, c->x, c->w.final_norm, feat_out, rows, H, s.rms_eps);
-    float *logits = logits_out ? logits_out : c->logits;
     kg::gemm(st, bf, feat_out, H, c->w.lm_head, logits, V, rows, V, H, false);
     kg::topk_rows(st, logits, V, rows, V, 1, greedy_out, nullptr);
     KOALA_CHECK_LAUNCH(c);
@@ -314,13 +385,24 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
         for (int j = 0; j < D; ++j) {
             float *xj = c->x + (size_t)j * batch * H;
             for (int k = 0; k < K; ++k) {
-                kg::gemm(st, bf, xj, H, c->w.draft_w[j * K + k], c->gu, H, batch, H, H, false);
-                kg::resblock_update(st, xj, c->gu, batch * H);
+                if (bf) {
+                    const int MT = kb::mt_of(batch);
+                    kb::prep_rows(st, xj, H, nullptr, 0, 0, 0, 0, nullptr, 0.f, nullptr, 0, c->xf, MT, batch, H);
+                    const int S = bf_gemm(c, st, c->w.draft_w[j * K + k], H, H, MT);
+                    kb::resblock_p(st, xj, H, c->part, S, MT * 16, H, batch, H);
+                } else {
+                    kg::gemm(st, bf, xj, H, c->w.draft_w[j * K + k], c->gu, H, batch, H, H, false);
+                    kg::resblock_update(st, xj, c->gu, batch * H);
+                }
             }
         }
         if (D > 0) {
-            kg::gemm(st, bf, c->x, H, c->w.lm_head, c->logits, V, D * batch, V, H, false);
-            kg::topk_rows(st, c->logits, V, D * batch, V, kmax, c->topk_idx, c->topk_val);
+            if (bf) {
+                bf_lm_head_topk(c, st, c->x, H, D * batch, c->logits, kmax, c->topk_idx, c->topk_val);
+            } else {
+                kg::gemm(st, bf, c->x, H, c->w.lm_head, c->logits, V, D * batch, V, H, false);
+                kg::topk_rows(st, c->logits, V, D * batch, V, kmax, c->topk_idx, c->topk_val);
+            }
             kg::fill_medusa(st, c->topk_idx, c->topk_val, kmax, c->tt, tree_tokens, tree_scores, batch, T, D);
         }
         KOALA_CHECK_LAUNCH(c);
@@ -329,18 +411,44 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
 
     // EAGLE-style: catch-up rows first, then one pass per tree depth that has expanded nodes
     const size_t ls = layer_stride_bytes(c);
-    int rows = batch * m;
+    // fc over [embedding ; feature] then the K draft layers; leaves the predicted features in c->x
+    auto run_head = [&](int rows_per_seq) {
+        const int rows = batch * rows_per_seq;
+        if (bf) {
+            const int MT = kb::mt_of(rows), Mp = MT * 16;
+            kb::prep_rows(st, c->act, 2 * H, nullptr, 0, 0, 0, 0, nullptr, 0.f, nullptr, 0, c->xf, MT, rows, 2 * H);
+            c->pend_S = bf_gemm(c, st, c->w.fc, H, 2 * H, MT);
+            c->pend_ld = H;
+            c->pend_mode = 2;
+            for (int k = 0; k < K; ++k)
+                decoder_layer_bf16(c, st, batch, rows_per_seq, c->w.draft_w + 6 * k, (char *)c->kv.draft_k + ls * k,
+                                   (char *)c->kv.draft_v + ls * k);
+            kb::prep_rows(st, c->x, H, c->part, c->pend_S, Mp, c->pend_ld, c->pend_mode, nullptr, 0.f, nullptr, 0,
+                          nullptr, MT, rows, H);
+            c->pend_S = 0;
+        } else {
+            kg::gemm(st, bf, c->act, 2 * H, c->w.fc, c->x, H, rows, H, 2 * H, false);
+            for (int k = 0; k < K; ++k)
+                decoder_layer(c, st, batch, rows_per_seq, c->w.draft_w + 6 * k, (char *)c->kv.draft_k + ls * k,
+                              (char *)c->kv.draft_v + ls * k);
+        }
+    };
+    // LM head + top-k on `rows` fp32 rows at a (row stride lda)
+    auto head_topk = [&](float *a, int lda, int rows, int k) {
+        if (bf) {
+            bf_lm_head_topk(c, st, a, lda, rows, c->logits, k, c->topk_idx, c->topk_val);
+        } else {
+            kg::gemm(st, bf, a, lda, c->w.lm_head, c->logits, V, rows, V, H, false);
+            kg::topk_rows(st, c->logits, V, rows, V, k, c->topk_idx, c->topk_val);
+        }
+    };
     kg::setup_catchup(st, c, batch, m);
-    kg::fc_input(st, bf, tok_in, c->w.embed, feat_in, c->act, rows, H);
-    kg::gemm(st, bf, c->act, 2 * H, c->w.fc, c->x, H, rows, H, 2 * H, false);
-    for (int k = 0; k < K; ++k)
-        decoder_layer(c, st, batch, m, c->w.draft_w + 6 * k, (char *)c->kv.draft_k + ls * k,
-                      (char *)c->kv.draft_v + ls * k);
+    kg::fc_input(st, bf, tok_in, c->w.embed, feat_in, c->act, batch * m, H);
+    run_head(m);
     if (D > 0) {
         // root's predicted feature -> fhat[b][0]; its logits decide the depth-1 tokens
         kg::gather_last_rows(st, c->x, c->fhat, (size_t)T * H, batch, m, H);
-        kg::gemm(st, bf, c->fhat, T * H, c->w.lm_head, c->logits, V, batch, V, H, false);
-        kg::topk_rows(st, c->logits, V, batch, V, c->topk[0], c->topk_idx, c->topk_val);
+        head_topk(c->fhat, T * H, batch, c->topk[0]);
         kg::fill_children(st, c->topk_idx, c->topk_val, c->topk[0], c->tt.level_nodes, 1, c->tt, 0, tree_tokens,
                           tree_scores, batch, T);
     }
@@ -348,16 +456,11 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
         const int nl = (int)c->level_exp[d].size();
         if (nl == 0) continue;
         const int32_t *lv = c->tt.level_nodes + (size_t)d * 64;
-        rows = batch * nl;
         kg::setup_level(st, c, batch, d, nl);
         kg::level_inputs(st, bf, tree_tokens, c->w.embed, c->fhat, lv, c->tt.parent, c->act, batch, nl, T, H);
-        kg::gemm(st, bf, c->act, 2 * H, c->w.fc, c->x, H, rows, H, 2 * H, false);
-        for (int k = 0; k < K; ++k)
-            decoder_layer(c, st, batch, nl, c->w.draft_w + 6 * k, (char *)c->kv.draft_k + ls * k,
-                          (char *)c->kv.draft_v + ls * k);
+        run_head(nl);
         kg::store_fhat(st, c->x, c->fhat, lv, batch, nl, T, H);
-        kg::gemm(st, bf, c->x, H, c->w.lm_head, c->logits, V, rows, V, H, false);
-        kg::topk_rows(st, c->logits, V, rows, V, c->topk[d], c->topk_idx, c->topk_val);
+        head_topk(c->x, H, batch * nl, c->topk[d]);
         kg::fill_children(st, c->topk_idx, c->topk_val, c->topk[d], lv, nl, c->tt, d, tree_tokens, tree_scores,
                           batch, T);
     }

@@ -56,8 +56,11 @@ struct koala_ctx {
     RowMeta meta;
     float *x, *act, *qkv, *qrot, *attn_out, *gu, *o_part, *ml, *logits, *fhat, *topk_val;
     int32_t *topk_idx, *tok_tmp;
-    void *act_bf16;  // packed bf16 activations for the MFMA path
-    float *splitk;   // split-K partial sums of the MFMA path
+    // bf16 path: activations as hi/lo bf16 MFMA fragments and the split-K partial sums
+    void *xf;
+    float *part;
+    size_t xf_bytes, part_bytes;
+    int pend_S, pend_ld, pend_mode;  // partial sums waiting to be folded into x (0 = none)
 };
 
 #define KOALA_CHECK_LAUNCH(ctx)                                              \
@@ -90,7 +93,7 @@ void rope_append(hipStream_t s, bool bf16, const float *qkv, const RowMeta &meta
                  int capacity, int max_batch_stride_rows);
 void attention(hipStream_t s, bool bf16, const float *qrot, const RowMeta &meta, const void *kcache,
                const void *vcache, float *o_part, float *ml, float *attn_out, int batch,
-               int rows_per_seq, int n_heads, int head_dim, int capacity, int nsplit);
+               int rows_per_seq, int n_heads, int head_dim, int capacity, int nsplit);  // attn_out NULL: no merge
 void silu_mul(hipStream_t s, const float *gu, float *act, int rows, int F);
 void resblock_update(hipStream_t s, float *x, const float *y, int n);
 void topk_rows(hipStream_t s, const float *logits, int ld, int rows, int V, int k, int32_t *idx, float *val);
@@ -119,3 +122,28 @@ void kv_commit(hipStream_t s, bool bf16, void *kcache, void *vcache, const int32
 void advance_ctx(hipStream_t s, int32_t *ctx_len, const int32_t *accept_len, int batch);
 
 }  // namespace kg
+
+// ---------------------------------------------------------------------------------------------
+// launchers implemented in kernels_bf16.hip (fragment-major bf16 weights, hi/lo bf16 activations)
+// ---------------------------------------------------------------------------------------------
+namespace kb {
+
+// number of 16-row activation tiles used for `rows` rows: 1, 2 or a multiple of 4
+inline int mt_of(int rows) { return rows <= 16 ? 1 : rows <= 32 ? 2 : 4 * ((rows + 63) / 64); }
+inline int pad64(int n) { return (n + 63) / 64 * 64; }
+inline size_t xf_bytes(int K, int MT) { return (size_t)(K / 32) * MT * 2 * 1024; }
+
+int gemm_splits(int Npad, int K);
+// P[S][MT*16][Npad] = partial sums of X[MT*16, K] * W[Npad, K]^T
+void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MT, int S);
+void prep_rows(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp_in, int ldp, int mode_in,
+               const void *gain, float eps, float *out32, int ldo, void *Xf, int MT, int M, int K);
+void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const RowMeta &meta, float *qrot,
+                 void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap);
+void attn_combine_frag(hipStream_t st, const float *o_part, const float *ml, void *Xf, int MT, int M,
+                       int n_heads, int nsplit, int head_dim);
+void silu_frag(hipStream_t st, const float *P, int S, int Mp, int ldp, void *Xf, int MT, int M, int F);
+void resblock_p(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int M, int H);
+void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *out, int ldo, int M, int N);
+
+}  // namespace kb

@@ -12,18 +12,38 @@ def _dev(provider, name, device, dtype):
     return torch.from_numpy(np.ascontiguousarray(provider.f32(name))).to(device)
 
 
+def fragment_major(w):
+    """Reorder a row-major [N, K] matrix into the fragment-major storage the bf16 kernels stream
+    (see include/koala.h): N is padded with zero rows to a multiple of 64, K must be a multiple
+    of 64; tiles of 64 rows x 64 k, each tile 8 fragments (row/16, k/32) of 64 lanes x 8 values,
+    lane = row%16 + 16*((k%32)/8).  Returns a flat tensor of Npad*K elements."""
+    import torch
+    N, K = w.shape
+    assert K % 64 == 0
+    Np = (N + 63) // 64 * 64
+    if Np != N:
+        w = torch.cat([w, torch.zeros(Np - N, K, dtype=w.dtype, device=w.device)], dim=0)
+    v = w.reshape(Np // 64, 4, 16, K // 64, 2, 4, 8)          # rb, t, li, kt, s, lg, e
+    return v.permute(0, 3, 1, 4, 5, 2, 6).contiguous().reshape(-1)
+
+
+def _mat(w, dtype):
+    return fragment_major(w) if dtype == "bf16" else w.contiguous()
+
+
 def _layer(provider, prefix, l, device, dtype):
     import torch
     g = lambda n: _dev(provider, f"{prefix}layers.{l}.{n}", device, dtype)
-    wqkv = torch.cat([g("wq"), g("wk"), g("wv")], dim=0).contiguous()
+    wqkv = torch.cat([g("wq"), g("wk"), g("wv")], dim=0)
     gate, up = g("wgate"), g("wup")
-    wgu = torch.stack([gate, up], dim=1).reshape(2 * gate.shape[0], gate.shape[1]).contiguous()
-    return (g("in_norm"), wqkv, g("wo"), g("post_norm"), wgu, g("wdown"))
+    wgu = torch.stack([gate, up], dim=1).reshape(2 * gate.shape[0], gate.shape[1])
+    return (g("in_norm"), _mat(wqkv, dtype), _mat(g("wo"), dtype), g("post_norm"), _mat(wgu, dtype),
+            _mat(g("wdown"), dtype))
 
 
 def pack_target_weights(provider, cfg, device="cuda"):
     dt = cfg["dtype"]
-    return dict(embed=_dev(provider, "embed", device, dt), lm_head=_dev(provider, "lm_head", device, dt),
+    return dict(embed=_dev(provider, "embed", device, dt), lm_head=_mat(_dev(provider, "lm_head", device, dt), dt),
                 final_norm=_dev(provider, "final_norm", device, dt),
                 layers=[_layer(provider, "", l, device, dt) for l in range(cfg["n_layers"])])
 
@@ -31,12 +51,12 @@ def pack_target_weights(provider, cfg, device="cuda"):
 def pack_eagle_weights(provider, cfg, device="cuda"):
     dt = cfg["dtype"]
     layers = [_layer(provider, "draft.", k, device, dt) for k in range(cfg["K"])]
-    return dict(fc=_dev(provider, "draft.fc", device, dt), draft=[t for layer in layers for t in layer])
+    return dict(fc=_mat(_dev(provider, "draft.fc", device, dt), dt), draft=[t for layer in layers for t in layer])
 
 
 def pack_medusa_weights(provider, cfg, device="cuda"):
     dt = cfg["dtype"]
-    return dict(fc=None, draft=[_dev(provider, f"medusa.{j}.{k}", device, dt)
+    return dict(fc=None, draft=[_mat(_dev(provider, f"medusa.{j}.{k}", device, dt), dt)
                                 for j in range(cfg["medusa_heads"]) for k in range(cfg["K"])])
 
 
