@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of one draft-then-verify iteration (draft_expand + tree_verify + accept_prefix) on one MI355X.
+
+A step is one full iteration on the 7B-shape EAGLE-style workload: 32-layer bf16 target, K draft
+layers, 26-node depth-5 tree, 1024-token KV context, batch 1, synthetic N(0, 0.02) weights and
+N(0, 1) KV / features (all resident in HBM before timing starts).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(cfg, T, C, D, K, levels):
+    """Bytes that must move per call (bf16 = 2 bytes): weights once per pass, KV context read,
+    tree KV written; activations of T*H size are ignored (<1%)."""
+    H, F, V, L = cfg["hidden"], cfg["ffn"], cfg["vocab"], cfg["n_layers"]
+    b = 2
+    P_l = 4 * H * H + 3 * H * F
+    verify = b * (L * P_l + V * H) + b * L * 2 * H * C + b * L * 2 * H * T + b * T * H
+    passes = 1 + sum(1 for n in levels[1:D] if n > 0)          # catch-up/root pass + expanded levels
+    draft = passes * b * (2 * H * H + K * P_l + V * H) + b * K * 2 * H * C * passes
+    return verify, draft
+
+
+def device_weights(cfg, torch, K, dev):
+    """Random-init weights generated on the device (seeded), in the library's layout."""
+    import paper_2408_08146_amd as KO
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    H, F, V = cfg["hidden"], cfg["ffn"], cfg["vocab"]
+
+    def mat(n, k):
+        return (torch.randn(n, k, generator=g, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+
+    def layer():
+        wqkv = KO.fragment_major(mat(3 * H, H))
+        wo = KO.fragment_major(mat(H, H))
+        gu = mat(2 * F, H)                                       # rows already interleaved: random anyway
+        wgu = KO.fragment_major(gu)
+        wd = KO.fragment_major(mat(H, F))
+        one = torch.ones(H, dtype=torch.bfloat16, device=dev)
+        return (one, wqkv, wo, one.clone(), wgu, wd)
+
+    w = dict(embed=mat(V, H), lm_head=KO.fragment_major(mat(V, H)),
+             final_norm=torch.ones(H, dtype=torch.bfloat16, device=dev),
+             layers=[layer() for _ in range(cfg["n_layers"])])
+    w["fc"] = KO.fragment_major(mat(H, 2 * H))
+    w["draft"] = [t for _ in range(K) for t in layer()]
+    return w
+
+
+def cpu_baseline(cfg, tree, K, levels):
+    """Time the unmodified fp32 oracle on a bounded sample: tree_verify over 2 of the target layers
+    plus final norm / LM head / argmax, and one EAGLE draft pass (fc + K layers + LM head + top-k) for
+    the root row; scale linearly to 32 layers and the iteration's draft passes."""
+    import numpy as np
+    import oracle
+    from koala_synth import get_config, target_weights, eagle_weights, tensor_normal, tensor_uniform_int
+    import copy
+    Ls = 2
+    c = copy.deepcopy(cfg)
+    c["n_layers"], c["K"] = Ls, K
+    Wt = target_weights(c, 0, cache=True)
+    Wd = eagle_weights(c, 0, cache=True)
+    for n in Wt.names() + Wd.names():                            # generate outside the timed part
+        (Wt if n in Wt.shapes else Wd).f32(n)
+    T, C = tree.n_nodes, cfg["ctx"]
+    dt = np.float32
+    tc = oracle.KVCache(Ls, c["n_heads"], C + T + 8, c["head_dim"], dt)
+    dc = oracle.KVCache(K, c["n_heads"], C + T + 8, c["head_dim"], dt)
+    for l in range(Ls):
+        tc.k[l][:, :C] = tensor_normal(1, f"bk{l}", (c["n_heads"], C, c["head_dim"]))
+        tc.v[l][:, :C] = tensor_normal(1, f"bv{l}", (c["n_heads"], C, c["head_dim"]))
+    for l in range(K):
+        dc.k[l][:, :C - 1] = tensor_normal(1, f"dk{l}", (c["n_heads"], C - 1, c["head_dim"]))
+        dc.v[l][:, :C - 1] = tensor_normal(1, f"dv{l}", (c["n_heads"], C - 1, c["head_dim"]))
+    tt = tensor_uniform_int(1, "tt", (T,), 0, c["vocab"])
+    feat = tensor_normal(1, "feat", (1, c["hidden"]))
+    # full sample (layers + head), then a head-only run to separate the per-layer cost
+    t0 = time.perf_counter()
+    oracle.verify_tree(c, Wt, tc, C, tt, tree.parent, dt)
+    t_full = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.verify_tree(c, Wt, tc, C, tt, tree.parent, dt, n_layers=0)
+    t_head = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    chain = oracle.tree_depths(np.array([-1]))                   # single node: only the root pass runs
+    oracle.eagle_expand(c, Wt, Wd, dc, C, feat, tt[:1], np.array([-1], np.int32), np.array([0], np.int32),
+                        np.array([], np.int32), dt)
+    lm = Wt.f32("lm_head")
+    _ = oracle.topk_desc(lm @ feat[0], 4)
+    t_pass = time.perf_counter() - t0
+    passes = 1 + sum(1 for n in levels[1:tree.depth] if n > 0)
+    t_layer = (t_full - t_head) / Ls
+    est = cfg["n_layers"] * t_layer + t_head + passes * t_pass
+    try:
+        import threadpoolctl
+        threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    return dict(value=1.0 / est, unit="iterations/s", cores=int(threads), kind="oracle",
+                sample=(f"fp32 NumPy oracle: tree_verify on {Ls} of {cfg['n_layers']} target layers + LM head "
+                        f"({t_full:.2f}s, head {t_head:.2f}s) and one EAGLE draft pass ({t_pass:.2f}s), scaled "
+                        f"linearly to {cfg['n_layers']} layers and {passes} draft passes; "
+                        f"host has {os.cpu_count()} logical CPUs"),
+                seconds_per_iteration_est=est)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--K", type=int, default=1, help="draft layers (EAGLE-style)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override target layer count (debug only)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2408_08146_amd as KO
+    from koala_synth import get_config
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    KO.load_library()
+    dev = "cuda:0"
+    cfg = get_config(args.config)
+    assert cfg["draft"] == "eagle" and cfg["dtype"] == "bf16" and cfg["batch"] == 1
+    if args.layers:
+        cfg["n_layers"] = args.layers
+    K = args.K
+    tree = cfg["tree_template"]
+    T, D, C, H, V = tree.n_nodes, tree.depth, cfg["ctx"], cfg["hidden"], cfg["vocab"]
+    cap = cfg["capacity"]
+
+    shape = dict(hidden=H, n_heads=cfg["n_heads"], head_dim=cfg["head_dim"], ffn=cfg["ffn"], vocab=V,
+                 n_layers=cfg["n_layers"], rms_eps=cfg["rms_eps"], rope_base=cfg["rope_base"], dtype=KO.KOALA_BF16)
+    ctx = KO.KoalaContext(shape, dict(kind=KO.KOALA_DRAFT_EAGLE, K=K, medusa_heads=0, max_m=1), tree, 1)
+    w = device_weights(cfg, torch, K, dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    kv = KO.alloc_kv(cfg, 1, cap, dev, K)
+    for name in ("target_k", "target_v", "draft_k", "draft_v"):
+        kv[name][:, :, :, :C].copy_(torch.randn(kv[name][:, :, :, :C].shape, generator=g, device=dev,
+                                                dtype=torch.float32).to(torch.bfloat16))
+    ws = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
+    ctx.bind(w, kv, ws)
+
+    feat_in = torch.randn(1, 1, H, generator=g, device=dev, dtype=torch.float32)
+    tok_in = torch.randint(0, V, (1, 1), generator=g, device=dev, dtype=torch.int32)
+    tree_tokens = torch.zeros(1, T, dtype=torch.int32, device=dev)
+    scores = torch.zeros(1, T, dtype=torch.float32, device=dev)
+    feat_out = torch.zeros(1, T, H, dtype=torch.float32, device=dev)
+    greedy = torch.zeros(1, T, dtype=torch.int32, device=dev)
+    a_len = torch.zeros(1, dtype=torch.int32, device=dev)
+    path = torch.zeros(1, D + 1, dtype=torch.int32, device=dev)
+    nxt = torch.zeros(1, dtype=torch.int32, device=dev)
+    ctx0 = torch.full((1,), C, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(events=None):
+        kv["ctx_len"].copy_(ctx0)                                # same workload every step (C = 1024)
+        if events: events[0].record(stream)
+        ctx.draft_expand(1, feat_in, tok_in, 1, tree_tokens, scores)
+        if events: events[1].record(stream)
+        ctx.tree_verify(1, tree_tokens, feat_out, None, greedy)
+        if events: events[2].record(stream)
+        ctx.accept_prefix(1, tree_tokens, greedy, a_len, path, nxt, True)
+        if events: events[3].record(stream)
+        # feed the result back (device side): the root's feature and the target's next token
+        feat_in.copy_(feat_out[:, :1])
+        tok_in.copy_(nxt.view(1, 1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    acc_sum = 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # per-call breakdown and accepted lengths (separate pass, events on the launch stream)
+    n_b = min(args.steps, 20)
+    parts = [0.0, 0.0, 0.0]
+    for _ in range(n_b):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        step(ev)
+        torch.cuda.synchronize()
+        for i in range(3):
+            parts[i] += ev[i].elapsed_time(ev[i + 1]) / n_b
+        acc_sum += int(a_len.item())
+    mean_tokens = 1.0 + acc_sum / n_b
+
+    # dominant kernel: the weight-streaming GEMM; HIP events around each of its launches
+    ctx.profile_begin(8192)
+    n_p = min(args.steps, 5)
+    for _ in range(n_p):
+        step()
+    torch.cuda.synchronize()
+    gemm_ms, gemm_launches, gemm_bytes = ctx.profile_end()
+
+    levels = [sum(1 for i in range(T) if len(tree.paths[i]) == d and any(tree.parent[j] == i for j in range(T)))
+              for d in range(D + 1)]
+    vb, db = algorithmic_bytes(cfg, T, C, D, K, levels)
+    achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
+    out = {
+        "metric": "draft_verify_iterations_per_s", "value": 1e3 / ms_per_step, "unit": "iterations/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config}: 7B-shape EAGLE-style K={K}, T={T} depth {D}, ctx {C}, "
+                               f"{cfg['n_layers']} target layers, batch 1", "K": K, "tree_nodes": T, "ctx": C},
+        "tokens_per_s": 1e3 / ms_per_step * mean_tokens, "mean_tokens_per_iteration": mean_tokens,
+        "ms_draft_expand": parts[0], "ms_tree_verify": parts[1], "ms_accept_prefix": parts[2],
+        "verify_bytes": vb, "draft_bytes": db,
+        "verify_hbm_frac": vb / (parts[1] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "iteration_hbm_frac": (vb + db) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "k_gemm_packed", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "launches_timed": gemm_launches, "avg_launch_us": gemm_ms * 1e3 / max(1, gemm_launches),
+                     "avg_launch_bytes": gemm_bytes / max(1, gemm_launches)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, tree, K, levels)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -118,7 +118,9 @@ typedef struct {
  * Keys are stored already rotated.  ctx_len: device int32[max_batch]; ctx_len[b]
  * = number of committed rows C_b of sequence b in the target cache.  Rows
  * C_b .. C_b + n_nodes - 1 are scratch for the tree, so capacity must always be
- * >= C_b + n_nodes (the caller's responsibility: C_b lives on the device). */
+ * >= C_b + n_nodes (the caller's responsibility: C_b lives on the device).  The
+ * caches must hold finite numbers everywhere (e.g. be zero-filled once after
+ * allocation): scratch rows are read, with weight zero, before they are written. */
 typedef struct {
     void *target_k, *target_v, *draft_k, *draft_v;
     int capacity;
@@ -183,6 +185,15 @@ koala_status koala_accept_prefix(koala_ctx *ctx, void *hip_stream, int batch,
                                  const int32_t *tree_tokens, const int32_t *greedy,
                                  int32_t *accept_len, int32_t *accept_path, int32_t *next_token,
                                  int commit);
+
+/* Measurement aid for benchmarks (not part of the method).  Between koala_profile_begin and
+ * koala_profile_end every weight-streaming GEMM launch of the bfloat16 path is bracketed by a pair
+ * of HIP events on the call's stream (at most max_launches pairs; further launches are not
+ * timed).  koala_profile_end synchronises on the recorded events and returns the summed kernel
+ * time in milliseconds, the number of timed launches and the weight bytes those launches
+ * streamed (their algorithmic HBM traffic).  Host only; any out pointer may be NULL. */
+koala_status koala_profile_begin(koala_ctx *ctx, int max_launches);
+koala_status koala_profile_end(koala_ctx *ctx, double *gemm_ms, int *gemm_launches, double *gemm_bytes);
 
 /* Text of the last error on this context ("" if none); valid until the next call. */
 const char *koala_last_error(const koala_ctx *ctx);

@@ -8,7 +8,8 @@ KOALA_FP32, KOALA_BF16 = 0, 1
 KOALA_DRAFT_EAGLE, KOALA_DRAFT_MEDUSA = 0, 1
 
 EXPORTS = ("koala_create", "koala_workspace_bytes", "koala_bind", "koala_draft_expand",
-           "koala_tree_verify", "koala_accept_prefix", "koala_last_error", "koala_destroy")
+           "koala_tree_verify", "koala_accept_prefix", "koala_profile_begin", "koala_profile_end",
+           "koala_last_error", "koala_destroy")
 
 _STATUS = {0: "KOALA_OK", -1: "KOALA_E_NULL", -2: "KOALA_E_SHAPE", -3: "KOALA_E_ALIGN",
            -4: "KOALA_E_CAPACITY", -5: "KOALA_E_UNSUPPORTED", -6: "KOALA_E_WORKSPACE",
@@ -71,11 +72,13 @@ def load_library():
     lib.koala_draft_expand.argtypes = [vp, vp, ip, vp, vp, ip, vp, vp]
     lib.koala_tree_verify.argtypes = [vp, vp, ip, vp, vp, vp, vp]
     lib.koala_accept_prefix.argtypes = [vp, vp, ip, vp, vp, vp, vp, vp, ip]
+    lib.koala_profile_begin.argtypes = [vp, ip]
+    lib.koala_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(ip), C.POINTER(C.c_double)]
     lib.koala_last_error.argtypes = [vp]
     lib.koala_last_error.restype = C.c_char_p
     lib.koala_destroy.argtypes = [vp]
     lib.koala_destroy.restype = None
-    for n in EXPORTS[:6]:
+    for n in EXPORTS[:8]:
         getattr(lib, n).restype = C.c_int
     _LIB = lib
     return lib
@@ -158,6 +161,15 @@ class KoalaContext:
         self._check(self.lib.koala_accept_prefix(self._h, _stream(stream), batch, _ptr(tree_tokens), _ptr(greedy),
                                                  _ptr(accept_len), _ptr(accept_path), _ptr(next_token),
                                                  1 if commit else 0))
+
+    def profile_begin(self, max_launches=4096):
+        self._check(self.lib.koala_profile_begin(self._h, max_launches))
+
+    def profile_end(self):
+        """Returns (summed GEMM kernel ms, timed launches, weight bytes streamed by them)."""
+        ms, n, b = C.c_double(), C.c_int(), C.c_double()
+        self._check(self.lib.koala_profile_end(self._h, C.byref(ms), C.byref(n), C.byref(b)))
+        return ms.value, n.value, b.value
 
     def close(self):
         if self._h:

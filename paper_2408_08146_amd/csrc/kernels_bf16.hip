@@ -371,3 +371,308 @@ void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *o
 }
 
 }  // namespace kb
+
+// =====================================================================================================
+// Tree-masked attention on MFMA (bf16 KV cache, fp32 queries split into bf16 hi + lo).
+//
+// grid (nsplit, n_heads, batch), 4 waves.  The sequence's visible key range [0, kv_end) is cut into
+// nsplit chunks; inside a chunk the waves take 32-key steps round-robin, each wave keeping an
+// online-softmax state (running max, sum, output) for all MT row tiles, merged through LDS at the end.
+// Per step and wave:
+//   S^T[key][row] = K[key][:] . Q[row][:]   A = K rows straight from the cache (16 B per lane),
+//                                            B = Q fragments (hi, lo) from LDS;
+//   mask by the row's visible prefix / ancestor bits, online softmax (row max across the 4 lane groups);
+//   O^T[d][row] += V^T[d][key] P^T[key][row] B = the probabilities exactly where the S^T tile left them
+//                                            (hi + lo), A = V transposed through a per-wave LDS tile.
+// The contraction order of the second product is chosen so that no probability moves between lanes:
+// slot (lane group g, element e) stands for key 16*(e/4) + 4*g + e%4 of the step.
+// =====================================================================================================
+namespace {
+
+// LDS tiles are written and read through different element types; these typedefs keep the
+// compiler from assuming the accesses cannot overlap.
+typedef unsigned short __attribute__((may_alias)) u16_alias;
+struct __attribute__((may_alias)) u64_alias { unsigned int x, y; };
+
+template <int DH, int MT>
+__global__ __launch_bounds__(256) void k_attn_mfma(const float *__restrict__ qrot, RowMeta meta,
+                                                   const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc,
+                                                   float *__restrict__ o_part, float *__restrict__ ml,
+                                                   int rows_per_seq, int n_heads, int cap, int nsplit, int H) {
+    constexpr int KS = DH / 32;            // contraction steps over the head dimension
+    constexpr int DT = DH / 16;            // 16-wide output tiles over the head dimension
+    constexpr int VS = DH * 2 + 8;         // bytes per key row of the transposed-read V tile (padded)
+    constexpr int LPR = DH / 8;            // lanes that cover one cache row with 16 B each
+    constexpr int VI = DH / 16;            // load instructions per 32-key V tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    u32x4 *qf = (u32x4 *)smem;                                   // [MT][KS][2][64]
+    unsigned char *vt_all = smem + (size_t)MT * KS * 2 * 64 * 16;  // [4 waves][32][VS]
+    const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, li = l & 15, lg = l >> 4;
+    unsigned char *vt = vt_all + (size_t)wave * 32 * VS;
+    const float scale = rsqrtf((float)DH);
+
+    // Q fragments (B operand): lane (row%16, g) holds Q[row][32*ks + 8*g .. +8], scaled, as hi and lo
+    for (int u = tid; u < MT * KS * 64; u += 256) {
+        const int lane = u & 63, ks = (u >> 6) % KS, mt = (u >> 6) / KS;
+        const int row = mt * 16 + (lane & 15);
+        float y[8];
+        if (row < rows_per_seq) {
+            const float *q = qrot + (size_t)(b * rows_per_seq + row) * H + h * DH + ks * 32 + 8 * (lane >> 4);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = q[e] * scale;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = 0.f;
+        }
+        uint32_t hi[8], lo[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            hi[e] = f2bf(y[e]);
+            lo[e] = f2bf(y[e] - bf2f(hi[e]));
+        }
+        u32x4 a, c;
+        a.x = hi[0] | (hi[1] << 16); a.y = hi[2] | (hi[3] << 16); a.z = hi[4] | (hi[5] << 16); a.w = hi[6] | (hi[7] << 16);
+        c.x = lo[0] | (lo[1] << 16); c.y = lo[2] | (lo[3] << 16); c.z = lo[4] | (lo[5] << 16); c.w = lo[6] | (lo[7] << 16);
+        qf[((mt * KS + ks) * 2 + 0) * 64 + lane] = a;
+        qf[((mt * KS + ks) * 2 + 1) * 64 + lane] = c;
+    }
+    // per-lane row metadata (lane's row in tile mt is mt*16 + li)
+    int nvis[MT], base[MT];
+    uint64_t mask[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int row = mt * 16 + li;
+        const bool ok = row < rows_per_seq;
+        const int r = b * rows_per_seq + (ok ? row : 0);
+        nvis[mt] = ok ? meta.row_nvis[r] : 0;
+        base[mt] = ok ? meta.row_base[r] : 0;
+        mask[mt] = ok ? meta.row_mask[r] : 0ull;
+    }
+    const int kv_end = meta.kv_end[b];
+    int chunk = (kv_end + nsplit - 1) / nsplit;
+    chunk = (chunk + 31) / 32 * 32;
+    const int j0 = s * chunk, j1 = min(kv_end, j0 + chunk);
+    const int nsteps = j1 > j0 ? (j1 - j0 + 31) / 32 : 0;
+    const bf16_t *kb = kc + ((size_t)b * n_heads + h) * cap * DH;
+    const bf16_t *vb = vc + ((size_t)b * n_heads + h) * cap * DH;
+
+    f32x4 acc_o[MT][DT];
+    float m_run[MT], l_run[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        m_run[mt] = -INFINITY;
+        l_run[mt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) acc_o[mt][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    __syncthreads();
+
+    for (int st = wave; st < nsteps; st += 4) {
+        const int k0 = j0 + st * 32;
+        // ---- loads: K fragments (A operand) and the V tile
+        u32x4 kf[2][KS];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int key = min(k0 + 16 * j + li, cap - 1);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kf[j][ks] = *(const u32x4 *)(kb + (size_t)key * DH + ks * 32 + 8 * lg);
+        }
+        u32x4 vr[VI];
+#pragma unroll
+        for (int i = 0; i < VI; ++i) {
+            const int key = min(k0 + i * (64 / LPR) + l / LPR, cap - 1);
+            vr[i] = *(const u32x4 *)(vb + (size_t)key * DH + (l % LPR) * 8);
+        }
+        // ---- S^T = K Q^T
+        f32x4 sc[2][MT];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) sc[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const bf16x8 qh = __builtin_bit_cast(bf16x8, qf[((mt * KS + ks) * 2 + 0) * 64 + l]);
+                const bf16x8 ql = __builtin_bit_cast(bf16x8, qf[((mt * KS + ks) * 2 + 1) * 64 + l]);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, kf[j][ks]);
+                    sc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qh, sc[j][mt], 0, 0, 0);
+                    sc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ql, sc[j][mt], 0, 0, 0);
+                }
+            }
+        // ---- V tile -> LDS (row-major, padded), written as 8-byte halves
+#pragma unroll
+        for (int i = 0; i < VI; ++i) {
+            const int kl = i * (64 / LPR) + l / LPR;
+            u64_alias *dst = (u64_alias *)(vt + (size_t)kl * VS + (l % LPR) * 16);
+            const bool in = k0 + kl < j1;   // rows past the chunk contribute exact zeros (0 * garbage could be NaN)
+            dst[0] = in ? u64_alias{vr[i].x, vr[i].y} : u64_alias{0u, 0u};
+            dst[1] = in ? u64_alias{vr[i].z, vr[i].w} : u64_alias{0u, 0u};
+        }
+        // ---- mask, online softmax; probabilities stay in place as the B operand (hi, lo)
+        bf16x8 ph[MT], pl[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float p[8];
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int key = k0 + 16 * (e >> 2) + 4 * lg + (e & 3);
+                const unsigned rel = (unsigned)(key - base[mt]);   // negative differences wrap to >= 64
+                const uint32_t half = rel < 32u ? (uint32_t)mask[mt] : (uint32_t)(mask[mt] >> 32);
+                const bool bit = rel < 64u && ((half >> (rel & 31u)) & 1u);
+                const bool vis = key < j1 && (key < nvis[mt] || bit);
+                p[e] = vis ? sc[e >> 2][mt][e & 3] : -INFINITY;
+                tmax = fmaxf(tmax, p[e]);
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            const float m_new = fmaxf(m_run[mt], tmax);
+            const float alpha = (m_run[mt] == -INFINITY) ? 0.f : __expf(m_run[mt] - m_new);
+            float psum = 0.f;
+            uint32_t hi[8], lo[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float v = (p[e] == -INFINITY) ? 0.f : __expf(p[e] - m_new);
+                psum += v;
+                hi[e] = f2bf(v);
+                lo[e] = f2bf(v - bf2f(hi[e]));
+            }
+            l_run[mt] = l_run[mt] * alpha + psum;
+            m_run[mt] = m_new;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                acc_o[mt][dt][0] *= alpha; acc_o[mt][dt][1] *= alpha;
+                acc_o[mt][dt][2] *= alpha; acc_o[mt][dt][3] *= alpha;
+            }
+            u32x4 a, c;
+            a.x = hi[0] | (hi[1] << 16); a.y = hi[2] | (hi[3] << 16); a.z = hi[4] | (hi[5] << 16); a.w = hi[6] | (hi[7] << 16);
+            c.x = lo[0] | (lo[1] << 16); c.y = lo[2] | (lo[3] << 16); c.z = lo[4] | (lo[5] << 16); c.w = lo[6] | (lo[7] << 16);
+            ph[mt] = __builtin_bit_cast(bf16x8, a);
+            pl[mt] = __builtin_bit_cast(bf16x8, c);
+        }
+        // ---- O^T += V^T P^T ; A operand gathered from the LDS tile: lane (d%16, g), slot e -> key 16*(e/4)+4g+e%4
+        const u16_alias *vt16 = (const u16_alias *)vt;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const int ka = 16 * ((2 * e2) >> 2) + 4 * lg + ((2 * e2) & 3);
+                const uint32_t v0 = vt16[(size_t)ka * (VS / 2) + dt * 16 + li];
+                const uint32_t v1 = vt16[(size_t)(ka + 1) * (VS / 2) + dt * 16 + li];
+                w[e2] = v0 | (v1 << 16);
+            }
+            u32x4 a;
+            a.x = w[0]; a.y = w[1]; a.z = w[2]; a.w = w[3];
+            const bf16x8 va = __builtin_bit_cast(bf16x8, a);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc_o[mt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, ph[mt], acc_o[mt][dt], 0, 0, 0);
+                acc_o[mt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pl[mt], acc_o[mt][dt], 0, 0, 0);
+            }
+        }
+    }
+    // ---- row sums across the four lane groups
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        l_run[mt] += __shfl_xor(l_run[mt], 16);
+        l_run[mt] += __shfl_xor(l_run[mt], 32);
+    }
+    // ---- merge the four waves through LDS (the Q / V regions are free now)
+    __syncthreads();
+    float *mo = (float *)smem;                         // [3 waves][MT][DT][64][4]
+    float *mm = mo + (size_t)3 * MT * DT * 256;        // [3 waves][MT][64][2]
+    if (wave > 0) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                *(f32x4 *)(mo + ((((size_t)(wave - 1) * MT + mt) * DT + dt) * 64 + l) * 4) = acc_o[mt][dt];
+            mm[(((wave - 1) * MT + mt) * 64 + l) * 2 + 0] = m_run[mt];
+            mm[(((wave - 1) * MT + mt) * 64 + l) * 2 + 1] = l_run[mt];
+        }
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        float M = m_run[mt];
+#pragma unroll
+        for (int w = 0; w < 3; ++w) M = fmaxf(M, mm[((w * MT + mt) * 64 + l) * 2]);
+        const float a0 = (m_run[mt] == -INFINITY) ? 0.f : __expf(m_run[mt] - M);
+        float lsum = l_run[mt] * a0;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            acc_o[mt][dt][0] *= a0; acc_o[mt][dt][1] *= a0; acc_o[mt][dt][2] *= a0; acc_o[mt][dt][3] *= a0;
+        }
+#pragma unroll
+        for (int w = 0; w < 3; ++w) {
+            const float mw = mm[((w * MT + mt) * 64 + l) * 2];
+            if (mw == -INFINITY) continue;
+            const float aw = __expf(mw - M);
+            lsum += aw * mm[((w * MT + mt) * 64 + l) * 2 + 1];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const f32x4 o = *(const f32x4 *)(mo + ((((size_t)w * MT + mt) * DT + dt) * 64 + l) * 4);
+                acc_o[mt][dt][0] += aw * o[0]; acc_o[mt][dt][1] += aw * o[1];
+                acc_o[mt][dt][2] += aw * o[2]; acc_o[mt][dt][3] += aw * o[3];
+            }
+        }
+        const int row = mt * 16 + li;
+        if (row < rows_per_seq) {
+            const size_t r = (size_t)b * rows_per_seq + row;
+            float *o = o_part + ((r * n_heads + h) * nsplit + s) * DH;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) *(f32x4 *)(o + dt * 16 + 4 * lg) = acc_o[mt][dt];
+            if (lg == 0) {
+                float *p = ml + ((r * n_heads + h) * nsplit + s) * 2;
+                p[0] = M;
+                p[1] = lsum;
+            }
+        }
+    }
+}
+
+template <int DH, int MT>
+void launch_attn(hipStream_t st, const float *qrot, const RowMeta &meta, const void *kc, const void *vc,
+                 float *o_part, float *ml, int batch, int rows_per_seq, int n_heads, int cap, int nsplit) {
+    constexpr int KS = DH / 32, DT = DH / 16, VS = DH * 2 + 8;
+    const size_t main_b = (size_t)MT * KS * 2 * 64 * 16 + (size_t)4 * 32 * VS;
+    const size_t merge_b = (size_t)3 * MT * DT * 256 * 4 + (size_t)3 * MT * 64 * 2 * 4;
+    const size_t sm = main_b > merge_b ? main_b : merge_b;
+    static bool done = false;
+    if (!done) {
+        (void)hipFuncSetAttribute((const void *)k_attn_mfma<DH, MT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)sm);
+        done = true;
+    }
+    k_attn_mfma<DH, MT><<<dim3(nsplit, n_heads, batch), 256, sm, st>>>(
+        qrot, meta, (const bf16_t *)kc, (const bf16_t *)vc, o_part, ml, rows_per_seq, n_heads, cap, nsplit,
+        n_heads * DH);
+}
+
+}  // namespace
+
+namespace kb {
+
+// rows_per_seq <= 64.  Writes per-split partial outputs (o_part, ml) like the generic kernel.
+void attention_mfma(hipStream_t st, const float *qrot, const RowMeta &meta, const void *kc, const void *vc,
+                    float *o_part, float *ml, int batch, int rows_per_seq, int n_heads, int head_dim, int cap,
+                    int nsplit) {
+    const int MT = rows_per_seq <= 16 ? 1 : rows_per_seq <= 32 ? 2 : 4;
+#define KOALA_ATT(DHV, MTV) \
+    launch_attn<DHV, MTV>(st, qrot, meta, kc, vc, o_part, ml, batch, rows_per_seq, n_heads, cap, nsplit)
+    if (head_dim == 128) {
+        if (MT == 1) KOALA_ATT(128, 1); else if (MT == 2) KOALA_ATT(128, 2); else KOALA_ATT(128, 4);
+    } else {
+        if (MT == 1) KOALA_ATT(64, 1); else if (MT == 2) KOALA_ATT(64, 2); else KOALA_ATT(64, 4);
+    }
+#undef KOALA_ATT
+}
+
+}  // namespace kb

@@ -119,7 +119,14 @@ void decoder_layer(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, co
 // Split-K GEMM on the fragment buffer: partial sums of X * W^T into c->part; returns the split count.
 int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) {
     const int Npad = kb::pad64(N), S = kb::gemm_splits(Npad, K);
+    const bool timed = c->prof_on && (size_t)(c->prof_used + 2) <= c->prof_ev.size();
+    if (timed) (void)hipEventRecord(c->prof_ev[c->prof_used], st);
     kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S);
+    if (timed) {
+        (void)hipEventRecord(c->prof_ev[c->prof_used + 1], st);
+        c->prof_used += 2;
+        c->prof_bytes += (double)Npad * K * 2.0;
+    }
     return S;
 }
 
@@ -135,8 +142,8 @@ void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_se
     int S = bf_gemm(c, st, lw[1], 3 * H, H, MT);
     kb::rope_append(st, c->part, S, Mp, 3 * H, c->meta, c->qrot, kc, vc, rows, H, s.n_heads, s.head_dim,
                     c->kv.capacity);
-    kg::attention(st, true, c->qrot, c->meta, kc, vc, c->o_part, c->ml, nullptr, batch, rows_per_seq, s.n_heads,
-                  s.head_dim, c->kv.capacity, ns);
+    kb::attention_mfma(st, c->qrot, c->meta, kc, vc, c->o_part, c->ml, batch, rows_per_seq, s.n_heads, s.head_dim,
+                       c->kv.capacity, ns);
     kb::attn_combine_frag(st, c->o_part, c->ml, c->xf, MT, rows, s.n_heads, ns, s.head_dim);
     S = bf_gemm(c, st, lw[2], H, H, MT);
     kb::prep_rows(st, c->x, H, c->part, S, Mp, H, 1, lw[3], s.rms_eps, nullptr, 0, c->xf, MT, rows, H);
@@ -205,6 +212,10 @@ koala_status koala_create(const koala_shape *shape, const koala_draft_shape *dra
     c->max_rows = max_batch * std::max(std::max(T, draft->max_m), std::max(1, draft->medusa_heads));
     c->bound = false;
     c->ws = nullptr;
+    c->prof_on = false;
+    c->prof_used = 0;
+    c->prof_bytes = 0.0;
+    c->pend_S = 0;
     c->parent.assign(tree->parent, tree->parent + T);
     c->rank.assign(tree->rank, tree->rank + T);
     c->topk.assign(tree->topk_per_depth, tree->topk_per_depth + D);
@@ -487,8 +498,46 @@ koala_status koala_accept_prefix(koala_ctx *c, void *hip_stream, int batch, cons
     return KOALA_OK;
 }
 
+koala_status koala_profile_begin(koala_ctx *c, int max_launches) {
+    if (!c) return KOALA_E_NULL;
+    c->err.clear();
+    if (max_launches < 1 || max_launches > (1 << 16)) return fail(c, KOALA_E_SHAPE, "max_launches out of range");
+    while (c->prof_ev.size() < (size_t)2 * max_launches) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return fail(c, KOALA_E_DEVICE, "hipEventCreate failed");
+        c->prof_ev.push_back(e);
+    }
+    c->prof_used = 0;
+    c->prof_bytes = 0.0;
+    c->prof_on = true;
+    return KOALA_OK;
+}
+
+koala_status koala_profile_end(koala_ctx *c, double *gemm_ms, int *gemm_launches, double *gemm_bytes) {
+    if (!c) return KOALA_E_NULL;
+    c->err.clear();
+    c->prof_on = false;
+    double total = 0.0;
+    for (int i = 0; i + 1 < c->prof_used; i += 2) {
+        float ms = 0.f;
+        if (hipEventSynchronize(c->prof_ev[i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, c->prof_ev[i], c->prof_ev[i + 1]) != hipSuccess)
+            return fail(c, KOALA_E_DEVICE, "reading profile events failed");
+        total += ms;
+    }
+    if (gemm_ms) *gemm_ms = total;
+    if (gemm_launches) *gemm_launches = c->prof_used / 2;
+    if (gemm_bytes) *gemm_bytes = c->prof_bytes;
+    c->prof_used = 0;
+    return KOALA_OK;
+}
+
 const char *koala_last_error(const koala_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
-void koala_destroy(koala_ctx *ctx) { delete ctx; }
+void koala_destroy(koala_ctx *ctx) {
+    if (!ctx) return;
+    for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+    delete ctx;
+}
 
 }  // extern "C"

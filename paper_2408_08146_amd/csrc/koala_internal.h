@@ -61,6 +61,12 @@ struct koala_ctx {
     float *part;
     size_t xf_bytes, part_bytes;
     int pend_S, pend_ld, pend_mode;  // partial sums waiting to be folded into x (0 = none)
+
+    // optional event timing of the GEMM launches (koala_profile_begin / _end)
+    std::vector<hipEvent_t> prof_ev;
+    int prof_used;
+    double prof_bytes;
+    bool prof_on;
 };
 
 #define KOALA_CHECK_LAUNCH(ctx)                                              \
@@ -142,6 +148,9 @@ void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const R
                  void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap);
 void attn_combine_frag(hipStream_t st, const float *o_part, const float *ml, void *Xf, int MT, int M,
                        int n_heads, int nsplit, int head_dim);
+void attention_mfma(hipStream_t st, const float *qrot, const RowMeta &meta, const void *kc, const void *vc,
+                    float *o_part, float *ml, int batch, int rows_per_seq, int n_heads, int head_dim, int cap,
+                    int nsplit);
 void silu_frag(hipStream_t st, const float *P, int S, int Mp, int ldp, void *Xf, int MT, int M, int F);
 void resblock_p(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int M, int H);
 void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *out, int ldo, int M, int N);
