@@ -24,7 +24,7 @@
  *    returned as negative koala_status values; koala_last_error() gives text.
  *  - Limits: at most 64 tree nodes per sequence, at most 64 catch-up rows (m),
  *    head_dim 64 or 128, hidden = n_heads * head_dim; for bfloat16 hidden and
- *    ffn must be multiples of 128.
+ *    ffn must be multiples of 128 and vocab at most 65536.
  *
  * Matrix storage.  For KOALA_FP32 every matrix [N, K] is plain row-major.  For
  * KOALA_BF16 every Linear weight (wqkv, wo, wgu, wdown, lm_head, fc, Medusa

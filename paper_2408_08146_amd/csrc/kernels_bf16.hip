@@ -5,8 +5,9 @@
 // stream out of HBM.  The kernels here are built around that:
 //   * weights are stored fragment-major (see koala.h): one wave load instruction reads 1 KiB of
 //     contiguous memory and lands exactly in the A operand of a 16x16x32 bf16 MFMA;
-//   * activations are split into bf16 hi + lo parts (x = hi + lo to ~16 mantissa bits), also
-//     in fragment order, so results stay at fp32-class accuracy while using the bf16 MFMA;
+//   * activations stay fp32 in memory; the GEMM splits them into bf16 hi + lo parts
+//     (x = hi + lo to ~16 mantissa bits) while staging them in LDS, applying RMSNorm on the way,
+//     so results stay at fp32-class accuracy while using the bf16 MFMA;
 //   * K is split over workgroups; partial sums go to a scratch buffer that the consumer
 //     kernel adds up in a fixed order (deterministic, no float atomics).
 #include "koala_internal.h"
@@ -27,19 +28,30 @@ __device__ __forceinline__ uint32_t f2bf(float v) {  // round to nearest even
 // ---------------------------------------------------------------------------------------------
 // Packed GEMM.  Wp: [Npad/64][K/64] tiles of 64 rows x 64 k, each tile = 8 fragments
 // (t = row/16, s = k/32) of 64 lanes x 16 B; lane = (row%16) + 16*((k%32)/8).
-// Xf: [K/32][MTT][hi,lo][64 lanes] x 16 B; lane = (m%16) + 16*((k%32)/8); a launch handles the MT
-//     activation tiles mt0 .. mt0+MT-1 of the MTT present.
-// P:  [S][MTT*16][Npad] fp32 partial sums; split sp covers 128-k chunks [sp*nch/S, (sp+1)*nch/S).
-// Workgroup = 4 waves; wave w owns row block wb*4 + w (64 rows); the X chunk is shared in LDS.
+// X:  fp32 rows [M][ldx] (rows >= M count as zero), optionally RMS-normalised on the fly:
+//     x * inv_rms(row) * gain[k], inv_rms from the per-chunk sums of squares a fold kernel left.
+//     While a 128-k chunk of weights streams, the workgroup converts the next chunk of X to
+//     bf16 hi + lo fragments (B operands) in LDS; a launch handles the MT activation tiles
+//     mt0 .. mt0+MT-1 (16 rows each).
+// P:  [S][Mp][Npad] fp32 partial sums; split sp covers 128-k chunks [sp*nch/S, (sp+1)*nch/S).
+// Workgroup = 4 waves; wave w owns row block wb*4 + w (64 weight rows).
 // ---------------------------------------------------------------------------------------------
+struct XSrc {
+    const float *x;       // activations
+    int ldx, M;
+    const float *sums;    // [nparts][srows] sums of squares per 256-column chunk, or nullptr: no normalisation
+    int nparts, srows;
+    const bf16_t *gain;   // RMSNorm gain [K] (with sums)
+    float eps;
+};
+
 template <int MT>
-__global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
-                                                     float *__restrict__ P, int Npad, int K, int S, int nwb,
-                                                     int MTT, int mt0) {
-    extern __shared__ u32x4 xs[];            // [2][XCH]
-    constexpr int XCH = 4 * MT * 2 * 64;     // 16-byte units of X per 128-k chunk
-    constexpr int XPT = XCH / 256;           // per thread
-    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
+__global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ Wp, XSrc xs_, float *__restrict__ P,
+                                                     int Npad, int K, int S, int nwb, int Mp, int mt0) {
+    extern __shared__ u32x4 xs[];            // [2][XCH] then inv_rms[64]
+    constexpr int XCH = 4 * MT * 2 * 64;     // 16-byte units of X fragments per 128-k chunk
+    float *inv_s = (float *)(xs + 2 * XCH);
+    const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, li = l & 15, lg = l >> 4;
     const int wb = blockIdx.x % nwb, sp = blockIdx.x / nwb;
     const int nch = K / 128;
     const int c_begin = (int)((long long)sp * nch / S), c_end = (int)((long long)(sp + 1) * nch / S);
@@ -47,36 +59,96 @@ __global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ W
     const int rb = wb * 4 + wave;
     const bool active = rb < Npad / 64;
     const u32x4 *wsrc = Wp + ((size_t)(active ? rb : 0) * (K / 64) + (size_t)c_begin * 2) * 512 + l;
-    // 16-byte unit u of chunk c lives at xsrc + (c*4 + u / (MT*128)) * MTT*128 + u % (MT*128)
-    const u32x4 *xsrc = Xf + (size_t)c_begin * 4 * MTT * 128 + (size_t)mt0 * 128;
-    auto xaddr = [&](int c, int u) { return xsrc + ((size_t)c * 4 + u / (MT * 128)) * (MTT * 128) + u % (MT * 128); };
+    const bool norm = xs_.sums != nullptr;
+
+    // fragment piece q = tid + 256*i (i < MT): k-step ksl, tile mt, lane pl -> row, 8 consecutive k
+    int p_row[MT], p_koff[MT], p_dst[MT];
+    bool p_ok[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const int q = tid + 256 * i, ksl = q / (MT * 64), rem = q % (MT * 64), mt = rem / 64, pl = rem % 64;
+        p_row[i] = (mt0 + mt) * 16 + (pl & 15);
+        p_koff[i] = ksl * 32 + 8 * (pl >> 4);
+        p_dst[i] = (ksl * MT * 2 + mt * 2) * 64 + pl;
+        p_ok[i] = p_row[i] < xs_.M;
+    }
+    if (norm) {
+        if (tid < MT * 16) {   // rows of this launch: mt0*16 + tid
+            const int row = mt0 * 16 + tid;
+            float tot = 0.f;
+            if (row < xs_.M)
+                for (int c = 0; c < xs_.nparts; ++c) tot += xs_.sums[(size_t)c * xs_.srows + row];
+            inv_s[tid] = 1.0f / sqrtf(tot / (float)K + xs_.eps);
+        }
+        __syncthreads();
+    }
+    float xr[MT][8];
+    auto xload = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            if (p_ok[i]) {
+                const float *src = xs_.x + (size_t)p_row[i] * xs_.ldx + (size_t)(c_begin + c) * 128 + p_koff[i];
+                const f32x4 a = *(const f32x4 *)src, b = *(const f32x4 *)(src + 4);
+                xr[i][0] = a[0]; xr[i][1] = a[1]; xr[i][2] = a[2]; xr[i][3] = a[3];
+                xr[i][4] = b[0]; xr[i][5] = b[1]; xr[i][6] = b[2]; xr[i][7] = b[3];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xr[i][e] = 0.f;
+            }
+        }
+    };
+    auto xstore = [&](int c, u32x4 *dst) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            float y[8];
+            if (norm && p_ok[i]) {
+                const float sc = inv_s[p_row[i] - mt0 * 16];
+                const u32x4 g = *(const u32x4 *)(xs_.gain + (size_t)(c_begin + c) * 128 + p_koff[i]);
+                const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    y[e] = xr[i][e] * sc * bf2f((e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) y[e] = xr[i][e];
+            }
+            uint32_t hi[8], lo[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                hi[e] = f2bf(y[e]);
+                lo[e] = f2bf(y[e] - bf2f(hi[e]));
+            }
+            u32x4 h, w;
+            h.x = hi[0] | (hi[1] << 16); h.y = hi[2] | (hi[3] << 16); h.z = hi[4] | (hi[5] << 16); h.w = hi[6] | (hi[7] << 16);
+            w.x = lo[0] | (lo[1] << 16); w.y = lo[2] | (lo[3] << 16); w.z = lo[4] | (lo[5] << 16); w.w = lo[6] | (lo[7] << 16);
+            dst[p_dst[i]] = h;
+            dst[p_dst[i] + 64] = w;
+        }
+    };
+
     f32x4 acc[4][MT];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[t][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
     u32x4 wr[2][8];
-    u32x4 xr[XPT];
     const int nb = nchunks * 2;
     auto wload = [&](int b, int slot) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) wr[slot][j] = __builtin_nontemporal_load(wsrc + (size_t)b * 512 + j * 64);
     };
     if (nchunks > 0) {
-#pragma unroll
-        for (int i = 0; i < XPT; ++i) xs[threadIdx.x + 256 * i] = *xaddr(0, threadIdx.x + 256 * i);
         if (active) {
             wload(0, 0);
             wload(1, 1);
         }
+        xload(0);
+        xstore(0, xs);
     }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
         const bool more = c + 1 < nchunks;
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < XPT; ++i) xr[i] = *xaddr(c + 1, threadIdx.x + 256 * i);
-        }
+        if (more) xload(c + 1);
         const u32x4 *xc = xs + (c & 1) * XCH;
         if (active) {
 #pragma unroll
@@ -107,11 +179,7 @@ __global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ W
                 }
             }
         }
-        if (more) {
-            u32x4 *xn = xs + ((c + 1) & 1) * XCH;
-#pragma unroll
-            for (int i = 0; i < XPT; ++i) xn[threadIdx.x + 256 * i] = xr[i];
-        }
+        if (more) xstore(c + 1, xs + ((c + 1) & 1) * XCH);
         __syncthreads();
     }
     if (active) {
@@ -120,85 +188,51 @@ __global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ W
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
                 const int row = (mt0 + m) * 16 + li, n = rb * 64 + 16 * t + 4 * lg;
-                *(f32x4 *)(P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = acc[t][m];
+                *(f32x4 *)(P + ((size_t)sp * Mp + row) * Npad + n) = acc[t][m];
             }
     }
 }
 
 // sum of the split-K partials of element (row, col)
 __device__ __forceinline__ float psum(const float *P, int S, int Mp, int ld, int row, int col) {
-    float v = 0.f;
-    for (int s = 0; s < S; ++s) v += P[((size_t)s * Mp + row) * ld + col];
-    return v;
-}
-
-// store 8 consecutive k of row m (k0 % 8 == 0) as hi/lo fragments
-__device__ __forceinline__ void store_frag8(u32x4 *Xf, int MT, int m, int k0, const float *y) {
-    uint32_t hi[8], lo[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        hi[e] = f2bf(y[e]);
-        lo[e] = f2bf(y[e] - bf2f(hi[e]));
+    const float *p = P + (size_t)row * ld + col;
+    const size_t stride = (size_t)Mp * ld;
+    float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {   // four loads in flight; the order of the additions is fixed
+        v0 += p[(size_t)s * stride];
+        v1 += p[(size_t)(s + 1) * stride];
+        v2 += p[(size_t)(s + 2) * stride];
+        v3 += p[(size_t)(s + 3) * stride];
     }
-    const int ks = k0 >> 5, lane = (m & 15) + 16 * ((k0 & 31) >> 3), mt = m >> 4;
-    u32x4 h, w;
-    h.x = hi[0] | (hi[1] << 16); h.y = hi[2] | (hi[3] << 16); h.z = hi[4] | (hi[5] << 16); h.w = hi[6] | (hi[7] << 16);
-    w.x = lo[0] | (lo[1] << 16); w.y = lo[2] | (lo[3] << 16); w.z = lo[4] | (lo[5] << 16); w.w = lo[6] | (lo[7] << 16);
-    u32x4 *dst = Xf + ((size_t)(ks * MT + mt) * 2) * 64 + lane;
-    dst[0] = h;
-    dst[64] = w;
+    for (; s < S; ++s) v0 += p[(size_t)s * stride];
+    return (v0 + v1) + (v2 + v3);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row preparation: (optional) add split-K partials into the fp32 rows, (optional) RMSNorm,
-// write fp32 and/or hi/lo fragments.  One block per (padded) row; rows >= M write zero fragments.
-// mode_in: 0 v = x; 1 v = x + sum(P), x <- v; 2 v = sum(P), x <- v.
+// Fold: x[m][j] = (mode 1: x +) sum of partials (mode 0: x unchanged), and the sum of squares of
+// each 256-column chunk of the result to sums[chunk][m] for the RMSNorm of the next GEMM.
+// grid (ceil(N/256), M).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_prep_rows(float *x, int ldx, const float *P, int S, int Mp_in, int ldp,
-                                                   int mode_in, const bf16_t *gain, float eps, float *out32,
-                                                   int ldo, u32x4 *Xf, int MT, int M, int K) {
+__global__ __launch_bounds__(256) void k_fold(float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode,
+                                              int N, float *sums, int srows) {
     __shared__ float red[4];
-    const int m = blockIdx.x, tid = threadIdx.x;
-    if (m >= M) {
-        if (Xf) {
-            const float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            for (int g = tid; g < K / 8; g += 256) store_frag8(Xf, MT, m, g * 8, z);
-        }
-        return;
-    }
-    float *xr = x + (size_t)m * ldx;
-    float ss = 0.f;
-    for (int j = tid; j < K; j += 256) {
-        float v;
-        if (mode_in == 0) v = xr[j];
+    const int c = blockIdx.x, m = blockIdx.y, tid = threadIdx.x, j = c * 256 + tid;
+    float v = 0.f;
+    if (j < N) {
+        if (mode == 0) v = x[(size_t)m * ldx + j];
         else {
-            v = psum(P, S, Mp_in, ldp, m, j);
-            if (mode_in == 1) v += xr[j];
-            xr[j] = v;
+            v = psum(P, S, Mp, ldp, m, j);
+            if (mode == 1) v += x[(size_t)m * ldx + j];
+            x[(size_t)m * ldx + j] = v;
         }
-        ss += v * v;
     }
-    float inv = 1.f;
-    if (gain) {
-        for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-        if ((tid & 63) == 0) red[tid >> 6] = ss;
-        __syncthreads();
-        inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)K + eps);
-    }
-    __syncthreads();   // x row fully written before it is re-read below
-    for (int g = tid; g < K / 8; g += 256) {
-        float y[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int j = g * 8 + e;
-            y[e] = gain ? xr[j] * inv * bf2f(gain[j]) : xr[j];
-        }
-        if (out32) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) out32[(size_t)m * ldo + g * 8 + e] = y[e];
-        }
-        if (Xf) store_frag8(Xf, MT, m, g * 8, y);
-    }
+    if (!sums) return;
+    float ss = v * v;
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) sums[(size_t)c * srows + m] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -221,61 +255,58 @@ __global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowMeta 
     vc[o + half + i] = (bf16_t)f2bf(v1);
 }
 
-// merge the attention splits and write the result as hi/lo fragments (K = H). grid: padded rows.
-__global__ __launch_bounds__(256) void k_attn_combine_frag(const float *o_part, const float *ml, u32x4 *Xf, int MT,
-                                                           int M, int n_heads, int nsplit, int DH, int H) {
-    const int r = blockIdx.x;
-    for (int g = threadIdx.x; g < H / 8; g += 256) {
-        float y[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (r < M) {
-            const int h = (g * 8) / DH, d0 = (g * 8) % DH;
-            const float *p = ml + ((size_t)r * n_heads + h) * nsplit * 2;
-            float Mx = -INFINITY;
-            for (int s = 0; s < nsplit; ++s) Mx = fmaxf(Mx, p[2 * s]);
-            float den = 0.f;
-            for (int s = 0; s < nsplit; ++s) {
-                const float ms = p[2 * s];
-                if (ms == -INFINITY) continue;
-                const float w = __expf(ms - Mx);
-                den += w * p[2 * s + 1];
-                const float *o = o_part + (((size_t)r * n_heads + h) * nsplit + s) * DH + d0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) y[e] += w * o[e];
-            }
-            const float inv = 1.0f / den;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] *= inv;
-        }
-        store_frag8(Xf, MT, r, g * 8, y);
+// merge the attention splits: out[r][h*DH + d]. grid (H/512, M), 64 threads x 8 columns
+__global__ __launch_bounds__(64) void k_attn_combine(const float *o_part, const float *ml, float *out, int n_heads,
+                                                     int nsplit, int DH, int H) {
+    const int r = blockIdx.y, g = blockIdx.x * 64 + threadIdx.x;
+    if (g >= H / 8) return;
+    const int h = (g * 8) / DH, d0 = (g * 8) % DH;
+    const float *p = ml + ((size_t)r * n_heads + h) * nsplit * 2;
+    float Mx = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) Mx = fmaxf(Mx, p[2 * s]);
+    float y[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float den = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        const float ms = p[2 * s];
+        if (ms == -INFINITY) continue;
+        const float w = __expf(ms - Mx);
+        den += w * p[2 * s + 1];
+        const f32x4 *o = (const f32x4 *)(o_part + (((size_t)r * n_heads + h) * nsplit + s) * DH + d0);
+        const f32x4 a = o[0], b = o[1];
+        y[0] += w * a[0]; y[1] += w * a[1]; y[2] += w * a[2]; y[3] += w * a[3];
+        y[4] += w * b[0]; y[5] += w * b[1]; y[6] += w * b[2]; y[7] += w * b[3];
     }
+    const float inv = 1.0f / den;
+    f32x4 *dst = (f32x4 *)(out + (size_t)r * H + g * 8);
+    dst[0] = (f32x4){y[0] * inv, y[1] * inv, y[2] * inv, y[3] * inv};
+    dst[1] = (f32x4){y[4] * inv, y[5] * inv, y[6] * inv, y[7] * inv};
 }
 
-// SiLU(gate) * up from the gate/up partials (rows interleaved: col 2f = gate, 2f+1 = up) -> fragments (K = F)
-__global__ __launch_bounds__(256) void k_silu_frag(const float *P, int S, int Mp, int ldp, u32x4 *Xf, int MT, int M,
-                                                   int F) {
-    const int r = blockIdx.x;
-    for (int g = threadIdx.x; g < F / 8; g += 256) {
-        float y[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (r < M) {
-            float gu[16];
+// act[r][f] = SiLU(gate_f) * up_f from the gate/up partials (col 2f = gate, 2f+1 = up).
+// grid (ceil(F/8/64), M), 64 threads x 8 outputs
+__global__ __launch_bounds__(64) void k_silu_p(const float *P, int S, int Mp, int ldp, float *act, int F) {
+    const int r = blockIdx.y, g = blockIdx.x * 64 + threadIdx.x;
+    if (g >= F / 8) return;
+    float gu[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) gu[e] = 0.f;
-            for (int s = 0; s < S; ++s) {
-                const f32x4 *src = (const f32x4 *)(P + ((size_t)s * Mp + r) * ldp + (size_t)g * 16);
+    for (int e = 0; e < 16; ++e) gu[e] = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const f32x4 *src = (const f32x4 *)(P + ((size_t)s * Mp + r) * ldp + (size_t)g * 16);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x4 v = src[q];
-                    gu[4 * q] += v.x; gu[4 * q + 1] += v.y; gu[4 * q + 2] += v.z; gu[4 * q + 3] += v.w;
-                }
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float a = gu[2 * e];
-                y[e] = a / (1.0f + __expf(-a)) * gu[2 * e + 1];
-            }
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 v = src[q];
+            gu[4 * q] += v[0]; gu[4 * q + 1] += v[1]; gu[4 * q + 2] += v[2]; gu[4 * q + 3] += v[3];
         }
-        store_frag8(Xf, MT, r, g * 8, y);
     }
+    float y[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float a = gu[2 * e];
+        y[e] = a / (1.0f + __expf(-a)) * gu[2 * e + 1];
+    }
+    f32x4 *dst = (f32x4 *)(act + (size_t)r * F + g * 8);
+    dst[0] = (f32x4){y[0], y[1], y[2], y[3]};
+    dst[1] = (f32x4){y[4], y[5], y[6], y[7]};
 }
 
 // Medusa residual block: x += SiLU(sum of partials)
@@ -293,6 +324,96 @@ __global__ void k_reduce_out(const float *P, int S, int Mp, int ldp, float *out,
     if (i >= (size_t)M * N) return;
     const int r = (int)(i / N), j = (int)(i % N);
     out[(size_t)r * ldo + j] = psum(P, S, Mp, ldp, r, j);
+}
+
+// ---------------------------------------------------------------------------------------------
+// LM-head epilogue: fold the split-K partials into logits and take the k largest per row
+// (descending value, equal values by ascending index) in two stages.
+// Stage 1, grid (ceil(V/1024), rows): each block reduces 1024 columns, optionally stores the
+// logits, and emits its own k best.  Stage 2, grid (rows): merges the blocks' candidates.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
+    return v > bv || (v == bv && i < bi);
+}
+
+// block-wide arg-best over (v, i); every thread gets the winner.  4 waves.
+__device__ __forceinline__ void block_best(float &v, int &i, float *sv, int *si) {
+    for (int o = 32; o > 0; o >>= 1) {
+        const float v2 = __shfl_xor(v, o);
+        const int i2 = __shfl_xor(i, o);
+        if (better(v2, i2, v, i)) { v = v2; i = i2; }
+    }
+    __syncthreads();   // previous round's readers are done with sv/si
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = v; si[threadIdx.x >> 6] = i; }
+    __syncthreads();
+    v = sv[0]; i = si[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w)
+        if (better(sv[w], si[w], v, i)) { v = sv[w]; i = si[w]; }
+}
+
+__global__ __launch_bounds__(256) void k_topk_stage1(const float *P, int S, int Mp, int ldp, float *logits, int ldl,
+                                                     int V, int k, float *cand_val, int *cand_idx) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x, j0 = c * 1024 + tid * 4;
+    float val[4] = {0.f, 0.f, 0.f, 0.f};
+    if (j0 < V) {   // ldp is a multiple of 64 and j0 of 4: the four columns exist in P even past V
+        for (int s = 0; s < S; ++s) {
+            const f32x4 v = *(const f32x4 *)(P + ((size_t)s * Mp + r) * ldp + j0);
+            val[0] += v[0]; val[1] += v[1]; val[2] += v[2]; val[3] += v[3];
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (j0 + q >= V) val[q] = -INFINITY;
+        else if (logits) logits[(size_t)r * ldl + j0 + q] = val[q];
+    }
+    unsigned taken = 0;
+    for (int it = 0; it < k; ++it) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (!((taken >> q) & 1u) && j0 + q < V && better(val[q], j0 + q, bv, bi)) { bv = val[q]; bi = j0 + q; }
+        block_best(bv, bi, sv, si);
+        if (bi >= j0 && bi < j0 + 4) taken |= 1u << (bi - j0);
+        if (tid == 0) {
+            cand_val[((size_t)r * gridDim.x + c) * k + it] = bv;
+            cand_idx[((size_t)r * gridDim.x + c) * k + it] = bi;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_topk_stage2(const float *cand_val, const int *cand_idx, int n_cand, int k,
+                                                     int32_t *idx, float *val) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    // each thread owns candidates tid, tid+256, ... (at most 4: n_cand <= 1024)
+    float cv[4];
+    int ci[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int a = tid + 256 * q;
+        cv[q] = a < n_cand ? cand_val[(size_t)r * n_cand + a] : -INFINITY;
+        ci[q] = a < n_cand ? cand_idx[(size_t)r * n_cand + a] : 0x7fffffff;
+    }
+    for (int it = 0; it < k; ++it) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (ci[q] != 0x7fffffff && better(cv[q], ci[q], bv, bi)) { bv = cv[q]; bi = ci[q]; }
+        block_best(bv, bi, sv, si);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (ci[q] == bi) ci[q] = 0x7fffffff;   // token ids are unique among the candidates
+        if (tid == 0) {
+            idx[(size_t)r * k + it] = bi;
+            if (val) val[(size_t)r * k + it] = bv;
+        }
+    }
 }
 
 inline int cdiv(size_t a, size_t b) { return (int)((a + b - 1) / b); }
@@ -315,19 +436,21 @@ int gemm_splits(int Npad, int K) {
 
 static bool g_attr_done[3] = {false, false, false};
 
-void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S) {
+void gemm_packed(hipStream_t st, const void *Wp, const GemmX &gx, float *P, int Npad, int K, int MTT, int S) {
     const int nwb = (Npad / 64 + 3) / 4;
     const dim3 grid(nwb * S);
+    XSrc xs;
+    xs.x = gx.x; xs.ldx = gx.ldx; xs.M = gx.M; xs.sums = gx.sums; xs.nparts = gx.nparts; xs.srows = gx.srows;
+    xs.gain = (const bf16_t *)gx.gain; xs.eps = gx.eps;
 #define KOALA_GEMM(MTV, IDX)                                                                                     \
     {                                                                                                            \
-        const size_t sm = (size_t)2 * 4 * MTV * 2 * 64 * 16;                                                     \
+        const size_t sm = (size_t)2 * 4 * MTV * 2 * 64 * 16 + 64 * sizeof(float);                                \
         if (!g_attr_done[IDX]) {                                                                                 \
             (void)hipFuncSetAttribute((const void *)k_gemm_packed<MTV>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                       (int)sm);                                                                  \
             g_attr_done[IDX] = true;                                                                             \
         }                                                                                                        \
-        k_gemm_packed<MTV><<<grid, 256, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, S, nwb, MTT, \
-                                                  mt0);                                                          \
+        k_gemm_packed<MTV><<<grid, 256, sm, st>>>((const u32x4 *)Wp, xs, P, Npad, K, S, nwb, MTT * 16, mt0);     \
     }
     // MTT is 1, 2 or a multiple of 4: groups of at most four activation tiles per launch
     for (int mt0 = 0; mt0 < MTT; mt0 += 4) {
@@ -339,11 +462,9 @@ void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int N
 #undef KOALA_GEMM
 }
 
-void prep_rows(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp_in, int ldp, int mode_in,
-               const void *gain, float eps, float *out32, int ldo, void *Xf, int MT, int M, int K) {
-    const int blocks = Xf ? MT * 16 : M;
-    k_prep_rows<<<blocks, 256, 0, st>>>(x, ldx, P, S, Mp_in, ldp, mode_in, (const bf16_t *)gain, eps, out32, ldo,
-                                        (u32x4 *)Xf, MT, M, K);
+void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,
+          float *sums, int srows) {
+    k_fold<<<dim3((N + 255) / 256, M), 256, 0, st>>>(x, ldx, P, S, Mp, ldp, mode, N, sums, srows);
 }
 
 void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const RowMeta &meta, float *qrot,
@@ -352,18 +473,26 @@ void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const R
                                                                   (bf16_t *)vc, H, n_heads, head_dim, cap);
 }
 
-void attn_combine_frag(hipStream_t st, const float *o_part, const float *ml, void *Xf, int MT, int M, int n_heads,
-                       int nsplit, int head_dim) {
-    k_attn_combine_frag<<<MT * 16, 256, 0, st>>>(o_part, ml, (u32x4 *)Xf, MT, M, n_heads, nsplit, head_dim,
-                                                 n_heads * head_dim);
+void attn_combine(hipStream_t st, const float *o_part, const float *ml, float *out, int M, int n_heads, int nsplit,
+                  int head_dim) {
+    const int H = n_heads * head_dim;
+    k_attn_combine<<<dim3((H / 8 + 63) / 64, M), 64, 0, st>>>(o_part, ml, out, n_heads, nsplit, head_dim, H);
 }
 
-void silu_frag(hipStream_t st, const float *P, int S, int Mp, int ldp, void *Xf, int MT, int M, int F) {
-    k_silu_frag<<<MT * 16, 256, 0, st>>>(P, S, Mp, ldp, (u32x4 *)Xf, MT, M, F);
+void silu_p(hipStream_t st, const float *P, int S, int Mp, int ldp, float *act, int M, int F) {
+    k_silu_p<<<dim3((F / 8 + 63) / 64, M), 64, 0, st>>>(P, S, Mp, ldp, act, F);
 }
 
 void resblock_p(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int M, int H) {
     k_resblock_p<<<cdiv((size_t)M * H, 256), 256, 0, st>>>(x, ldx, P, S, Mp, ldp, M, H);
+}
+
+// cand buffers: rows * ceil(V/1024) * k entries each
+void logits_topk(hipStream_t st, const float *P, int S, int Mp, int ldp, float *logits, int ldl, int rows, int V,
+                 int k, float *cand_val, int *cand_idx, int32_t *idx, float *val) {
+    const int nchunk = (V + 1023) / 1024;
+    k_topk_stage1<<<dim3(nchunk, rows), 256, 0, st>>>(P, S, Mp, ldp, logits, ldl, V, k, cand_val, cand_idx);
+    k_topk_stage2<<<rows, 256, 0, st>>>(cand_val, cand_idx, nchunk * k, k, idx, val);
 }
 
 void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *out, int ldo, int M, int N) {

@@ -75,19 +75,19 @@ size_t carve(koala_ctx *c, char *base) {
     c->topk_val = w.take<float>((size_t)R * KOALA_TOPK_MAX);
     c->topk_idx = w.take<int32_t>((size_t)R * KOALA_TOPK_MAX);
     c->tok_tmp = w.take<int32_t>(R);
-    c->xf = nullptr;
     c->part = nullptr;
-    c->xf_bytes = c->part_bytes = 0;
+    c->part_bytes = 0;
     if (s.dtype == KOALA_BF16) {
         const int MTmax = kb::mt_of(R);
-        c->xf_bytes = kb::xf_bytes(std::max(2 * H, F), MTmax);
         const int shapes[6][2] = {{3 * H, H}, {H, H}, {2 * F, H}, {H, F}, {kb::pad64(V), H}, {H, 2 * H}};
         size_t worst = 0;
         for (auto &sh : shapes)
             worst = std::max(worst, (size_t)kb::gemm_splits(kb::pad64(sh[0]), sh[1]) * kb::pad64(sh[0]));
         c->part_bytes = worst * MTmax * 16 * sizeof(float);
-        c->xf = w.take<char>(c->xf_bytes);
         c->part = w.take<float>(c->part_bytes / sizeof(float));
+        c->row_sums = w.take<float>((size_t)R * 128);
+        c->cand_val = w.take<float>((size_t)R * ((V + 1023) / 1024) * KOALA_TOPK_MAX);
+        c->cand_idx = w.take<int>((size_t)R * ((V + 1023) / 1024) * KOALA_TOPK_MAX);
     }
     return w.off;
 }
@@ -116,12 +116,12 @@ void decoder_layer(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, co
     kg::gemm(st, bf, c->act, F, lw[5], c->x, H, rows, H, F, true);
 }
 
-// Split-K GEMM on the fragment buffer: partial sums of X * W^T into c->part; returns the split count.
-int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) {
+// Split-K GEMM: partial sums of X * W^T into c->part; returns the split count.
+int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT, const kb::GemmX &gx) {
     const int Npad = kb::pad64(N), S = kb::gemm_splits(Npad, K);
     const bool timed = c->prof_on && (size_t)(c->prof_used + 2) <= c->prof_ev.size();
     if (timed) (void)hipEventRecord(c->prof_ev[c->prof_used], st);
-    kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S);
+    kb::gemm_packed(st, Wp, gx, c->part, Npad, K, MT, S);
     if (timed) {
         (void)hipEventRecord(c->prof_ev[c->prof_used + 1], st);
         c->prof_used += 2;
@@ -130,40 +130,53 @@ int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) 
     return S;
 }
 
-// bf16 decoder layer.  On entry c->pend_* may describe partial sums (of the previous down
-// projection or of the EAGLE fc) still to be folded into x; on exit the down projection's are pending.
+kb::GemmX plain_x(const float *x, int ldx, int M) { return kb::GemmX{x, ldx, M, nullptr, 0, 0, nullptr, 0.f}; }
+
+kb::GemmX normed_x(const koala_ctx *c, const float *x, int M, const void *gain) {
+    const int H = c->shape.hidden;
+    return kb::GemmX{x, H, M, c->row_sums, (H + 255) / 256, c->max_rows, gain, c->shape.rms_eps};
+}
+
+// Folds the pending partial sums (of a down projection or of the EAGLE fc) into c->x and leaves the
+// chunk sums of squares for the RMSNorm of the next GEMM.  mode 0 if nothing is pending.
+void fold_pending(koala_ctx *c, hipStream_t st, int rows, int Mp, bool want_sums) {
+    const int H = c->shape.hidden;
+    kb::fold(st, c->x, H, c->part, c->pend_S, Mp, c->pend_ld, c->pend_S ? c->pend_mode : 0, rows, H,
+             want_sums ? c->row_sums : nullptr, c->max_rows);
+    c->pend_S = 0;
+}
+
+// bf16 decoder layer.  On entry c->pend_* may describe partial sums still to be folded into x; on exit
+// the down projection's are pending.
 void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, const void *const *lw,
                         void *kc, void *vc) {
     const koala_shape &s = c->shape;
     const int rows = batch * rows_per_seq, H = s.hidden, F = s.ffn, MT = kb::mt_of(rows), Mp = MT * 16;
     const int ns = attn_nsplit(c);
-    kb::prep_rows(st, c->x, H, c->part, c->pend_S, Mp, c->pend_ld, c->pend_S ? c->pend_mode : 0, lw[0], s.rms_eps,
-                  nullptr, 0, c->xf, MT, rows, H);
-    int S = bf_gemm(c, st, lw[1], 3 * H, H, MT);
+    fold_pending(c, st, rows, Mp, true);
+    int S = bf_gemm(c, st, lw[1], 3 * H, H, MT, normed_x(c, c->x, rows, lw[0]));
     kb::rope_append(st, c->part, S, Mp, 3 * H, c->meta, c->qrot, kc, vc, rows, H, s.n_heads, s.head_dim,
                     c->kv.capacity);
     kb::attention_mfma(st, c->qrot, c->meta, kc, vc, c->o_part, c->ml, batch, rows_per_seq, s.n_heads, s.head_dim,
                        c->kv.capacity, ns);
-    kb::attn_combine_frag(st, c->o_part, c->ml, c->xf, MT, rows, s.n_heads, ns, s.head_dim);
-    S = bf_gemm(c, st, lw[2], H, H, MT);
-    kb::prep_rows(st, c->x, H, c->part, S, Mp, H, 1, lw[3], s.rms_eps, nullptr, 0, c->xf, MT, rows, H);
-    S = bf_gemm(c, st, lw[4], 2 * F, H, MT);
-    kb::silu_frag(st, c->part, S, Mp, 2 * F, c->xf, MT, rows, F);
-    S = bf_gemm(c, st, lw[5], H, F, MT);
+    kb::attn_combine(st, c->o_part, c->ml, c->attn_out, rows, s.n_heads, ns, s.head_dim);
+    S = bf_gemm(c, st, lw[2], H, H, MT, plain_x(c->attn_out, H, rows));
+    kb::fold(st, c->x, H, c->part, S, Mp, H, 1, rows, H, c->row_sums, c->max_rows);
+    S = bf_gemm(c, st, lw[4], 2 * F, H, MT, normed_x(c, c->x, rows, lw[3]));
+    kb::silu_p(st, c->part, S, Mp, 2 * F, c->act, rows, F);
+    S = bf_gemm(c, st, lw[5], H, F, MT, plain_x(c->act, F, rows));
     c->pend_S = S;
     c->pend_ld = H;
     c->pend_mode = 1;
 }
 
-// logits of `rows` rows whose fp32 inputs are at a[r*lda ..]: fragments -> LM head -> reduce -> top-k
-void bf_lm_head_topk(koala_ctx *c, hipStream_t st, float *a, int lda, int rows, float *logits, int k,
-                     int32_t *idx, float *val) {
+// logits of `rows` fp32 rows at a (row stride lda): LM head -> fold -> top-k
+void bf_lm_head_topk(koala_ctx *c, hipStream_t st, const float *a, int lda, int rows, int k, int32_t *idx,
+                     float *val) {
     const koala_shape &s = c->shape;
     const int MT = kb::mt_of(rows), Vp = kb::pad64(s.vocab);
-    kb::prep_rows(st, a, lda, nullptr, 0, 0, 0, 0, nullptr, 0.f, nullptr, 0, c->xf, MT, rows, s.hidden);
-    const int S = bf_gemm(c, st, c->w.lm_head, s.vocab, s.hidden, MT);
-    kb::reduce_out(st, c->part, S, MT * 16, Vp, logits, s.vocab, rows, s.vocab);
-    kg::topk_rows(st, logits, s.vocab, rows, s.vocab, k, idx, val);
+    const int S = bf_gemm(c, st, c->w.lm_head, s.vocab, s.hidden, MT, plain_x(a, lda, rows));
+    kb::logits_topk(st, c->part, S, MT * 16, Vp, nullptr, 0, rows, s.vocab, k, c->cand_val, c->cand_idx, idx, val);
 }
 
 size_t elt(const koala_ctx *c) { return c->shape.dtype == KOALA_BF16 ? 2 : 4; }
@@ -196,7 +209,7 @@ koala_status koala_create(const koala_shape *shape, const koala_draft_shape *dra
         return KOALA_E_SHAPE;
     if (s.dtype != KOALA_FP32 && s.dtype != KOALA_BF16) return KOALA_E_UNSUPPORTED;
     if (s.head_dim != 64 && s.head_dim != 128) return KOALA_E_UNSUPPORTED;
-    if (s.dtype == KOALA_BF16 && (s.hidden % 128 || s.ffn % 128)) return KOALA_E_UNSUPPORTED;
+    if (s.dtype == KOALA_BF16 && (s.hidden % 128 || s.ffn % 128 || s.vocab > 65536)) return KOALA_E_UNSUPPORTED;
     if (draft->kind != KOALA_DRAFT_EAGLE && draft->kind != KOALA_DRAFT_MEDUSA) return KOALA_E_UNSUPPORTED;
     if (draft->K < 1 || draft->max_m < 1 || draft->max_m > KOALA_MAX_M) return KOALA_E_SHAPE;
     const int T = tree->n_nodes, D = tree->depth;
@@ -353,13 +366,12 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
         for (int l = 0; l < s.n_layers; ++l)
             decoder_layer_bf16(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,
                                (char *)c->kv.target_v + ls * l);
-        // last down projection folded in, final RMSNorm -> features (fp32) and fragments for the LM head
-        kb::prep_rows(st, c->x, H, c->part, c->pend_S, Mp, c->pend_ld, 1, c->w.final_norm, s.rms_eps, feat_out, H,
-                      c->xf, MT, rows, H);
-        c->pend_S = 0;
-        const int S = bf_gemm(c, st, c->w.lm_head, V, H, MT);
-        kb::reduce_out(st, c->part, S, Mp, kb::pad64(V), logits, V, rows, V);
-        kg::topk_rows(st, logits, V, rows, V, 1, greedy_out, nullptr);
+        // last down projection folded in, final RMSNorm -> features, LM head, greedy ids
+        fold_pending(c, st, rows, Mp, false);
+        kg::rmsnorm(st, true, c->x, c->w.final_norm, feat_out, rows, H, s.rms_eps);
+        const int S = bf_gemm(c, st, c->w.lm_head, V, H, MT, plain_x(feat_out, H, rows));
+        kb::logits_topk(st, c->part, S, Mp, kb::pad64(V), logits_out, V, rows, V, 1, c->cand_val, c->cand_idx,
+                        greedy_out, nullptr);
         KOALA_CHECK_LAUNCH(c);
         return KOALA_OK;
     }
@@ -398,8 +410,7 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
             for (int k = 0; k < K; ++k) {
                 if (bf) {
                     const int MT = kb::mt_of(batch);
-                    kb::prep_rows(st, xj, H, nullptr, 0, 0, 0, 0, nullptr, 0.f, nullptr, 0, c->xf, MT, batch, H);
-                    const int S = bf_gemm(c, st, c->w.draft_w[j * K + k], H, H, MT);
+                    const int S = bf_gemm(c, st, c->w.draft_w[j * K + k], H, H, MT, plain_x(xj, H, batch));
                     kb::resblock_p(st, xj, H, c->part, S, MT * 16, H, batch, H);
                 } else {
                     kg::gemm(st, bf, xj, H, c->w.draft_w[j * K + k], c->gu, H, batch, H, H, false);
@@ -409,7 +420,7 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
         }
         if (D > 0) {
             if (bf) {
-                bf_lm_head_topk(c, st, c->x, H, D * batch, c->logits, kmax, c->topk_idx, c->topk_val);
+                bf_lm_head_topk(c, st, c->x, H, D * batch, kmax, c->topk_idx, c->topk_val);
             } else {
                 kg::gemm(st, bf, c->x, H, c->w.lm_head, c->logits, V, D * batch, V, H, false);
                 kg::topk_rows(st, c->logits, V, D * batch, V, kmax, c->topk_idx, c->topk_val);
@@ -427,16 +438,13 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
         const int rows = batch * rows_per_seq;
         if (bf) {
             const int MT = kb::mt_of(rows), Mp = MT * 16;
-            kb::prep_rows(st, c->act, 2 * H, nullptr, 0, 0, 0, 0, nullptr, 0.f, nullptr, 0, c->xf, MT, rows, 2 * H);
-            c->pend_S = bf_gemm(c, st, c->w.fc, H, 2 * H, MT);
+            c->pend_S = bf_gemm(c, st, c->w.fc, H, 2 * H, MT, plain_x(c->act, 2 * H, rows));
             c->pend_ld = H;
             c->pend_mode = 2;
             for (int k = 0; k < K; ++k)
                 decoder_layer_bf16(c, st, batch, rows_per_seq, c->w.draft_w + 6 * k, (char *)c->kv.draft_k + ls * k,
                                    (char *)c->kv.draft_v + ls * k);
-            kb::prep_rows(st, c->x, H, c->part, c->pend_S, Mp, c->pend_ld, c->pend_mode, nullptr, 0.f, nullptr, 0,
-                          nullptr, MT, rows, H);
-            c->pend_S = 0;
+            fold_pending(c, st, rows, Mp, false);
         } else {
             kg::gemm(st, bf, c->act, 2 * H, c->w.fc, c->x, H, rows, H, 2 * H, false);
             for (int k = 0; k < K; ++k)
@@ -447,7 +455,7 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
     // LM head + top-k on `rows` fp32 rows at a (row stride lda)
     auto head_topk = [&](float *a, int lda, int rows, int k) {
         if (bf) {
-            bf_lm_head_topk(c, st, a, lda, rows, c->logits, k, c->topk_idx, c->topk_val);
+            bf_lm_head_topk(c, st, a, lda, rows, k, c->topk_idx, c->topk_val);
         } else {
             kg::gemm(st, bf, a, lda, c->w.lm_head, c->logits, V, rows, V, H, false);
             kg::topk_rows(st, c->logits, V, rows, V, k, c->topk_idx, c->topk_val);
