@@ -5,9 +5,10 @@
 // stream out of HBM.  The kernels here are built around that:
 //   * weights are stored fragment-major (see koala.h): one wave load instruction reads 1 KiB of
 //     contiguous memory and lands exactly in the A operand of a 16x16x32 bf16 MFMA;
-//   * activations stay fp32 in memory; the GEMM splits them into bf16 hi + lo parts
-//     (x = hi + lo to ~16 mantissa bits) while staging them in LDS, applying RMSNorm on the way,
-//     so results stay at fp32-class accuracy while using the bf16 MFMA;
+//   * GEMM inputs are written by their producers as bf16 hi + lo parts (x = hi + lo to ~16
+//     mantissa bits) in MFMA fragment order, so results stay at fp32-class accuracy on the bf16
+//     MFMA; RMSNorm is split into the gain (applied by the producer) and the row scale (applied by
+//     whoever consumes the GEMM result), since the GEMM is linear in the row scale;
 //   * K is split over workgroups; partial sums go to a scratch buffer that the consumer
 //     kernel adds up in a fixed order (deterministic, no float atomics).
 #include "koala_internal.h"
@@ -28,30 +29,19 @@ __device__ __forceinline__ uint32_t f2bf(float v) {  // round to nearest even
 // ---------------------------------------------------------------------------------------------
 // Packed GEMM.  Wp: [Npad/64][K/64] tiles of 64 rows x 64 k, each tile = 8 fragments
 // (t = row/16, s = k/32) of 64 lanes x 16 B; lane = (row%16) + 16*((k%32)/8).
-// X:  fp32 rows [M][ldx] (rows >= M count as zero), optionally RMS-normalised on the fly:
-//     x * inv_rms(row) * gain[k], inv_rms from the per-chunk sums of squares a fold kernel left.
-//     While a 128-k chunk of weights streams, the workgroup converts the next chunk of X to
-//     bf16 hi + lo fragments (B operands) in LDS; a launch handles the MT activation tiles
-//     mt0 .. mt0+MT-1 (16 rows each).
-// P:  [S][Mp][Npad] fp32 partial sums; split sp covers 128-k chunks [sp*nch/S, (sp+1)*nch/S).
-// Workgroup = 4 waves; wave w owns row block wb*4 + w (64 weight rows).
+// Xf: [K/32][MTT][hi,lo][64 lanes] x 16 B; lane = (m%16) + 16*((k%32)/8); a launch handles the MT
+//     activation tiles mt0 .. mt0+MT-1 of the MTT present.
+// P:  [S][MTT*16][Npad] fp32 partial sums; split sp covers 128-k chunks [sp*nch/S, (sp+1)*nch/S).
+// Workgroup = 4 waves; wave w owns row block wb*4 + w (64 rows); the X chunk is shared in LDS.
 // ---------------------------------------------------------------------------------------------
-struct XSrc {
-    const float *x;       // activations
-    int ldx, M;
-    const float *sums;    // [nparts][srows] sums of squares per 256-column chunk, or nullptr: no normalisation
-    int nparts, srows;
-    const bf16_t *gain;   // RMSNorm gain [K] (with sums)
-    float eps;
-};
-
 template <int MT>
-__global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ Wp, XSrc xs_, float *__restrict__ P,
-                                                     int Npad, int K, int S, int nwb, int Mp, int mt0) {
-    extern __shared__ u32x4 xs[];            // [2][XCH] then inv_rms[64]
-    constexpr int XCH = 4 * MT * 2 * 64;     // 16-byte units of X fragments per 128-k chunk
-    float *inv_s = (float *)(xs + 2 * XCH);
-    const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, li = l & 15, lg = l >> 4;
+__global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
+                                                     float *__restrict__ P, int Npad, int K, int S, int nwb,
+                                                     int MTT, int mt0) {
+    extern __shared__ u32x4 xs[];            // [2][XCH]
+    constexpr int XCH = 4 * MT * 2 * 64;     // 16-byte units of X per 128-k chunk
+    constexpr int XPT = XCH / 256;           // per thread
+    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
     const int wb = blockIdx.x % nwb, sp = blockIdx.x / nwb;
     const int nch = K / 128;
     const int c_begin = (int)((long long)sp * nch / S), c_end = (int)((long long)(sp + 1) * nch / S);
@@ -59,96 +49,36 @@ __global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ W
     const int rb = wb * 4 + wave;
     const bool active = rb < Npad / 64;
     const u32x4 *wsrc = Wp + ((size_t)(active ? rb : 0) * (K / 64) + (size_t)c_begin * 2) * 512 + l;
-    const bool norm = xs_.sums != nullptr;
-
-    // fragment piece q = tid + 256*i (i < MT): k-step ksl, tile mt, lane pl -> row, 8 consecutive k
-    int p_row[MT], p_koff[MT], p_dst[MT];
-    bool p_ok[MT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        const int q = tid + 256 * i, ksl = q / (MT * 64), rem = q % (MT * 64), mt = rem / 64, pl = rem % 64;
-        p_row[i] = (mt0 + mt) * 16 + (pl & 15);
-        p_koff[i] = ksl * 32 + 8 * (pl >> 4);
-        p_dst[i] = (ksl * MT * 2 + mt * 2) * 64 + pl;
-        p_ok[i] = p_row[i] < xs_.M;
-    }
-    if (norm) {
-        if (tid < MT * 16) {   // rows of this launch: mt0*16 + tid
-            const int row = mt0 * 16 + tid;
-            float tot = 0.f;
-            if (row < xs_.M)
-                for (int c = 0; c < xs_.nparts; ++c) tot += xs_.sums[(size_t)c * xs_.srows + row];
-            inv_s[tid] = 1.0f / sqrtf(tot / (float)K + xs_.eps);
-        }
-        __syncthreads();
-    }
-    float xr[MT][8];
-    auto xload = [&](int c) {
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            if (p_ok[i]) {
-                const float *src = xs_.x + (size_t)p_row[i] * xs_.ldx + (size_t)(c_begin + c) * 128 + p_koff[i];
-                const f32x4 a = *(const f32x4 *)src, b = *(const f32x4 *)(src + 4);
-                xr[i][0] = a[0]; xr[i][1] = a[1]; xr[i][2] = a[2]; xr[i][3] = a[3];
-                xr[i][4] = b[0]; xr[i][5] = b[1]; xr[i][6] = b[2]; xr[i][7] = b[3];
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) xr[i][e] = 0.f;
-            }
-        }
-    };
-    auto xstore = [&](int c, u32x4 *dst) {
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            float y[8];
-            if (norm && p_ok[i]) {
-                const float sc = inv_s[p_row[i] - mt0 * 16];
-                const u32x4 g = *(const u32x4 *)(xs_.gain + (size_t)(c_begin + c) * 128 + p_koff[i]);
-                const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    y[e] = xr[i][e] * sc * bf2f((e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu));
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) y[e] = xr[i][e];
-            }
-            uint32_t hi[8], lo[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                hi[e] = f2bf(y[e]);
-                lo[e] = f2bf(y[e] - bf2f(hi[e]));
-            }
-            u32x4 h, w;
-            h.x = hi[0] | (hi[1] << 16); h.y = hi[2] | (hi[3] << 16); h.z = hi[4] | (hi[5] << 16); h.w = hi[6] | (hi[7] << 16);
-            w.x = lo[0] | (lo[1] << 16); w.y = lo[2] | (lo[3] << 16); w.z = lo[4] | (lo[5] << 16); w.w = lo[6] | (lo[7] << 16);
-            dst[p_dst[i]] = h;
-            dst[p_dst[i] + 64] = w;
-        }
-    };
-
+    // 16-byte unit u of chunk c lives at xsrc + (c*4 + u / (MT*128)) * MTT*128 + u % (MT*128)
+    const u32x4 *xsrc = Xf + (size_t)c_begin * 4 * MTT * 128 + (size_t)mt0 * 128;
+    auto xaddr = [&](int c, int u) { return xsrc + ((size_t)c * 4 + u / (MT * 128)) * (MTT * 128) + u % (MT * 128); };
     f32x4 acc[4][MT];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[t][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
     u32x4 wr[2][8];
+    u32x4 xr[XPT];
     const int nb = nchunks * 2;
     auto wload = [&](int b, int slot) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) wr[slot][j] = __builtin_nontemporal_load(wsrc + (size_t)b * 512 + j * 64);
     };
     if (nchunks > 0) {
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) xs[threadIdx.x + 256 * i] = *xaddr(0, threadIdx.x + 256 * i);
         if (active) {
             wload(0, 0);
             wload(1, 1);
         }
-        xload(0);
-        xstore(0, xs);
     }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
         const bool more = c + 1 < nchunks;
-        if (more) xload(c + 1);
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < XPT; ++i) xr[i] = *xaddr(c + 1, threadIdx.x + 256 * i);
+        }
         const u32x4 *xc = xs + (c & 1) * XCH;
         if (active) {
 #pragma unroll
@@ -179,7 +109,11 @@ __global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ W
                 }
             }
         }
-        if (more) xstore(c + 1, xs + ((c + 1) & 1) * XCH);
+        if (more) {
+            u32x4 *xn = xs + ((c + 1) & 1) * XCH;
+#pragma unroll
+            for (int i = 0; i < XPT; ++i) xn[threadIdx.x + 256 * i] = xr[i];
+        }
         __syncthreads();
     }
     if (active) {
@@ -188,7 +122,7 @@ __global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ W
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
                 const int row = (mt0 + m) * 16 + li, n = rb * 64 + 16 * t + 4 * lg;
-                *(f32x4 *)(P + ((size_t)sp * Mp + row) * Npad + n) = acc[t][m];
+                *(f32x4 *)(P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = acc[t][m];
             }
     }
 }
@@ -209,43 +143,117 @@ __device__ __forceinline__ float psum(const float *P, int S, int Mp, int ld, int
     return (v0 + v1) + (v2 + v3);
 }
 
+// 8 consecutive columns (col % 8 == 0) of the summed partials of a row; splits are read four at a
+// time so that eight loads are in flight, and added in a fixed order
+__device__ __forceinline__ void psum8(const float *P, int S, int Mp, int ld, int row, int col, float *v) {
+    const f32x4 *src = (const f32x4 *)(P + (size_t)row * ld + col);
+    const size_t stride = (size_t)Mp * ld / 4;   // in f32x4 units
+    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {
+        const f32x4 a0 = src[(size_t)s * stride], b0 = src[(size_t)s * stride + 1];
+        const f32x4 a1 = src[(size_t)(s + 1) * stride], b1 = src[(size_t)(s + 1) * stride + 1];
+        const f32x4 a2 = src[(size_t)(s + 2) * stride], b2 = src[(size_t)(s + 2) * stride + 1];
+        const f32x4 a3 = src[(size_t)(s + 3) * stride], b3 = src[(size_t)(s + 3) * stride + 1];
+        lo += (a0 + a1) + (a2 + a3);
+        hi += (b0 + b1) + (b2 + b3);
+    }
+    for (; s < S; ++s) {
+        lo += src[(size_t)s * stride];
+        hi += src[(size_t)s * stride + 1];
+    }
+    v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
+    v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+}
+
+// store 8 consecutive k of row m (k0 % 8 == 0) as hi/lo fragments
+__device__ __forceinline__ void store_frag8(u32x4 *Xf, int MT, int m, int k0, const float *y) {
+    uint32_t hi[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        hi[e] = f2bf(y[e]);
+        lo[e] = f2bf(y[e] - bf2f(hi[e]));
+    }
+    const int ks = k0 >> 5, lane = (m & 15) + 16 * ((k0 & 31) >> 3), mt = m >> 4;
+    u32x4 h, w;
+    h.x = hi[0] | (hi[1] << 16); h.y = hi[2] | (hi[3] << 16); h.z = hi[4] | (hi[5] << 16); h.w = hi[6] | (hi[7] << 16);
+    w.x = lo[0] | (lo[1] << 16); w.y = lo[2] | (lo[3] << 16); w.z = lo[4] | (lo[5] << 16); w.w = lo[6] | (lo[7] << 16);
+    u32x4 *dst = Xf + ((size_t)(ks * MT + mt) * 2) * 64 + lane;
+    dst[0] = h;
+    dst[64] = w;
+}
+
+// RMSNorm row scale from the per-chunk sums of squares a fold left: 1/sqrt(mean(x^2) + eps).
+// sums == nullptr: no normalisation pending, scale 1.
+struct RowScale {
+    const float *sums;   // [nparts][srows]
+    int nparts, srows, K;
+    float eps;
+};
+__device__ __forceinline__ float row_scale(const RowScale &rs, int row) {
+    if (!rs.sums) return 1.f;
+    float tot = 0.f;
+    for (int c = 0; c < rs.nparts; ++c) tot += rs.sums[(size_t)c * rs.srows + row];
+    return 1.0f / sqrtf(tot / (float)rs.K + rs.eps);
+}
+
 // ---------------------------------------------------------------------------------------------
-// Fold: x[m][j] = (mode 1: x +) sum of partials (mode 0: x unchanged), and the sum of squares of
-// each 256-column chunk of the result to sums[chunk][m] for the RMSNorm of the next GEMM.
-// grid (ceil(N/256), M).
+// Fold: v = (mode 1: x +) sum of partials (mode 0: x as is); x <- v (modes 1, 2); optionally the
+// hi/lo fragments of gain * v (gain == nullptr: of v) for the next GEMM, and the sum of squares of
+// each 512-column chunk to sums[chunk][m].  RMSNorm is linear in the row scale, so the GEMM runs
+// on gain * v and its consumer multiplies by row_scale().  grid (ceil(N/512), M), 64 threads x 8 cols.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_fold(float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode,
-                                              int N, float *sums, int srows) {
-    __shared__ float red[4];
-    const int c = blockIdx.x, m = blockIdx.y, tid = threadIdx.x, j = c * 256 + tid;
-    float v = 0.f;
+__global__ __launch_bounds__(64) void k_fold(float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode,
+                                             int N, const bf16_t *gain, u32x4 *Xf, int MT, float *sums, int srows) {
+    const int c = blockIdx.x, m = blockIdx.y, j = (c * 64 + threadIdx.x) * 8;
+    float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (j < N) {
-        if (mode == 0) v = x[(size_t)m * ldx + j];
-        else {
-            v = psum(P, S, Mp, ldp, m, j);
-            if (mode == 1) v += x[(size_t)m * ldx + j];
-            x[(size_t)m * ldx + j] = v;
+        float *xr = x + (size_t)m * ldx + j;
+        if (mode != 0) psum8(P, S, Mp, ldp, m, j, v);
+        if (mode != 2) {
+            const f32x4 a = *(const f32x4 *)xr, b = *(const f32x4 *)(xr + 4);
+            v[0] += a[0]; v[1] += a[1]; v[2] += a[2]; v[3] += a[3];
+            v[4] += b[0]; v[5] += b[1]; v[6] += b[2]; v[7] += b[3];
+        }
+        if (mode != 0) {
+            *(f32x4 *)xr = (f32x4){v[0], v[1], v[2], v[3]};
+            *(f32x4 *)(xr + 4) = (f32x4){v[4], v[5], v[6], v[7]};
+        }
+        if (Xf) {
+            float y[8];
+            if (gain) {
+                const u32x4 g = *(const u32x4 *)(gain + j);
+                const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) y[e] = v[e] * bf2f((e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) y[e] = v[e];
+            }
+            store_frag8(Xf, MT, m, j, y);
         }
     }
     if (!sums) return;
-    float ss = v * v;
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
-    __syncthreads();
-    if (tid == 0) sums[(size_t)c * srows + m] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (threadIdx.x == 0) sums[(size_t)c * srows + m] = ss;
 }
 
 // ---------------------------------------------------------------------------------------------
 // RoPE + KV append from the QKV partials.  grid (rows, n_heads), block head_dim/2.
 // ---------------------------------------------------------------------------------------------
-__global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowMeta meta, float *qrot, bf16_t *kc,
-                                bf16_t *vc, int H, int n_heads, int DH, int cap) {
+__global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowScale rs, RowMeta meta, float *qrot,
+                                bf16_t *kc, bf16_t *vc, int H, int n_heads, int DH, int cap) {
     const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x, half = DH / 2;
     const int b = meta.row_b[r], slot = meta.row_slot[r];
     const float c = meta.rope_cos[(size_t)r * half + i], s = meta.rope_sin[(size_t)r * half + i];
-    const float q0 = psum(P, S, Mp, ldp, r, h * DH + i), q1 = psum(P, S, Mp, ldp, r, h * DH + half + i);
-    const float k0 = psum(P, S, Mp, ldp, r, H + h * DH + i), k1 = psum(P, S, Mp, ldp, r, H + h * DH + half + i);
-    const float v0 = psum(P, S, Mp, ldp, r, 2 * H + h * DH + i), v1 = psum(P, S, Mp, ldp, r, 2 * H + h * DH + half + i);
+    const float sc = row_scale(rs, r);
+    const float q0 = sc * psum(P, S, Mp, ldp, r, h * DH + i), q1 = sc * psum(P, S, Mp, ldp, r, h * DH + half + i);
+    const float k0 = sc * psum(P, S, Mp, ldp, r, H + h * DH + i), k1 = sc * psum(P, S, Mp, ldp, r, H + h * DH + half + i);
+    const float v0 = sc * psum(P, S, Mp, ldp, r, 2 * H + h * DH + i),
+                v1 = sc * psum(P, S, Mp, ldp, r, 2 * H + h * DH + half + i);
     qrot[(size_t)r * H + h * DH + i] = q0 * c - q1 * s;
     qrot[(size_t)r * H + h * DH + half + i] = q1 * c + q0 * s;
     const size_t o = (((size_t)b * n_heads + h) * cap + slot) * DH;
@@ -255,9 +263,9 @@ __global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowMeta 
     vc[o + half + i] = (bf16_t)f2bf(v1);
 }
 
-// merge the attention splits: out[r][h*DH + d]. grid (H/512, M), 64 threads x 8 columns
-__global__ __launch_bounds__(64) void k_attn_combine(const float *o_part, const float *ml, float *out, int n_heads,
-                                                     int nsplit, int DH, int H) {
+// merge the attention splits and write the result as hi/lo fragments (K = H). grid (H/512, M), 64 threads
+__global__ __launch_bounds__(64) void k_attn_combine_frag(const float *o_part, const float *ml, u32x4 *Xf, int MT,
+                                                          int n_heads, int nsplit, int DH, int H) {
     const int r = blockIdx.y, g = blockIdx.x * 64 + threadIdx.x;
     if (g >= H / 8) return;
     const int h = (g * 8) / DH, d0 = (g * 8) % DH;
@@ -277,36 +285,28 @@ __global__ __launch_bounds__(64) void k_attn_combine(const float *o_part, const 
         y[4] += w * b[0]; y[5] += w * b[1]; y[6] += w * b[2]; y[7] += w * b[3];
     }
     const float inv = 1.0f / den;
-    f32x4 *dst = (f32x4 *)(out + (size_t)r * H + g * 8);
-    dst[0] = (f32x4){y[0] * inv, y[1] * inv, y[2] * inv, y[3] * inv};
-    dst[1] = (f32x4){y[4] * inv, y[5] * inv, y[6] * inv, y[7] * inv};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) y[e] *= inv;
+    store_frag8(Xf, MT, r, g * 8, y);
 }
 
-// act[r][f] = SiLU(gate_f) * up_f from the gate/up partials (col 2f = gate, 2f+1 = up).
-// grid (ceil(F/8/64), M), 64 threads x 8 outputs
-__global__ __launch_bounds__(64) void k_silu_p(const float *P, int S, int Mp, int ldp, float *act, int F) {
+// SiLU(gate) * up from the gate/up partials (col 2f = gate, 2f+1 = up), scaled by the pending RMSNorm
+// row scale, as hi/lo fragments (K = F).  grid (ceil(F/8/64), M), 64 threads x 8 outputs
+__global__ __launch_bounds__(64) void k_silu_frag(const float *P, int S, int Mp, int ldp, RowScale rs, u32x4 *Xf,
+                                                  int MT, int F) {
     const int r = blockIdx.y, g = blockIdx.x * 64 + threadIdx.x;
     if (g >= F / 8) return;
     float gu[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) gu[e] = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const f32x4 *src = (const f32x4 *)(P + ((size_t)s * Mp + r) * ldp + (size_t)g * 16);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const f32x4 v = src[q];
-            gu[4 * q] += v[0]; gu[4 * q + 1] += v[1]; gu[4 * q + 2] += v[2]; gu[4 * q + 3] += v[3];
-        }
-    }
+    psum8(P, S, Mp, ldp, r, g * 16, gu);
+    psum8(P, S, Mp, ldp, r, g * 16 + 8, gu + 8);
+    const float sc = row_scale(rs, r);
     float y[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const float a = gu[2 * e];
-        y[e] = a / (1.0f + __expf(-a)) * gu[2 * e + 1];
+        const float a = sc * gu[2 * e];
+        y[e] = a / (1.0f + __expf(-a)) * (sc * gu[2 * e + 1]);
     }
-    f32x4 *dst = (f32x4 *)(act + (size_t)r * F + g * 8);
-    dst[0] = (f32x4){y[0], y[1], y[2], y[3]};
-    dst[1] = (f32x4){y[4], y[5], y[6], y[7]};
+    store_frag8(Xf, MT, r, g * 8, y);
 }
 
 // Medusa residual block: x += SiLU(sum of partials)
@@ -352,8 +352,9 @@ __device__ __forceinline__ void block_best(float &v, int &i, float *sv, int *si)
         if (better(sv[w], si[w], v, i)) { v = sv[w]; i = si[w]; }
 }
 
-__global__ __launch_bounds__(256) void k_topk_stage1(const float *P, int S, int Mp, int ldp, float *logits, int ldl,
-                                                     int V, int k, float *cand_val, int *cand_idx) {
+__global__ __launch_bounds__(256) void k_topk_stage1(const float *P, int S, int Mp, int ldp, RowScale rs,
+                                                     float *logits, int ldl, int V, int k, float *cand_val,
+                                                     int *cand_idx) {
     __shared__ float sv[4];
     __shared__ int si[4];
     const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x, j0 = c * 1024 + tid * 4;
@@ -363,6 +364,8 @@ __global__ __launch_bounds__(256) void k_topk_stage1(const float *P, int S, int 
             const f32x4 v = *(const f32x4 *)(P + ((size_t)s * Mp + r) * ldp + j0);
             val[0] += v[0]; val[1] += v[1]; val[2] += v[2]; val[3] += v[3];
         }
+        const float sc = row_scale(rs, r);
+        val[0] *= sc; val[1] *= sc; val[2] *= sc; val[3] *= sc;
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -428,29 +431,31 @@ int gemm_splits(int Npad, int K) {
     int target = 384;
     if (const char *e = getenv("KOALA_GEMM_WGS")) target = atoi(e) > 0 ? atoi(e) : target;
     int S = (target + nwb / 2) / nwb;
+    int smax = 16;
+    if (const char *e = getenv("KOALA_GEMM_SMAX")) smax = atoi(e) > 0 && atoi(e) <= 16 ? atoi(e) : smax;
     S = S < 1 ? 1 : S;
-    S = S > 16 ? 16 : S;
+    S = S > smax ? smax : S;
     S = S > nch ? nch : S;
     return S;
 }
 
 static bool g_attr_done[3] = {false, false, false};
 
-void gemm_packed(hipStream_t st, const void *Wp, const GemmX &gx, float *P, int Npad, int K, int MTT, int S) {
+static RowScale mk_scale(const NormScale &n) { return RowScale{n.sums, n.nparts, n.srows, n.K, n.eps}; }
+
+void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S) {
     const int nwb = (Npad / 64 + 3) / 4;
     const dim3 grid(nwb * S);
-    XSrc xs;
-    xs.x = gx.x; xs.ldx = gx.ldx; xs.M = gx.M; xs.sums = gx.sums; xs.nparts = gx.nparts; xs.srows = gx.srows;
-    xs.gain = (const bf16_t *)gx.gain; xs.eps = gx.eps;
 #define KOALA_GEMM(MTV, IDX)                                                                                     \
     {                                                                                                            \
-        const size_t sm = (size_t)2 * 4 * MTV * 2 * 64 * 16 + 64 * sizeof(float);                                \
+        const size_t sm = (size_t)2 * 4 * MTV * 2 * 64 * 16;                                                     \
         if (!g_attr_done[IDX]) {                                                                                 \
             (void)hipFuncSetAttribute((const void *)k_gemm_packed<MTV>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                       (int)sm);                                                                  \
             g_attr_done[IDX] = true;                                                                             \
         }                                                                                                        \
-        k_gemm_packed<MTV><<<grid, 256, sm, st>>>((const u32x4 *)Wp, xs, P, Npad, K, S, nwb, MTT * 16, mt0);     \
+        k_gemm_packed<MTV><<<grid, 256, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, S, nwb, MTT, \
+                                                  mt0);                                                          \
     }
     // MTT is 1, 2 or a multiple of 4: groups of at most four activation tiles per launch
     for (int mt0 = 0; mt0 < MTT; mt0 += 4) {
@@ -463,24 +468,28 @@ void gemm_packed(hipStream_t st, const void *Wp, const GemmX &gx, float *P, int 
 }
 
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,
-          float *sums, int srows) {
-    k_fold<<<dim3((N + 255) / 256, M), 256, 0, st>>>(x, ldx, P, S, Mp, ldp, mode, N, sums, srows);
+          const void *gain, void *Xf, int MT, float *sums, int srows) {
+    k_fold<<<dim3((N + 511) / 512, M), 64, 0, st>>>(x, ldx, P, S, Mp, ldp, mode, N, (const bf16_t *)gain, (u32x4 *)Xf,
+                                                    MT, sums, srows);
 }
 
-void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const RowMeta &meta, float *qrot,
-                 void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap) {
-    k_rope_append_p<<<dim3(rows, n_heads), head_dim / 2, 0, st>>>(P, S, Mp, ldp, meta, qrot, (bf16_t *)kc,
-                                                                  (bf16_t *)vc, H, n_heads, head_dim, cap);
+void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, const RowMeta &meta,
+                 float *qrot, void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap) {
+    k_rope_append_p<<<dim3(rows, n_heads), head_dim / 2, 0, st>>>(P, S, Mp, ldp, mk_scale(ns), meta, qrot,
+                                                                  (bf16_t *)kc, (bf16_t *)vc, H, n_heads, head_dim,
+                                                                  cap);
 }
 
-void attn_combine(hipStream_t st, const float *o_part, const float *ml, float *out, int M, int n_heads, int nsplit,
-                  int head_dim) {
+void attn_combine_frag(hipStream_t st, const float *o_part, const float *ml, void *Xf, int MT, int M, int n_heads,
+                       int nsplit, int head_dim) {
     const int H = n_heads * head_dim;
-    k_attn_combine<<<dim3((H / 8 + 63) / 64, M), 64, 0, st>>>(o_part, ml, out, n_heads, nsplit, head_dim, H);
+    k_attn_combine_frag<<<dim3((H / 8 + 63) / 64, M), 64, 0, st>>>(o_part, ml, (u32x4 *)Xf, MT, n_heads, nsplit,
+                                                                   head_dim, H);
 }
 
-void silu_p(hipStream_t st, const float *P, int S, int Mp, int ldp, float *act, int M, int F) {
-    k_silu_p<<<dim3((F / 8 + 63) / 64, M), 64, 0, st>>>(P, S, Mp, ldp, act, F);
+void silu_frag(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, void *Xf, int MT, int M,
+               int F) {
+    k_silu_frag<<<dim3((F / 8 + 63) / 64, M), 64, 0, st>>>(P, S, Mp, ldp, mk_scale(ns), (u32x4 *)Xf, MT, F);
 }
 
 void resblock_p(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int M, int H) {
@@ -488,10 +497,11 @@ void resblock_p(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp
 }
 
 // cand buffers: rows * ceil(V/1024) * k entries each
-void logits_topk(hipStream_t st, const float *P, int S, int Mp, int ldp, float *logits, int ldl, int rows, int V,
-                 int k, float *cand_val, int *cand_idx, int32_t *idx, float *val) {
+void logits_topk(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, float *logits, int ldl,
+                 int rows, int V, int k, float *cand_val, int *cand_idx, int32_t *idx, float *val) {
     const int nchunk = (V + 1023) / 1024;
-    k_topk_stage1<<<dim3(nchunk, rows), 256, 0, st>>>(P, S, Mp, ldp, logits, ldl, V, k, cand_val, cand_idx);
+    k_topk_stage1<<<dim3(nchunk, rows), 256, 0, st>>>(P, S, Mp, ldp, mk_scale(ns), logits, ldl, V, k, cand_val,
+                                                      cand_idx);
     k_topk_stage2<<<rows, 256, 0, st>>>(cand_val, cand_idx, nchunk * k, k, idx, val);
 }
 

@@ -34,7 +34,9 @@ struct Carver {
 
 int attn_nsplit(const koala_ctx *c) {
     // enough (split, head, sequence) workgroups to cover the chip a few times over
-    int ns = 1024 / std::max(1, c->shape.n_heads * 1);
+    int target = 256;
+    if (const char *e = getenv("KOALA_ATTN_WGS")) target = atoi(e) > 0 ? atoi(e) : target;
+    int ns = target / std::max(1, c->shape.n_heads * 1);
     return std::max(1, std::min((int)KOALA_NSPLIT_MAX, ns));
 }
 
@@ -75,8 +77,9 @@ size_t carve(koala_ctx *c, char *base) {
     c->topk_val = w.take<float>((size_t)R * KOALA_TOPK_MAX);
     c->topk_idx = w.take<int32_t>((size_t)R * KOALA_TOPK_MAX);
     c->tok_tmp = w.take<int32_t>(R);
+    c->xf = nullptr;
     c->part = nullptr;
-    c->part_bytes = 0;
+    c->xf_bytes = c->part_bytes = 0;
     if (s.dtype == KOALA_BF16) {
         const int MTmax = kb::mt_of(R);
         const int shapes[6][2] = {{3 * H, H}, {H, H}, {2 * F, H}, {H, F}, {kb::pad64(V), H}, {H, 2 * H}};
@@ -84,8 +87,10 @@ size_t carve(koala_ctx *c, char *base) {
         for (auto &sh : shapes)
             worst = std::max(worst, (size_t)kb::gemm_splits(kb::pad64(sh[0]), sh[1]) * kb::pad64(sh[0]));
         c->part_bytes = worst * MTmax * 16 * sizeof(float);
+        c->xf_bytes = kb::xf_bytes(std::max(2 * H, F), MTmax);
+        c->xf = w.take<char>(c->xf_bytes);
         c->part = w.take<float>(c->part_bytes / sizeof(float));
-        c->row_sums = w.take<float>((size_t)R * 128);
+        c->row_sums = w.take<float>((size_t)R * 64);
         c->cand_val = w.take<float>((size_t)R * ((V + 1023) / 1024) * KOALA_TOPK_MAX);
         c->cand_idx = w.take<int>((size_t)R * ((V + 1023) / 1024) * KOALA_TOPK_MAX);
     }
@@ -116,12 +121,12 @@ void decoder_layer(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, co
     kg::gemm(st, bf, c->act, F, lw[5], c->x, H, rows, H, F, true);
 }
 
-// Split-K GEMM: partial sums of X * W^T into c->part; returns the split count.
-int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT, const kb::GemmX &gx) {
+// Split-K GEMM on the fragments in c->xf: partial sums of X * W^T into c->part; returns the split count.
+int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) {
     const int Npad = kb::pad64(N), S = kb::gemm_splits(Npad, K);
     const bool timed = c->prof_on && (size_t)(c->prof_used + 2) <= c->prof_ev.size();
     if (timed) (void)hipEventRecord(c->prof_ev[c->prof_used], st);
-    kb::gemm_packed(st, Wp, gx, c->part, Npad, K, MT, S);
+    kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S);
     if (timed) {
         (void)hipEventRecord(c->prof_ev[c->prof_used + 1], st);
         c->prof_used += 2;
@@ -130,20 +135,26 @@ int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT, 
     return S;
 }
 
-kb::GemmX plain_x(const float *x, int ldx, int M) { return kb::GemmX{x, ldx, M, nullptr, 0, 0, nullptr, 0.f}; }
+kb::NormScale no_scale() { return kb::NormScale{nullptr, 0, 0, 1, 0.f}; }
 
-kb::GemmX normed_x(const koala_ctx *c, const float *x, int M, const void *gain) {
+// row scale of an RMSNorm over the hidden dimension whose chunk sums are in c->row_sums
+kb::NormScale hidden_scale(const koala_ctx *c) {
     const int H = c->shape.hidden;
-    return kb::GemmX{x, H, M, c->row_sums, (H + 255) / 256, c->max_rows, gain, c->shape.rms_eps};
+    return kb::NormScale{c->row_sums, (H + 511) / 512, c->max_rows, H, c->shape.rms_eps};
 }
 
-// Folds the pending partial sums (of a down projection or of the EAGLE fc) into c->x and leaves the
-// chunk sums of squares for the RMSNorm of the next GEMM.  mode 0 if nothing is pending.
-void fold_pending(koala_ctx *c, hipStream_t st, int rows, int Mp, bool want_sums) {
+// Folds the pending partial sums (of a down projection or of the EAGLE fc; none: x as is) into c->x.
+// With `gain` it also leaves gain * x as GEMM fragments and the chunk sums for the row scale.
+void fold_pending(koala_ctx *c, hipStream_t st, int rows, int MT, const void *gain) {
     const int H = c->shape.hidden;
-    kb::fold(st, c->x, H, c->part, c->pend_S, Mp, c->pend_ld, c->pend_S ? c->pend_mode : 0, rows, H,
-             want_sums ? c->row_sums : nullptr, c->max_rows);
+    kb::fold(st, c->x, H, c->part, c->pend_S, MT * 16, c->pend_ld, c->pend_S ? c->pend_mode : 0, rows, H, gain,
+             gain ? c->xf : nullptr, MT, gain ? c->row_sums : nullptr, c->max_rows);
     c->pend_S = 0;
+}
+
+// fp32 rows -> GEMM fragments (no normalisation)
+void rows_to_frags(koala_ctx *c, hipStream_t st, const float *a, int lda, int rows, int K, int MT) {
+    kb::fold(st, const_cast<float *>(a), lda, nullptr, 0, 0, 0, 0, rows, K, nullptr, c->xf, MT, nullptr, 0);
 }
 
 // bf16 decoder layer.  On entry c->pend_* may describe partial sums still to be folded into x; on exit
@@ -153,30 +164,32 @@ void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_se
     const koala_shape &s = c->shape;
     const int rows = batch * rows_per_seq, H = s.hidden, F = s.ffn, MT = kb::mt_of(rows), Mp = MT * 16;
     const int ns = attn_nsplit(c);
-    fold_pending(c, st, rows, Mp, true);
-    int S = bf_gemm(c, st, lw[1], 3 * H, H, MT, normed_x(c, c->x, rows, lw[0]));
-    kb::rope_append(st, c->part, S, Mp, 3 * H, c->meta, c->qrot, kc, vc, rows, H, s.n_heads, s.head_dim,
-                    c->kv.capacity);
+    fold_pending(c, st, rows, MT, lw[0]);
+    int S = bf_gemm(c, st, lw[1], 3 * H, H, MT);
+    kb::rope_append(st, c->part, S, Mp, 3 * H, hidden_scale(c), c->meta, c->qrot, kc, vc, rows, H, s.n_heads,
+                    s.head_dim, c->kv.capacity);
     kb::attention_mfma(st, c->qrot, c->meta, kc, vc, c->o_part, c->ml, batch, rows_per_seq, s.n_heads, s.head_dim,
                        c->kv.capacity, ns);
-    kb::attn_combine(st, c->o_part, c->ml, c->attn_out, rows, s.n_heads, ns, s.head_dim);
-    S = bf_gemm(c, st, lw[2], H, H, MT, plain_x(c->attn_out, H, rows));
-    kb::fold(st, c->x, H, c->part, S, Mp, H, 1, rows, H, c->row_sums, c->max_rows);
-    S = bf_gemm(c, st, lw[4], 2 * F, H, MT, normed_x(c, c->x, rows, lw[3]));
-    kb::silu_p(st, c->part, S, Mp, 2 * F, c->act, rows, F);
-    S = bf_gemm(c, st, lw[5], H, F, MT, plain_x(c->act, F, rows));
+    kb::attn_combine_frag(st, c->o_part, c->ml, c->xf, MT, rows, s.n_heads, ns, s.head_dim);
+    S = bf_gemm(c, st, lw[2], H, H, MT);
+    kb::fold(st, c->x, H, c->part, S, Mp, H, 1, rows, H, lw[3], c->xf, MT, c->row_sums, c->max_rows);
+    S = bf_gemm(c, st, lw[4], 2 * F, H, MT);
+    kb::silu_frag(st, c->part, S, Mp, 2 * F, hidden_scale(c), c->xf, MT, rows, F);
+    S = bf_gemm(c, st, lw[5], H, F, MT);
     c->pend_S = S;
     c->pend_ld = H;
     c->pend_mode = 1;
 }
 
-// logits of `rows` fp32 rows at a (row stride lda): LM head -> fold -> top-k
+// top-k of the LM-head logits of `rows` fp32 rows at a (row stride lda)
 void bf_lm_head_topk(koala_ctx *c, hipStream_t st, const float *a, int lda, int rows, int k, int32_t *idx,
                      float *val) {
     const koala_shape &s = c->shape;
     const int MT = kb::mt_of(rows), Vp = kb::pad64(s.vocab);
-    const int S = bf_gemm(c, st, c->w.lm_head, s.vocab, s.hidden, MT, plain_x(a, lda, rows));
-    kb::logits_topk(st, c->part, S, MT * 16, Vp, nullptr, 0, rows, s.vocab, k, c->cand_val, c->cand_idx, idx, val);
+    rows_to_frags(c, st, a, lda, rows, s.hidden, MT);
+    const int S = bf_gemm(c, st, c->w.lm_head, s.vocab, s.hidden, MT);
+    kb::logits_topk(st, c->part, S, MT * 16, Vp, no_scale(), nullptr, 0, rows, s.vocab, k, c->cand_val, c->cand_idx,
+                    idx, val);
 }
 
 size_t elt(const koala_ctx *c) { return c->shape.dtype == KOALA_BF16 ? 2 : 4; }
@@ -366,12 +379,13 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
         for (int l = 0; l < s.n_layers; ++l)
             decoder_layer_bf16(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,
                                (char *)c->kv.target_v + ls * l);
-        // last down projection folded in, final RMSNorm -> features, LM head, greedy ids
-        fold_pending(c, st, rows, Mp, false);
+        // last down projection folded in; the LM head runs on gain * x and its logits take the row scale;
+        // the features (an output) are normalised separately
+        fold_pending(c, st, rows, MT, c->w.final_norm);
         kg::rmsnorm(st, true, c->x, c->w.final_norm, feat_out, rows, H, s.rms_eps);
-        const int S = bf_gemm(c, st, c->w.lm_head, V, H, MT, plain_x(feat_out, H, rows));
-        kb::logits_topk(st, c->part, S, Mp, kb::pad64(V), logits_out, V, rows, V, 1, c->cand_val, c->cand_idx,
-                        greedy_out, nullptr);
+        const int S = bf_gemm(c, st, c->w.lm_head, V, H, MT);
+        kb::logits_topk(st, c->part, S, Mp, kb::pad64(V), hidden_scale(c), logits_out, V, rows, V, 1, c->cand_val,
+                        c->cand_idx, greedy_out, nullptr);
         KOALA_CHECK_LAUNCH(c);
         return KOALA_OK;
     }
@@ -410,7 +424,8 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
             for (int k = 0; k < K; ++k) {
                 if (bf) {
                     const int MT = kb::mt_of(batch);
-                    const int S = bf_gemm(c, st, c->w.draft_w[j * K + k], H, H, MT, plain_x(xj, H, batch));
+                    rows_to_frags(c, st, xj, H, batch, H, MT);
+                    const int S = bf_gemm(c, st, c->w.draft_w[j * K + k], H, H, MT);
                     kb::resblock_p(st, xj, H, c->part, S, MT * 16, H, batch, H);
                 } else {
                     kg::gemm(st, bf, xj, H, c->w.draft_w[j * K + k], c->gu, H, batch, H, H, false);
@@ -438,13 +453,14 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
         const int rows = batch * rows_per_seq;
         if (bf) {
             const int MT = kb::mt_of(rows), Mp = MT * 16;
-            c->pend_S = bf_gemm(c, st, c->w.fc, H, 2 * H, MT, plain_x(c->act, 2 * H, rows));
+            rows_to_frags(c, st, c->act, 2 * H, rows, 2 * H, MT);
+            c->pend_S = bf_gemm(c, st, c->w.fc, H, 2 * H, MT);
             c->pend_ld = H;
             c->pend_mode = 2;
             for (int k = 0; k < K; ++k)
                 decoder_layer_bf16(c, st, batch, rows_per_seq, c->w.draft_w + 6 * k, (char *)c->kv.draft_k + ls * k,
                                    (char *)c->kv.draft_v + ls * k);
-            fold_pending(c, st, rows, Mp, false);
+            fold_pending(c, st, rows, MT, nullptr);
         } else {
             kg::gemm(st, bf, c->act, 2 * H, c->w.fc, c->x, H, rows, H, 2 * H, false);
             for (int k = 0; k < K; ++k)

@@ -56,12 +56,13 @@ struct koala_ctx {
     RowMeta meta;
     float *x, *act, *qkv, *qrot, *attn_out, *gu, *o_part, *ml, *logits, *fhat, *topk_val;
     int32_t *topk_idx, *tok_tmp;
-    // bf16 path: split-K partial sums
+    // bf16 path: GEMM input as hi/lo bf16 MFMA fragments, and the split-K partial sums
+    void *xf;
     float *part;
-    size_t part_bytes;
+    size_t xf_bytes, part_bytes;
     float *cand_val;   // [rows][ceil(V/1024)][16] top-k candidates of the LM-head epilogue
     int *cand_idx;
-    float *row_sums;   // [128 chunks][rows] sums of squares per 256-column chunk (RMSNorm of the next GEMM)
+    float *row_sums;   // [64 chunks][rows] sums of squares per 512-column chunk (RMSNorm row scale)
     int pend_S, pend_ld, pend_mode;  // partial sums waiting to be folded into x (0 = none)
 
     // optional event timing of the GEMM launches (koala_profile_begin / _end)
@@ -140,34 +141,34 @@ namespace kb {
 inline int mt_of(int rows) { return rows <= 16 ? 1 : rows <= 32 ? 2 : 4 * ((rows + 63) / 64); }
 inline int pad64(int n) { return (n + 63) / 64 * 64; }
 
-// Activation operand of the packed GEMM: fp32 rows, optionally RMS-normalised while staged
-// (sums = per-256-column-chunk sums of squares [nparts][srows] left by fold(), gain in bf16).
-struct GemmX {
-    const float *x;
-    int ldx, M;
+inline size_t xf_bytes(int K, int MT) { return (size_t)(K / 32) * MT * 2 * 1024; }
+
+// Pending RMSNorm row scale: 1/sqrt(sum_c sums[c][row] / K + eps); sums == nullptr means scale 1.
+struct NormScale {
     const float *sums;
-    int nparts, srows;
-    const void *gain;
+    int nparts, srows, K;
     float eps;
 };
 
 int gemm_splits(int Npad, int K);
-// P[S][MTT*16][Npad] = partial sums of X[M, K] * W[Npad, K]^T
-void gemm_packed(hipStream_t st, const void *Wp, const GemmX &gx, float *P, int Npad, int K, int MTT, int S);
-// x = (mode 1: x +) sum of partials (mode 0: x unchanged); sums (may be NULL) receives chunk sums of squares
+// P[S][MTT*16][Npad] = partial sums of X * W^T, X given as hi/lo fragments [K/32][MTT][2][64] x 16 B
+void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S);
+// v = (mode 1: x +) sum of partials (mode 0: x as is); x <- v for modes 1, 2; Xf (may be NULL) receives the
+// fragments of gain * v (gain NULL: v); sums (may be NULL) the sums of squares of v per 512-column chunk
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,
-          float *sums, int srows);
-void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const RowMeta &meta, float *qrot,
-                 void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap);
+          const void *gain, void *Xf, int MT, float *sums, int srows);
+void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, const RowMeta &meta,
+                 float *qrot, void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap);
 void attention_mfma(hipStream_t st, const float *qrot, const RowMeta &meta, const void *kc, const void *vc,
                     float *o_part, float *ml, int batch, int rows_per_seq, int n_heads, int head_dim, int cap,
                     int nsplit);
-void attn_combine(hipStream_t st, const float *o_part, const float *ml, float *out, int M, int n_heads, int nsplit,
-                  int head_dim);
-void silu_p(hipStream_t st, const float *P, int S, int Mp, int ldp, float *act, int M, int F);
+void attn_combine_frag(hipStream_t st, const float *o_part, const float *ml, void *Xf, int MT, int M, int n_heads,
+                       int nsplit, int head_dim);
+void silu_frag(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, void *Xf, int MT, int M,
+               int F);
 void resblock_p(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int M, int H);
 void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *out, int ldo, int M, int N);
-void logits_topk(hipStream_t st, const float *P, int S, int Mp, int ldp, float *logits, int ldl, int rows, int V,
-                 int k, float *cand_val, int *cand_idx, int32_t *idx, float *val);
+void logits_topk(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, float *logits, int ldl,
+                 int rows, int V, int k, float *cand_val, int *cand_idx, int32_t *idx, float *val);
 
 }  // namespace kb
