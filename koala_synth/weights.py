@@ -37,6 +37,8 @@ class ModelWeights:
     def bits(self, name: str) -> np.ndarray:
         """uint16 bfloat16 bit patterns (bf16 workloads only)."""
         assert self.dtype == "bf16"
+        if self._cache is not None:
+            return to_bf16_bits(self.f32(name))          # already bf16-representable: exact
         return to_bf16_bits(self._raw(name))
 
     def f32(self, name: str) -> np.ndarray:

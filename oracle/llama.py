@@ -42,16 +42,20 @@ def rope_rotate(x, pos, base):
 class KVCache:
     """Per-layer key/value rows of one sequence: k[l], v[l] are [n_heads, capacity, head_dim]."""
 
-    def __init__(self, n_layers, n_heads, capacity, head_dim, dtype=np.float64):
+    def __init__(self, n_layers, n_heads, capacity, head_dim, dtype=np.float64, store=None):
+        """store: optional function applied to every key/value row as it is written, modelling the
+        storage format of the cache (e.g. rounding to bfloat16); None keeps rows exact."""
         self.k = [np.zeros((n_heads, capacity, head_dim), dtype) for _ in range(n_layers)]
         self.v = [np.zeros((n_heads, capacity, head_dim), dtype) for _ in range(n_layers)]
         self.capacity = capacity
+        self.store = store
 
     def copy(self):
         c = KVCache.__new__(KVCache)
         c.k = [a.copy() for a in self.k]
         c.v = [a.copy() for a in self.v]
         c.capacity = self.capacity
+        c.store = self.store
         return c
 
 
@@ -66,15 +70,18 @@ def attention_row(q, kc, vc, slots):
     return np.einsum("hs,hsd->hd", p, v)
 
 
-def decoder_layer_rows(x, pos, slots, visible, lw, kc, vc, n_heads, head_dim, eps, base):
+def decoder_layer_rows(x, pos, slots, visible, lw, kc, vc, n_heads, head_dim, eps, base, store=None):
     """One decoder layer over T new rows.
 
     x[T,H] residual stream in; pos[T] rotary position ids; slots[T] cache slot
     each row's key/value is written to; visible[i] = list of cache slots row i
     attends to (it must contain slots[i]); lw = dict of this layer's tensors
     (in_norm, wq, wk, wv, wo, post_norm, wgate, wup, wdown; matrices [out,in]).
-    All new keys/values are written before any row attends.  Returns x_out[T,H].
+    All new keys/values are written (through `store`, if given: the cache's storage format)
+    before any row attends.  Returns x_out[T,H].
     """
+    if store is None:
+        store = lambda a: a
     T, H = x.shape
     a = rmsnorm(x, lw["in_norm"], eps)
     q = (a @ lw["wq"].T).reshape(T, n_heads, head_dim)
@@ -82,8 +89,8 @@ def decoder_layer_rows(x, pos, slots, visible, lw, kc, vc, n_heads, head_dim, ep
     v = (a @ lw["wv"].T).reshape(T, n_heads, head_dim)
     for i in range(T):
         q[i] = rope_rotate(q[i], pos[i], base)
-        kc[:, slots[i], :] = rope_rotate(k[i], pos[i], base)
-        vc[:, slots[i], :] = v[i]
+        kc[:, slots[i], :] = store(rope_rotate(k[i], pos[i], base))
+        vc[:, slots[i], :] = store(v[i])
     o = np.empty((T, H), x.dtype)
     for i in range(T):
         o[i] = attention_row(q[i], kc, vc, list(visible[i])).reshape(H)

@@ -51,7 +51,7 @@ def target_rows(cfg, W, cache: KVCache, tokens, pos, slots, visible, dt=np.float
     L = cfg["n_layers"] if n_layers is None else n_layers
     for l in range(L):
         x = decoder_layer_rows(x, pos, slots, visible, _layer(W, "", l, dt), cache.k[l], cache.v[l],
-                               cfg["n_heads"], cfg["head_dim"], cfg["rms_eps"], cfg["rope_base"])
+                               cfg["n_heads"], cfg["head_dim"], cfg["rms_eps"], cfg["rope_base"], cache.store)
     feat = rmsnorm(x, _w(W, "final_norm", dt), cfg["rms_eps"])
     logits = feat @ _w(W, "lm_head", dt).T
     return feat, logits
@@ -149,7 +149,7 @@ def eagle_rows(cfg, Wt, Wd, dcache, tokens, feats, pos, slots, visible, dt=np.fl
     for k in range(cfg["K"]):
         x = decoder_layer_rows(x, pos, slots, visible, _layer(Wd, "draft.", k, dt), dcache.k[k],
                                dcache.v[k], cfg["n_heads"], cfg["head_dim"], cfg["rms_eps"],
-                               cfg["rope_base"])
+                               cfg["rope_base"], dcache.store)
     return x
 
 

@@ -31,7 +31,7 @@ def _round(cfg, x):
 
 class Case:
     def __init__(self, name, device="cuda", n_layers=None, norm_gain="random", batch=None, ctx=None,
-                 K=None, max_m=None, make_gpu=True, **over):
+                 K=None, max_m=None, make_gpu=True, kv_storage_rounding=False, **over):
         import torch
         cfg = get_config(name, **over)
         if n_layers is not None:
@@ -60,8 +60,14 @@ class Case:
         self.max_m = max_m or 1
         self.device = device
         L, nh, dh = cfg["n_layers"], cfg["n_heads"], cfg["head_dim"]
-        self.tc = [oracle.KVCache(L, nh, self.cap, dh) for _ in range(self.B)]
-        self.dc = [oracle.KVCache(cfg["K"], nh, self.cap, dh) for _ in range(self.B)] if self.eagle else None
+        # kv_storage_rounding: the oracle rounds every key/value row it writes to the cache's bf16
+        # storage format (the device cache is bf16); off = rows stay exact
+        store = None
+        if kv_storage_rounding and cfg["dtype"] == "bf16":
+            store = lambda a: bf16_bits_to_f32(to_bf16_bits(np.asarray(a, np.float32))).astype(np.float64)
+        self.tc = [oracle.KVCache(L, nh, self.cap, dh, store=store) for _ in range(self.B)]
+        self.dc = ([oracle.KVCache(cfg["K"], nh, self.cap, dh, store=store) for _ in range(self.B)]
+                   if self.eagle else None)
         self.gpu = None
         if make_gpu:
             self._make_gpu(torch)
