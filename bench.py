@@ -21,15 +21,18 @@ os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(cfg, T, C, D, K, levels):
+def algorithmic_bytes(cfg, T, ctx_lens, D, K, levels, medusa_heads):
     """Bytes that must move per call (bf16 = 2 bytes): weights once per pass, KV context read,
     tree KV written; activations of T*H size are ignored (<1%)."""
     H, F, V, L = cfg["hidden"], cfg["ffn"], cfg["vocab"], cfg["n_layers"]
-    b = 2
+    b, B, sumC = 2, len(ctx_lens), sum(ctx_lens)
     P_l = 4 * H * H + 3 * H * F
-    verify = b * (L * P_l + V * H) + b * L * 2 * H * C + b * L * 2 * H * T + b * T * H
-    passes = 1 + sum(1 for n in levels[1:D] if n > 0)          # catch-up/root pass + expanded levels
-    draft = passes * b * (2 * H * H + K * P_l + V * H) + b * K * 2 * H * C * passes
+    verify = b * (L * P_l + V * H) + b * L * 2 * H * sumC + b * L * 2 * H * T * B + b * T * B * H
+    if cfg["draft"] == "medusa":
+        draft = b * (medusa_heads * K * H * H + V * H)
+    else:
+        passes = 1 + sum(1 for n in levels[1:D] if n > 0)      # catch-up/root pass + expanded levels
+        draft = passes * b * (2 * H * H + K * P_l + V * H) + b * K * 2 * H * sumC * passes
     return verify, draft
 
 
@@ -55,8 +58,12 @@ def device_weights(cfg, torch, K, dev):
     w = dict(embed=mat(V, H), lm_head=KO.fragment_major(mat(V, H)),
              final_norm=torch.ones(H, dtype=torch.bfloat16, device=dev),
              layers=[layer() for _ in range(cfg["n_layers"])])
-    w["fc"] = KO.fragment_major(mat(H, 2 * H))
-    w["draft"] = [t for _ in range(K) for t in layer()]
+    if cfg["draft"] == "medusa":
+        w["fc"] = None
+        w["draft"] = [KO.fragment_major(mat(H, H)) for _ in range(cfg["medusa_heads"] * K)]
+    else:
+        w["fc"] = KO.fragment_major(mat(H, 2 * H))
+        w["draft"] = [t for _ in range(K) for t in layer()]
     return w
 
 
@@ -130,7 +137,7 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="cfg2")
-    ap.add_argument("--K", type=int, default=1, help="draft layers (EAGLE-style)")
+    ap.add_argument("--K", type=int, default=0, help="draft layers per head (0: 1 for cfg2, else the config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="override target layer count (debug only)")
     ap.add_argument("--graph", type=int, default=0, help="1: replay the iteration as a captured HIP graph")
@@ -148,51 +155,65 @@ def main():
     KO.load_library()
     dev = "cuda:0"
     cfg = get_config(args.config)
-    assert cfg["draft"] == "eagle" and cfg["dtype"] == "bf16" and cfg["batch"] == 1
+    assert cfg["dtype"] == "bf16"
     if args.layers:
         cfg["n_layers"] = args.layers
-    K = args.K
+    eagle = cfg["draft"] == "eagle"
+    K = args.K if args.K > 0 else (1 if args.config == "cfg2" else cfg["K"])
+    B = cfg["batch"]
     tree = cfg["tree_template"]
-    T, D, C, H, V = tree.n_nodes, tree.depth, cfg["ctx"], cfg["hidden"], cfg["vocab"]
+    T, D, H, V = tree.n_nodes, tree.depth, cfg["hidden"], cfg["vocab"]
     cap = cfg["capacity"]
+    if isinstance(cfg["ctx"], tuple):                            # ragged batch: lengths from seed 2
+        from koala_synth import tensor_uniform_int
+        from koala_synth.configs import SEED_LENGTHS
+        ctx_lens = [int(v) for v in tensor_uniform_int(SEED_LENGTHS, "ctx_lens", (B,), cfg["ctx"][0], cfg["ctx"][1] + 1)]
+    else:
+        ctx_lens = [int(cfg["ctx"])] * B
+    C = max(ctx_lens)
 
     shape = dict(hidden=H, n_heads=cfg["n_heads"], head_dim=cfg["head_dim"], ffn=cfg["ffn"], vocab=V,
                  n_layers=cfg["n_layers"], rms_eps=cfg["rms_eps"], rope_base=cfg["rope_base"], dtype=KO.KOALA_BF16)
-    ctx = KO.KoalaContext(shape, dict(kind=KO.KOALA_DRAFT_EAGLE, K=K, medusa_heads=0, max_m=1), tree, 1)
+    ctx = KO.KoalaContext(shape, dict(kind=KO.KOALA_DRAFT_EAGLE if eagle else KO.KOALA_DRAFT_MEDUSA, K=K,
+                                      medusa_heads=cfg["medusa_heads"], max_m=1), tree, B)
     w = device_weights(cfg, torch, K, dev)
     g = torch.Generator(device=dev)
     g.manual_seed(1)
-    kv = KO.alloc_kv(cfg, 1, cap, dev, K)
+    kv = KO.alloc_kv(cfg, B, cap, dev, K if eagle else 0)
     for name in ("target_k", "target_v", "draft_k", "draft_v"):
-        kv[name][:, :, :, :C].copy_(torch.randn(kv[name][:, :, :, :C].shape, generator=g, device=dev,
-                                                dtype=torch.float32).to(torch.bfloat16))
+        if kv[name] is None:
+            continue
+        for l in range(kv[name].shape[0]):                       # layer by layer: bounded temporaries
+            for b in range(B):
+                view = kv[name][l, b, :, :ctx_lens[b]]
+                view.copy_(torch.randn(view.shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16))
     ws = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
     ctx.bind(w, kv, ws)
 
-    feat_in = torch.randn(1, 1, H, generator=g, device=dev, dtype=torch.float32)
-    tok_in = torch.randint(0, V, (1, 1), generator=g, device=dev, dtype=torch.int32)
-    tree_tokens = torch.zeros(1, T, dtype=torch.int32, device=dev)
-    scores = torch.zeros(1, T, dtype=torch.float32, device=dev)
-    feat_out = torch.zeros(1, T, H, dtype=torch.float32, device=dev)
-    greedy = torch.zeros(1, T, dtype=torch.int32, device=dev)
-    a_len = torch.zeros(1, dtype=torch.int32, device=dev)
-    path = torch.zeros(1, D + 1, dtype=torch.int32, device=dev)
-    nxt = torch.zeros(1, dtype=torch.int32, device=dev)
-    ctx0 = torch.full((1,), C, dtype=torch.int32, device=dev)
+    feat_in = torch.randn(B, 1, H, generator=g, device=dev, dtype=torch.float32)
+    tok_in = torch.randint(0, V, (B, 1), generator=g, device=dev, dtype=torch.int32)
+    tree_tokens = torch.zeros(B, T, dtype=torch.int32, device=dev)
+    scores = torch.zeros(B, T, dtype=torch.float32, device=dev)
+    feat_out = torch.zeros(B, T, H, dtype=torch.float32, device=dev)
+    greedy = torch.zeros(B, T, dtype=torch.int32, device=dev)
+    a_len = torch.zeros(B, dtype=torch.int32, device=dev)
+    path = torch.zeros(B, D + 1, dtype=torch.int32, device=dev)
+    nxt = torch.zeros(B, dtype=torch.int32, device=dev)
+    ctx0 = torch.tensor(ctx_lens, dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
 
     def step(events=None):
-        kv["ctx_len"].copy_(ctx0)                                # same workload every step (C = 1024)
+        kv["ctx_len"].copy_(ctx0)                                # same workload every step
         if events: events[0].record(stream)
-        ctx.draft_expand(1, feat_in, tok_in, 1, tree_tokens, scores)
+        ctx.draft_expand(B, feat_in, tok_in, 1, tree_tokens, scores)
         if events: events[1].record(stream)
-        ctx.tree_verify(1, tree_tokens, feat_out, None, greedy)
+        ctx.tree_verify(B, tree_tokens, feat_out, None, greedy)
         if events: events[2].record(stream)
-        ctx.accept_prefix(1, tree_tokens, greedy, a_len, path, nxt, True)
+        ctx.accept_prefix(B, tree_tokens, greedy, a_len, path, nxt, True)
         if events: events[3].record(stream)
         # feed the result back (device side): the root's feature and the target's next token
         feat_in.copy_(feat_out[:, :1])
-        tok_in.copy_(nxt.view(1, 1))
+        tok_in.copy_(nxt.view(B, 1))
 
     if args.calib_copy:
         src = torch.ones(args.calib_copy << 20, dtype=torch.uint8, device=dev)
@@ -230,7 +251,7 @@ def main():
         torch.cuda.synchronize()
         for i in range(3):
             parts[i] += ev[i].elapsed_time(ev[i + 1]) / n_b
-        acc_sum += int(a_len.item())
+        acc_sum += float(a_len.float().mean().item())
     mean_tokens = 1.0 + acc_sum / n_b
 
     # dominant kernel: the weight-streaming GEMM; HIP events around each of its launches
@@ -243,7 +264,7 @@ def main():
 
     levels = [sum(1 for i in range(T) if len(tree.paths[i]) == d and any(tree.parent[j] == i for j in range(T)))
               for d in range(D + 1)]
-    vb, db = algorithmic_bytes(cfg, T, C, D, K, levels)
+    vb, db = algorithmic_bytes(cfg, T, ctx_lens, D, K, levels, cfg["medusa_heads"])
     achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
     traffic = None                                               # HBM bytes per launch from the rocprofv3 PMC runs
     tfile = os.path.join(ROOT, "profiles", f"traffic_k_gemm_packed_{args.config}.txt")
@@ -255,10 +276,11 @@ def main():
         "metric": "draft_verify_iterations_per_s", "value": 1e3 / ms_per_step, "unit": "iterations/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.config}: 7B-shape EAGLE-style K={K}, T={T} depth {D}, ctx {C}, "
-                               f"{cfg['n_layers']} target layers, batch 1", "K": K, "tree_nodes": T, "ctx": C,
+        "config": {"workload": f"{args.config}: hidden {H}, {'EAGLE' if eagle else 'Medusa'}-style K={K}, T={T} depth "
+                               f"{D}, ctx {ctx_lens if B > 1 else C}, {cfg['n_layers']} target layers, batch {B}",
+                   "K": K, "tree_nodes": T, "ctx": C, "batch": B,
                    "launch": "hip_graph" if args.graph else "stream"},
-        "tokens_per_s": 1e3 / ms_per_step * mean_tokens, "mean_tokens_per_iteration": mean_tokens,
+        "tokens_per_s": 1e3 / ms_per_step * mean_tokens * B, "mean_tokens_per_iteration": mean_tokens,
         "ms_draft_expand": parts[0], "ms_tree_verify": parts[1], "ms_accept_prefix": parts[2],
         "verify_bytes": vb, "draft_bytes": db,
         "verify_hbm_frac": vb / (parts[1] * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -268,7 +290,7 @@ def main():
                      "launches_timed": gemm_launches, "avg_launch_us": gemm_ms * 1e3 / max(1, gemm_launches),
                      "avg_launch_bytes": gemm_bytes / max(1, gemm_launches)},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and eagle and B == 1:
         out["cpu_baseline"] = cpu_baseline(cfg, tree, K, levels)
     print(json.dumps(out))
 
