@@ -127,13 +127,14 @@ __global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ W
     }
 }
 
-// sum of the split-K partials of element (row, col)
+// Sums of split-K partials.  Loads are issued in batches (16 vector loads / 24 scalar loads in
+// flight) so that a sum costs one or two memory round trips; the order of the additions is fixed.
 __device__ __forceinline__ float psum(const float *P, int S, int Mp, int ld, int row, int col) {
     const float *p = P + (size_t)row * ld + col;
     const size_t stride = (size_t)Mp * ld;
     float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
     int s = 0;
-    for (; s + 4 <= S; s += 4) {   // four loads in flight; the order of the additions is fixed
+    for (; s + 4 <= S; s += 4) {
         v0 += p[(size_t)s * stride];
         v1 += p[(size_t)(s + 1) * stride];
         v2 += p[(size_t)(s + 2) * stride];
@@ -143,13 +144,47 @@ __device__ __forceinline__ float psum(const float *P, int S, int Mp, int ld, int
     return (v0 + v1) + (v2 + v3);
 }
 
-// 8 consecutive columns (col % 8 == 0) of the summed partials of a row; splits are read four at a
-// time so that eight loads are in flight, and added in a fixed order
+// N sums at once: element (row, col[i]) for i < N
+template <int N>
+__device__ __forceinline__ void psum_n(const float *P, int S, int Mp, int ld, int row, const int *col, float *out) {
+    const float *p = P + (size_t)row * ld;
+    const size_t stride = (size_t)Mp * ld;
+    float acc[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {
+        float t[4][N];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < N; ++i) t[u][i] = p[(size_t)(s + u) * stride + col[i]];
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += (t[0][i] + t[1][i]) + (t[2][i] + t[3][i]);
+    }
+    for (; s < S; ++s)
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += p[(size_t)s * stride + col[i]];
+#pragma unroll
+    for (int i = 0; i < N; ++i) out[i] = acc[i];
+}
+
+// 8 consecutive columns (col % 8 == 0) of the summed partials of a row
 __device__ __forceinline__ void psum8(const float *P, int S, int Mp, int ld, int row, int col, float *v) {
     const f32x4 *src = (const f32x4 *)(P + (size_t)row * ld + col);
     const size_t stride = (size_t)Mp * ld / 4;   // in f32x4 units
     f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
     int s = 0;
+    for (; s + 8 <= S; s += 8) {
+        f32x4 a[8], b[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            a[u] = src[(size_t)(s + u) * stride];
+            b[u] = src[(size_t)(s + u) * stride + 1];
+        }
+        lo += ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+        hi += ((b[0] + b[1]) + (b[2] + b[3])) + ((b[4] + b[5]) + (b[6] + b[7]));
+    }
     for (; s + 4 <= S; s += 4) {
         const f32x4 a0 = src[(size_t)s * stride], b0 = src[(size_t)s * stride + 1];
         const f32x4 a1 = src[(size_t)(s + 1) * stride], b1 = src[(size_t)(s + 1) * stride + 1];
@@ -249,11 +284,12 @@ __global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowScale
     const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x, half = DH / 2;
     const int b = meta.row_b[r], slot = meta.row_slot[r];
     const float c = meta.rope_cos[(size_t)r * half + i], s = meta.rope_sin[(size_t)r * half + i];
+    const int cols[6] = {h * DH + i, h * DH + half + i, H + h * DH + i, H + h * DH + half + i, 2 * H + h * DH + i,
+                         2 * H + h * DH + half + i};
+    float t[6];
+    psum_n<6>(P, S, Mp, ldp, r, cols, t);
     const float sc = row_scale(rs, r);
-    const float q0 = sc * psum(P, S, Mp, ldp, r, h * DH + i), q1 = sc * psum(P, S, Mp, ldp, r, h * DH + half + i);
-    const float k0 = sc * psum(P, S, Mp, ldp, r, H + h * DH + i), k1 = sc * psum(P, S, Mp, ldp, r, H + h * DH + half + i);
-    const float v0 = sc * psum(P, S, Mp, ldp, r, 2 * H + h * DH + i),
-                v1 = sc * psum(P, S, Mp, ldp, r, 2 * H + h * DH + half + i);
+    const float q0 = sc * t[0], q1 = sc * t[1], k0 = sc * t[2], k1 = sc * t[3], v0 = sc * t[4], v1 = sc * t[5];
     qrot[(size_t)r * H + h * DH + i] = q0 * c - q1 * s;
     qrot[(size_t)r * H + h * DH + half + i] = q1 * c + q0 * s;
     const size_t o = (((size_t)b * n_heads + h) * cap + slot) * DH;
@@ -263,30 +299,47 @@ __global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowScale
     vc[o + half + i] = (bf16_t)f2bf(v1);
 }
 
-// merge the attention splits and write the result as hi/lo fragments (K = H). grid (H/512, M), 64 threads
+// merge the attention splits and write the result as hi/lo fragments (K = H). grid (H/512, M), 64 threads.
+// All loads are issued before anything is combined (one memory round trip).
 __global__ __launch_bounds__(64) void k_attn_combine_frag(const float *o_part, const float *ml, u32x4 *Xf, int MT,
                                                           int n_heads, int nsplit, int DH, int H) {
     const int r = blockIdx.y, g = blockIdx.x * 64 + threadIdx.x;
     if (g >= H / 8) return;
     const int h = (g * 8) / DH, d0 = (g * 8) % DH;
     const float *p = ml + ((size_t)r * n_heads + h) * nsplit * 2;
+    const float *ob = o_part + ((size_t)r * n_heads + h) * nsplit * DH + d0;
+    f32x4 oa[KOALA_NSPLIT_MAX], oc[KOALA_NSPLIT_MAX];
+    float ms[KOALA_NSPLIT_MAX], ls[KOALA_NSPLIT_MAX];
+#pragma unroll
+    for (int s = 0; s < KOALA_NSPLIT_MAX; ++s) {
+        if (s < nsplit) {
+            const f32x4 *o = (const f32x4 *)(ob + (size_t)s * DH);
+            oa[s] = o[0];
+            oc[s] = o[1];
+            ms[s] = p[2 * s];
+            ls[s] = p[2 * s + 1];
+        } else {
+            oa[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            oc[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            ms[s] = -INFINITY;
+            ls[s] = 0.f;
+        }
+    }
     float Mx = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) Mx = fmaxf(Mx, p[2 * s]);
-    float y[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < KOALA_NSPLIT_MAX; ++s) Mx = fmaxf(Mx, ms[s]);
+    f32x4 ya = {0.f, 0.f, 0.f, 0.f}, yc = {0.f, 0.f, 0.f, 0.f};
     float den = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-        const float ms = p[2 * s];
-        if (ms == -INFINITY) continue;
-        const float w = __expf(ms - Mx);
-        den += w * p[2 * s + 1];
-        const f32x4 *o = (const f32x4 *)(o_part + (((size_t)r * n_heads + h) * nsplit + s) * DH + d0);
-        const f32x4 a = o[0], b = o[1];
-        y[0] += w * a[0]; y[1] += w * a[1]; y[2] += w * a[2]; y[3] += w * a[3];
-        y[4] += w * b[0]; y[5] += w * b[1]; y[6] += w * b[2]; y[7] += w * b[3];
+#pragma unroll
+    for (int s = 0; s < KOALA_NSPLIT_MAX; ++s) {
+        const float w = (ms[s] == -INFINITY) ? 0.f : __expf(ms[s] - Mx);
+        den += w * ls[s];
+        ya += w * oa[s];
+        yc += w * oc[s];
     }
     const float inv = 1.0f / den;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) y[e] *= inv;
+    const float y[8] = {ya[0] * inv, ya[1] * inv, ya[2] * inv, ya[3] * inv, yc[0] * inv, yc[1] * inv, yc[2] * inv,
+                        yc[3] * inv};
     store_frag8(Xf, MT, r, g * 8, y);
 }
 
@@ -551,6 +604,33 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const float *__restrict__ qro
     unsigned char *vt = vt_all + (size_t)wave * 32 * VS;
     const float scale = rsqrtf((float)DH);
 
+    // key range of this workgroup, and the first step's K fragments (A operand) / V tile rows; the loads
+    // are in flight while the Q fragments are built
+    const int kv_end = meta.kv_end[b];
+    int chunk = (kv_end + nsplit - 1) / nsplit;
+    chunk = (chunk + 31) / 32 * 32;
+    const int j0 = s * chunk, j1 = min(kv_end, j0 + chunk);
+    const int nsteps = j1 > j0 ? (j1 - j0 + 31) / 32 : 0;
+    const bf16_t *kb = kc + ((size_t)b * n_heads + h) * cap * DH;
+    const bf16_t *vb = vc + ((size_t)b * n_heads + h) * cap * DH;
+    u32x4 kf[2][KS], vr[VI];
+    auto load_step = [&](int st) {
+        const int k0 = j0 + st * 32;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int key = min(k0 + 16 * j + li, cap - 1);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kf[j][ks] = *(const u32x4 *)(kb + (size_t)key * DH + ks * 32 + 8 * lg);
+        }
+#pragma unroll
+        for (int i = 0; i < VI; ++i) {
+            const int key = min(k0 + i * (64 / LPR) + l / LPR, cap - 1);
+            vr[i] = *(const u32x4 *)(vb + (size_t)key * DH + (l % LPR) * 8);
+        }
+    };
+    if (wave < nsteps) load_step(wave);
+
     // Q fragments (B operand): lane (row%16, g) holds Q[row][32*ks + 8*g .. +8], scaled, as hi and lo
     for (int u = tid; u < MT * KS * 64; u += 256) {
         const int lane = u & 63, ks = (u >> 6) % KS, mt = (u >> 6) / KS;
@@ -588,14 +668,6 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const float *__restrict__ qro
         base[mt] = ok ? meta.row_base[r] : 0;
         mask[mt] = ok ? meta.row_mask[r] : 0ull;
     }
-    const int kv_end = meta.kv_end[b];
-    int chunk = (kv_end + nsplit - 1) / nsplit;
-    chunk = (chunk + 31) / 32 * 32;
-    const int j0 = s * chunk, j1 = min(kv_end, j0 + chunk);
-    const int nsteps = j1 > j0 ? (j1 - j0 + 31) / 32 : 0;
-    const bf16_t *kb = kc + ((size_t)b * n_heads + h) * cap * DH;
-    const bf16_t *vb = vc + ((size_t)b * n_heads + h) * cap * DH;
-
     f32x4 acc_o[MT][DT];
     float m_run[MT], l_run[MT];
 #pragma unroll
@@ -609,21 +681,6 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const float *__restrict__ qro
 
     for (int st = wave; st < nsteps; st += 4) {
         const int k0 = j0 + st * 32;
-        // ---- loads: K fragments (A operand) and the V tile
-        u32x4 kf[2][KS];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int key = min(k0 + 16 * j + li, cap - 1);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                kf[j][ks] = *(const u32x4 *)(kb + (size_t)key * DH + ks * 32 + 8 * lg);
-        }
-        u32x4 vr[VI];
-#pragma unroll
-        for (int i = 0; i < VI; ++i) {
-            const int key = min(k0 + i * (64 / LPR) + l / LPR, cap - 1);
-            vr[i] = *(const u32x4 *)(vb + (size_t)key * DH + (l % LPR) * 8);
-        }
         // ---- S^T = K Q^T
         f32x4 sc[2][MT];
 #pragma unroll
@@ -652,6 +709,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const float *__restrict__ qro
             dst[0] = in ? u64_alias{vr[i].x, vr[i].y} : u64_alias{0u, 0u};
             dst[1] = in ? u64_alias{vr[i].z, vr[i].w} : u64_alias{0u, 0u};
         }
+        if (st + 4 < nsteps) load_step(st + 4);   // kf / vr are free again: next step's loads overlap the rest
         // ---- mask, online softmax; probabilities stay in place as the B operand (hi, lo)
         bf16x8 ph[MT], pl[MT];
 #pragma unroll
