@@ -65,12 +65,15 @@ __global__ __launch_bounds__(256) void k_gemm_packed(const u32x4 *__restrict__ W
         for (int j = 0; j < 8; ++j) wr[slot][j] = __builtin_nontemporal_load(wsrc + (size_t)b * 512 + j * 64);
     };
     if (nchunks > 0) {
+        // X loads first, weight loads right behind them: the wait for X then leaves the weight loads in flight
 #pragma unroll
-        for (int i = 0; i < XPT; ++i) xs[threadIdx.x + 256 * i] = *xaddr(0, threadIdx.x + 256 * i);
+        for (int i = 0; i < XPT; ++i) xr[i] = *xaddr(0, threadIdx.x + 256 * i);
         if (active) {
             wload(0, 0);
             wload(1, 1);
         }
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) xs[threadIdx.x + 256 * i] = xr[i];
     }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
