@@ -187,9 +187,9 @@ koala_status koala_accept_prefix(koala_ctx *ctx, void *hip_stream, int batch,
                                  int commit);
 
 /* Measurement aid for benchmarks (not part of the method).  Between koala_profile_begin and
- * koala_profile_end every weight-streaming GEMM launch of the bfloat16 path is bracketed by a pair
- * of HIP events on the call's stream (at most max_launches pairs; further launches are not
- * timed).  koala_profile_end synchronises on the recorded events and returns the summed kernel
+ * koala_profile_end every weight-streaming GEMM launch of the bfloat16 path carries a pair
+ * of HIP events bound to its own dispatch on the call's stream, which take the kernel's begin and
+ * end times (at most max_launches pairs; further launches are not timed).  koala_profile_end synchronises on the recorded events and returns the summed kernel
  * time in milliseconds, the number of timed launches and the weight bytes those launches
  * streamed (their algorithmic HBM traffic).  Host only; any out pointer may be NULL. */
 koala_status koala_profile_begin(koala_ctx *ctx, int max_launches);

@@ -499,7 +499,8 @@ static bool g_attr_done[3] = {false, false, false};
 
 static RowScale mk_scale(const NormScale &n) { return RowScale{n.sums, n.nparts, n.srows, n.K, n.eps}; }
 
-void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S) {
+void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S,
+                 hipEvent_t ev_start, hipEvent_t ev_stop) {
     const int nwb = (Npad / 64 + 3) / 4;
     const dim3 grid(nwb * S);
 #define KOALA_GEMM(MTV, IDX)                                                                                     \
@@ -510,8 +511,13 @@ void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int N
                                       (int)sm);                                                                  \
             g_attr_done[IDX] = true;                                                                             \
         }                                                                                                        \
-        k_gemm_packed<MTV><<<grid, 256, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, S, nwb, MTT, \
-                                                  mt0);                                                          \
+        if (ev_start || ev_stop) /* events bound to the dispatch itself: they read the kernel's own begin and end */ \
+            hipExtLaunchKernelGGL(k_gemm_packed<MTV>, grid, dim3(256), sm, st, mt0 == 0 ? ev_start : nullptr,    \
+                                  mt0 + 4 >= MTT ? ev_stop : nullptr, 0, (const u32x4 *)Wp, (const u32x4 *)Xf, P, \
+                                  Npad, K, S, nwb, MTT, mt0);                                                    \
+        else                                                                                                     \
+            k_gemm_packed<MTV><<<grid, 256, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, S, nwb,  \
+                                                      MTT, mt0);                                                 \
     }
     // MTT is 1, 2 or a multiple of 4: groups of at most four activation tiles per launch
     for (int mt0 = 0; mt0 < MTT; mt0 += 4) {

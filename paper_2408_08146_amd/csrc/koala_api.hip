@@ -125,10 +125,9 @@ void decoder_layer(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, co
 int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) {
     const int Npad = kb::pad64(N), S = kb::gemm_splits(Npad, K);
     const bool timed = c->prof_on && (size_t)(c->prof_used + 2) <= c->prof_ev.size();
-    if (timed) (void)hipEventRecord(c->prof_ev[c->prof_used], st);
-    kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S);
+    kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S, timed ? c->prof_ev[c->prof_used] : nullptr,
+                    timed ? c->prof_ev[c->prof_used + 1] : nullptr);
     if (timed) {
-        (void)hipEventRecord(c->prof_ev[c->prof_used + 1], st);
         c->prof_used += 2;
         c->prof_bytes += (double)Npad * K * 2.0;
     }

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 #include <string>
@@ -152,7 +153,9 @@ struct NormScale {
 
 int gemm_splits(int Npad, int K);
 // P[S][MTT*16][Npad] = partial sums of X * W^T, X given as hi/lo fragments [K/32][MTT][2][64] x 16 B
-void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S);
+// ev_start/ev_stop (either may be null) are attached to the dispatch: they take the kernel's own begin and end times
+void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S,
+                 hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 // v = (mode 1: x +) sum of partials (mode 0: x as is); x <- v for modes 1, 2; Xf (may be NULL) receives the
 // fragments of gain * v (gain NULL: v); sums (may be NULL) the sums of squares of v per 512-column chunk
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,
