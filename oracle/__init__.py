@@ -19,4 +19,4 @@ from .llama import (rmsnorm, silu, softmax, rope_rotate, attention_row, decoder_
 from .tree import tree_depths, ancestor_mask, children_lists, expanded_nodes  # noqa: F401
 from .spec import (target_rows, decode_one, prefill, verify_tree, accept_greedy, commit_path,  # noqa: F401
                    topk_desc, eagle_rows, eagle_expand, medusa_expand, iteration_eagle,
-                   greedy_reference)
+                   greedy_reference, generate_speculative, mean_tokens_per_iteration, n_alpha)

@@ -248,3 +248,60 @@ def iteration_eagle(cfg, Wt, Wd, tcache, dcache, C, feat_in, tok_in, parent, ran
     return dict(tree_tokens=tokens, feat=feat, logits=logits, greedy=greedy, accept_len=a,
                 path=path, next_token=nxt, emitted=emitted, C=C2,
                 feat_in=feat[path], tok_in=np.asarray(emitted, np.int32), draft=dr)
+
+
+# ----------------------------------------------------------------------------
+# generation loop and its statistics (sections 2.2, 4.1)
+# ----------------------------------------------------------------------------
+def generate_speculative(cfg, Wt, Wd, prompt, n_new, parent, rank, topk, dt=np.float64):
+    """Prefill `prompt` with the target, then repeat draft -> verify -> accept -> commit until
+    at least n_new tokens were emitted (the first of them is the prefill's own greedy token).
+    cfg["draft"] selects the head: "eagle" (the draft cache is brought up to date by the
+    catch-up rows of every call, all prompt rows in the first) or "medusa".
+    Returns dict(tokens[n_new], accept_lens[iterations], trees[iterations][T], C)."""
+    T = len(parent)
+    cap = len(prompt) + n_new + 2 * T + 2
+    tcache = KVCache(cfg["n_layers"], cfg["n_heads"], cap, cfg["head_dim"], dt)
+    feats, logits = prefill(cfg, Wt, tcache, prompt, dt)
+    root = int(np.argmax(logits[-1]))
+    out, accept_lens, trees = [root], [], []
+    C = len(prompt)
+    eagle = cfg["draft"] == "eagle"
+    if eagle:
+        dcache = KVCache(cfg["K"], cfg["n_heads"], cap, cfg["head_dim"], dt)
+        feat_in, tok_in = feats, np.asarray(list(prompt[1:]) + [root], np.int32)
+    else:
+        feat_in, tok_in = feats[-1:], np.asarray([root], np.int32)
+    while len(out) < n_new:
+        if eagle:
+            tokens = eagle_expand(cfg, Wt, Wd, dcache, C, feat_in, tok_in, parent, rank, topk, dt)["tokens"]
+        else:
+            tokens = medusa_expand(cfg, Wt, Wd, feat_in[-1], int(tok_in[-1]), parent, rank, topk, dt)["tokens"]
+        feat, _, greedy = verify_tree(cfg, Wt, tcache, C, tokens, parent, dt)
+        a, path, nxt = accept_greedy(tokens, greedy, parent)
+        C = commit_path(tcache, C, path)
+        emitted = [int(tokens[p]) for p in path[1:]] + [nxt]
+        out += emitted
+        accept_lens.append(a)
+        trees.append(np.asarray(tokens).copy())
+        feat_in, tok_in = feat[path], np.asarray(emitted, np.int32)
+    return dict(tokens=out[:n_new], accept_lens=accept_lens, trees=trees, C=C)
+
+
+def mean_tokens_per_iteration(accept_lens):
+    """Average number of tokens one draft-verify iteration yields (section 4.1): every
+    iteration emits its accepted drafted tokens plus the target's own next token."""
+    return float(np.mean(np.asarray(accept_lens) + 1)) if len(accept_lens) else 0.0
+
+
+def n_alpha(accept_lens, max_depth):
+    """Acceptance rate of the n-th drafted token given that the n-1 before it were accepted
+    (section 4.1), n = 1..max_depth, from the accepted lengths of chain drafts:
+    alpha_n = #{iterations with a >= n} / #{iterations with a >= n-1}; nan where the
+    denominator is zero."""
+    a = np.asarray(accept_lens)
+    out = []
+    for n in range(1, max_depth + 1):
+        den = int(np.sum(a >= n - 1))
+        out.append(float(np.sum(a >= n)) / den if den else float("nan"))
+    return out
