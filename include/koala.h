@@ -186,6 +186,38 @@ koala_status koala_accept_prefix(koala_ctx *ctx, void *hip_stream, int batch,
                                  int32_t *accept_len, int32_t *accept_path, int32_t *next_token,
                                  int commit);
 
+/* Statistics of a generation run.  accept_hist[a] counts the iterations that accepted exactly a
+ * drafted tokens; from it follow the average number of tokens per iteration (section 4.1:
+ * sum_a (a+1) accept_hist[a] / iterations) and, for a chain template, the n-alpha acceptance rates
+ * (section 4.1: alpha_n = #{a >= n} / #{a >= n-1}). */
+typedef struct {
+    int32_t iterations;       /* draft-verify iterations run */
+    int32_t tokens;           /* tokens produced by them, >= max_new */
+    int32_t accept_hist[64];
+} koala_gen_stats;
+
+/* Generation loop on sequence 0 (section 2.2 repeated; metrics of section 4.1): repeat
+ * draft_expand -> tree_verify -> accept_prefix(commit), feeding the features and tokens of the
+ * accepted path back as the next call's catch-up rows, until max_new tokens have been produced.
+ * Preconditions are those of koala_draft_expand for the first call: the target cache holds
+ * rows 0 .. ctx_len0-1, an EAGLE draft cache rows 0 .. ctx_len0-m-1, and
+ *   feat_in device fp32 [m, hidden], tok_in device int32 [m] as in koala_draft_expand
+ *           (tok_in[m-1] is the root of the first tree);
+ *   ctx_len0 the value of ctx_len[0] on the device (checked), with
+ *           ctx_len0 + max_new + depth + n_nodes <= capacity;
+ *   use_draft = 0: plain autoregressive decoding with the target only (the baseline of the
+ *           speed-up ratio in section 4.1); the context must have a single-node tree, feat_in is
+ *           ignored and every iteration yields one token;
+ *   out_tokens device int32 [max_new] (out): the tokens produced, in order (tok_in[m-1] itself is
+ *           not repeated);
+ *   stats   host (out).
+ * An EAGLE context needs max_m >= depth + 1.  The accepted length of every iteration is read
+ * back (one 4-byte copy and a stream synchronisation per iteration), so the call returns with
+ * the stream idle.  Uses buffers inside the workspace; batch > 1 is not supported here. */
+koala_status koala_generate(koala_ctx *ctx, void *hip_stream, const float *feat_in,
+                            const int32_t *tok_in, int m, int ctx_len0, int max_new, int use_draft,
+                            int32_t *out_tokens, koala_gen_stats *stats);
+
 /* Measurement aid for benchmarks (not part of the method).  Between koala_profile_begin and
  * koala_profile_end every weight-streaming GEMM launch of the bfloat16 path carries a pair
  * of HIP events bound to its own dispatch on the call's stream, which take the kernel's begin and

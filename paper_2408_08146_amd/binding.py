@@ -8,8 +8,8 @@ KOALA_FP32, KOALA_BF16 = 0, 1
 KOALA_DRAFT_EAGLE, KOALA_DRAFT_MEDUSA = 0, 1
 
 EXPORTS = ("koala_create", "koala_workspace_bytes", "koala_bind", "koala_draft_expand",
-           "koala_tree_verify", "koala_accept_prefix", "koala_profile_begin", "koala_profile_end",
-           "koala_last_error", "koala_destroy")
+           "koala_tree_verify", "koala_accept_prefix", "koala_generate", "koala_profile_begin",
+           "koala_profile_end", "koala_last_error", "koala_destroy")
 
 _STATUS = {0: "KOALA_OK", -1: "KOALA_E_NULL", -2: "KOALA_E_SHAPE", -3: "KOALA_E_ALIGN",
            -4: "KOALA_E_CAPACITY", -5: "KOALA_E_UNSUPPORTED", -6: "KOALA_E_WORKSPACE",
@@ -43,6 +43,10 @@ class _Weights(C.Structure):
                 ("draft_w", C.POINTER(C.c_void_p))]
 
 
+class _GenStats(C.Structure):
+    _fields_ = [("iterations", C.c_int32), ("tokens", C.c_int32), ("accept_hist", C.c_int32 * 64)]
+
+
 class _KV(C.Structure):
     _fields_ = [("target_k", C.c_void_p), ("target_v", C.c_void_p), ("draft_k", C.c_void_p),
                 ("draft_v", C.c_void_p), ("capacity", C.c_int), ("ctx_len", C.c_void_p)]
@@ -72,13 +76,14 @@ def load_library():
     lib.koala_draft_expand.argtypes = [vp, vp, ip, vp, vp, ip, vp, vp]
     lib.koala_tree_verify.argtypes = [vp, vp, ip, vp, vp, vp, vp]
     lib.koala_accept_prefix.argtypes = [vp, vp, ip, vp, vp, vp, vp, vp, ip]
+    lib.koala_generate.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp, C.POINTER(_GenStats)]
     lib.koala_profile_begin.argtypes = [vp, ip]
     lib.koala_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(ip), C.POINTER(C.c_double)]
     lib.koala_last_error.argtypes = [vp]
     lib.koala_last_error.restype = C.c_char_p
     lib.koala_destroy.argtypes = [vp]
     lib.koala_destroy.restype = None
-    for n in EXPORTS[:8]:
+    for n in EXPORTS[:9]:
         getattr(lib, n).restype = C.c_int
     _LIB = lib
     return lib
@@ -161,6 +166,13 @@ class KoalaContext:
         self._check(self.lib.koala_accept_prefix(self._h, _stream(stream), batch, _ptr(tree_tokens), _ptr(greedy),
                                                  _ptr(accept_len), _ptr(accept_path), _ptr(next_token),
                                                  1 if commit else 0))
+
+    def generate(self, feat_in, tok_in, m, ctx_len0, max_new, out_tokens, use_draft=True, stream=None):
+        """Returns dict(iterations, tokens, accept_hist[list])."""
+        st = _GenStats()
+        self._check(self.lib.koala_generate(self._h, _stream(stream), _ptr(feat_in), _ptr(tok_in), m, ctx_len0,
+                                            max_new, 1 if use_draft else 0, _ptr(out_tokens), C.byref(st)))
+        return dict(iterations=st.iterations, tokens=st.tokens, accept_hist=list(st.accept_hist))
 
     def profile_begin(self, max_launches=4096):
         self._check(self.lib.koala_profile_begin(self._h, max_launches))

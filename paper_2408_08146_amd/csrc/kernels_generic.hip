@@ -415,6 +415,31 @@ __global__ void k_advance(int32_t *ctx_len, const int32_t *accept_len, int batch
     if (b < batch) ctx_len[b] += accept_len[b] + 1;
 }
 
+// Inputs of the next draft step from one accepted path (one sequence): block i <= a copies the
+// feature of path node i to row i and sets tok_next[i] to the token that follows it (the next
+// path node's token, or the target's own token after the last accepted node); the same tokens are
+// appended to out_tokens[n_done + i] while that index is below max_new.  grid D+1 blocks.
+__global__ void k_gen_next(const float *feat_out, const int32_t *tree_tokens, const int32_t *accept_len,
+                           const int32_t *accept_path, const int32_t *next_token, int T, int H, float *feat_next,
+                           int32_t *tok_next, int32_t *out_tokens, int n_done, int max_new) {
+    const int i = blockIdx.x, a = accept_len[0];
+    if (i > a) return;
+    const int node = accept_path[i];
+    if (node < 0 || node >= T) return;   // never for a path the accept scan wrote
+    const float *src = feat_out + (size_t)node * H;
+    float *dst = feat_next + (size_t)i * H;
+    for (int j = threadIdx.x; j < H; j += blockDim.x) dst[j] = src[j];
+    if (threadIdx.x == 0) {
+        int32_t tok = next_token[0];
+        if (i < a) {
+            const int nx = accept_path[i + 1];
+            if (nx >= 0 && nx < T) tok = tree_tokens[nx];
+        }
+        tok_next[i] = tok;
+        if (n_done + i < max_new) out_tokens[n_done + i] = tok;
+    }
+}
+
 inline int cdiv(size_t a, size_t b) { return (int)((a + b - 1) / b); }
 
 }  // namespace
@@ -567,6 +592,13 @@ void advance_ctx(hipStream_t s, int32_t *ctx_len, const int32_t *accept_len, int
 // dst[b * dst_stride + j] = x[(b*m + m-1) * H + j]: the newest row of every sequence
 void gather_last_rows(hipStream_t s, const float *x, float *dst, size_t dst_stride, int batch, int m, int H) {
     k_gather_last<<<batch, 256, 0, s>>>(x, dst, dst_stride, m, H);
+}
+
+void gen_next(hipStream_t s, const float *feat_out, const int32_t *tree_tokens, const int32_t *accept_len,
+              const int32_t *accept_path, const int32_t *next_token, int T, int D, int H, float *feat_next,
+              int32_t *tok_next, int32_t *out_tokens, int n_done, int max_new) {
+    k_gen_next<<<D + 1, 256, 0, s>>>(feat_out, tree_tokens, accept_len, accept_path, next_token, T, H, feat_next,
+                                     tok_next, out_tokens, n_done, max_new);
 }
 
 }  // namespace kg

@@ -77,6 +77,17 @@ size_t carve(koala_ctx *c, char *base) {
     c->topk_val = w.take<float>((size_t)R * KOALA_TOPK_MAX);
     c->topk_idx = w.take<int32_t>((size_t)R * KOALA_TOPK_MAX);
     c->tok_tmp = w.take<int32_t>(R);
+    {
+        const int gm = std::max(D + 1, c->draft.max_m);
+        c->gen_feat = w.take<float>((size_t)T * H);
+        c->gen_feat_in = w.take<float>((size_t)gm * H);
+        c->gen_tree = w.take<int32_t>(T);
+        c->gen_greedy = w.take<int32_t>(T);
+        c->gen_acc = w.take<int32_t>(1);
+        c->gen_path = w.take<int32_t>(D + 1);
+        c->gen_next = w.take<int32_t>(1);
+        c->gen_tok_in = w.take<int32_t>(gm);
+    }
     c->xf = nullptr;
     c->part = nullptr;
     c->xf_bytes = c->part_bytes = 0;
@@ -518,6 +529,74 @@ koala_status koala_accept_prefix(koala_ctx *c, void *hip_stream, int batch, cons
         kg::advance_ctx(st, c->kv.ctx_len, accept_len, batch);
     }
     KOALA_CHECK_LAUNCH(c);
+    return KOALA_OK;
+}
+
+koala_status koala_generate(koala_ctx *c, void *hip_stream, const float *feat_in, const int32_t *tok_in, int m,
+                            int ctx_len0, int max_new, int use_draft, int32_t *out_tokens, koala_gen_stats *stats) {
+    koala_status st0 = check_call(c, 1);
+    if (st0 != KOALA_OK) return st0;
+    if (!tok_in || !out_tokens || !stats || (use_draft && !feat_in))
+        return fail(c, KOALA_E_NULL, "generate: tok_in, out_tokens and stats are required (feat_in too when drafting)");
+    const koala_shape &s = c->shape;
+    const bool eagle = c->draft.kind == KOALA_DRAFT_EAGLE;
+    if (m < 1 || m > c->draft.max_m) return fail(c, KOALA_E_SHAPE, "generate: m must be in 1..max_m");
+    if (max_new < 1) return fail(c, KOALA_E_SHAPE, "generate: max_new must be positive");
+    if (!use_draft && c->T != 1)
+        return fail(c, KOALA_E_SHAPE, "generate: plain decoding (use_draft = 0) needs a single-node tree");
+    if (use_draft && eagle && c->draft.max_m < c->D + 1)
+        return fail(c, KOALA_E_SHAPE, "generate: the draft head needs max_m >= depth + 1 catch-up rows");
+    // every iteration needs rows C .. C + n_nodes - 1 of the caches; C grows by at most depth + 1 per iteration
+    if (ctx_len0 < m || (long long)ctx_len0 + max_new + c->D + c->T > c->kv.capacity)
+        return fail(c, KOALA_E_SHAPE, "generate: ctx_len0 + max_new + depth + n_nodes exceeds the cache capacity");
+    hipStream_t st = (hipStream_t)hip_stream;
+    memset(stats, 0, sizeof(*stats));
+    {
+        int32_t c_dev = -1;
+        if (hipMemcpyAsync(&c_dev, c->kv.ctx_len, sizeof(c_dev), hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess)
+            return fail(c, KOALA_E_DEVICE, "generate: reading ctx_len[0] failed");
+        if (c_dev != ctx_len0) return fail(c, KOALA_E_SHAPE, "generate: ctx_len0 differs from ctx_len[0] on the device");
+    }
+    if (hipMemcpyAsync(c->gen_tok_in, tok_in, (size_t)m * sizeof(int32_t), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(c, KOALA_E_DEVICE, "generate: copy of tok_in failed");
+    if (use_draft && hipMemcpyAsync(c->gen_feat_in, feat_in, (size_t)m * s.hidden * sizeof(float),
+                                    hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(c, KOALA_E_DEVICE, "generate: copy of feat_in failed");
+    int n_done = 0, cur_m = m;
+    while (n_done < max_new) {
+        koala_status r;
+        if (use_draft) {
+            r = koala_draft_expand(c, st, 1, c->gen_feat_in, c->gen_tok_in, cur_m, c->gen_tree, nullptr);
+            if (r != KOALA_OK) return r;
+        } else {
+            kg::set_root(st, c->gen_tok_in, cur_m, c->gen_tree, nullptr, 1, c->T);
+        }
+        r = koala_tree_verify(c, st, 1, c->gen_tree, c->gen_feat, nullptr, c->gen_greedy);
+        if (r != KOALA_OK) return r;
+        r = koala_accept_prefix(c, st, 1, c->gen_tree, c->gen_greedy, c->gen_acc, c->gen_path, c->gen_next, 1);
+        if (r != KOALA_OK) return r;
+        kg::gen_next(st, c->gen_feat, c->gen_tree, c->gen_acc, c->gen_path, c->gen_next, c->T, c->D, s.hidden,
+                     c->gen_feat_in, c->gen_tok_in, out_tokens, n_done, max_new);
+        KOALA_CHECK_LAUNCH(c);
+        int32_t a = -1;
+        if (hipMemcpyAsync(&a, c->gen_acc, sizeof(a), hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess)
+            return fail(c, KOALA_E_DEVICE, "generate: reading the accepted length failed");
+        if (a < 0 || a > c->D) return fail(c, KOALA_E_DEVICE, "generate: accepted length out of range");
+        stats->accept_hist[a] += 1;
+        stats->iterations += 1;
+        n_done += a + 1;
+        cur_m = eagle && use_draft ? a + 1 : 1;
+        if (!(eagle && use_draft) && a > 0) {
+            // only the newest row is needed: move row a of the next inputs to row 0
+            if (hipMemcpyAsync(c->gen_tok_in, c->gen_tok_in + a, sizeof(int32_t), hipMemcpyDeviceToDevice, st) != hipSuccess ||
+                hipMemcpyAsync(c->gen_feat_in, c->gen_feat_in + (size_t)a * s.hidden, (size_t)s.hidden * sizeof(float),
+                               hipMemcpyDeviceToDevice, st) != hipSuccess)
+                return fail(c, KOALA_E_DEVICE, "generate: moving the newest row failed");
+        }
+    }
+    stats->tokens = n_done;
     return KOALA_OK;
 }
 

@@ -57,6 +57,9 @@ struct koala_ctx {
     RowMeta meta;
     float *x, *act, *qkv, *qrot, *attn_out, *gu, *o_part, *ml, *logits, *fhat, *topk_val;
     int32_t *topk_idx, *tok_tmp;
+    // generation loop state of sequence 0 (koala_generate)
+    float *gen_feat, *gen_feat_in;                       // [T][H] verify features; [max(D+1, max_m)][H] next draft inputs
+    int32_t *gen_tree, *gen_greedy, *gen_acc, *gen_path, *gen_next, *gen_tok_in;
     // bf16 path: GEMM input as hi/lo bf16 MFMA fragments, and the split-K partial sums
     void *xf;
     float *part;
@@ -130,6 +133,10 @@ void kv_commit(hipStream_t s, bool bf16, void *kcache, void *vcache, const int32
                const int32_t *accept_len, const int32_t *accept_path, int D, int n_layers,
                int max_batch, int batch, int n_heads, int capacity, int head_dim);
 void advance_ctx(hipStream_t s, int32_t *ctx_len, const int32_t *accept_len, int batch);
+// generation loop: next draft inputs (rows 0..a) and emitted tokens from the accepted path of sequence 0
+void gen_next(hipStream_t s, const float *feat_out, const int32_t *tree_tokens, const int32_t *accept_len,
+              const int32_t *accept_path, const int32_t *next_token, int T, int D, int H, float *feat_next,
+              int32_t *tok_next, int32_t *out_tokens, int n_done, int max_new);
 
 }  // namespace kg
 
