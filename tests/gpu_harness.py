@@ -31,7 +31,7 @@ def _round(cfg, x):
 
 class Case:
     def __init__(self, name, device="cuda", n_layers=None, norm_gain="random", batch=None, ctx=None,
-                 K=None, max_m=None, make_gpu=True, kv_storage_rounding=False, **over):
+                 K=None, max_m=None, make_gpu=True, kv_storage_rounding=False, weights=None, **over):
         import torch
         cfg = get_config(name, **over)
         if n_layers is not None:
@@ -46,10 +46,13 @@ class Case:
         self.B, self.T, self.D = cfg["batch"], self.tree.n_nodes, self.tree.depth
         self.H, self.V = cfg["hidden"], cfg["vocab"]
         self.tol = TOL[cfg["dtype"]]
-        self.Wt = target_weights(cfg, SEED_WEIGHTS, norm_gain=norm_gain, cache=True)
         self.eagle = cfg["draft"] == "eagle"
-        self.Wd = (eagle_weights if self.eagle else medusa_weights)(
-            cfg, SEED_WEIGHTS, **({"norm_gain": norm_gain} if self.eagle else {}), cache=True)
+        if weights is not None:          # weights: function cfg -> (target, draft) weight providers
+            self.Wt, self.Wd = weights(cfg)
+        else:
+            self.Wt = target_weights(cfg, SEED_WEIGHTS, norm_gain=norm_gain, cache=True)
+            self.Wd = (eagle_weights if self.eagle else medusa_weights)(
+                cfg, SEED_WEIGHTS, **({"norm_gain": norm_gain} if self.eagle else {}), cache=True)
         if isinstance(cfg["ctx"], tuple):
             lo, hi = cfg["ctx"]
             self.ctx_lens = [int(v) for v in tensor_uniform_int(SEED_LENGTHS, "ctx_lens", (self.B,), lo, hi + 1)]
@@ -157,6 +160,18 @@ class Case:
         self.gpu.tree_verify(B, tt, feat, logits, greedy)
         torch.cuda.synchronize()
         return feat.cpu().numpy(), (logits.cpu().numpy() if want_logits else None), greedy.cpu().numpy()
+
+    def gpu_generate(self, feat_in, tok_in, max_new, use_draft=True):
+        """koala_generate on sequence 0.  Returns (tokens[max_new], stats dict)."""
+        torch = self.torch
+        feat_in = np.asarray(feat_in, np.float32).reshape(-1, self.H)
+        tok_in = np.asarray(tok_in, np.int32).reshape(-1)
+        m = len(tok_in)
+        out = torch.full((max_new,), -1, dtype=torch.int32, device=self.device)
+        stats = self.gpu.generate(self.t(feat_in), self.t(tok_in), m, self.ctx_lens[0], max_new, out,
+                                  use_draft=use_draft)
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), stats
 
     def gpu_draft(self, feat_in, tok_in):
         torch = self.torch
