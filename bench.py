@@ -67,6 +67,102 @@ def device_weights(cfg, torch, K, dev):
     return w
 
 
+def predictable_device_weights(cfg, torch, K, dev, sigma, gain=4.0):
+    """Device-side build of the weight pair koala_synth.predictable_pair describes (greedy successor of
+    token t is t+1; the draft's ranking of it is perturbed by sigma), in the library's layout."""
+    import paper_2408_08146_amd as KO
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    H, F, V = cfg["hidden"], cfg["ffn"], cfg["vocab"]
+    bf = torch.bfloat16
+
+    def mat(n, k):
+        return (torch.randn(n, k, generator=g, device=dev, dtype=torch.float32) * 0.02).to(bf)
+
+    def layer():
+        one = torch.ones(H, dtype=bf, device=dev)
+        return (one, KO.fragment_major(mat(3 * H, H)), KO.fragment_major(torch.zeros(H, H, dtype=bf, device=dev)),
+                one.clone(), KO.fragment_major(mat(2 * F, H)), KO.fragment_major(torch.zeros(H, F, dtype=bf, device=dev)))
+
+    embed = mat(V, H)
+    lm = (torch.roll(embed.float(), 1, dims=0) * (gain / 0.02)).to(bf)
+    w = dict(embed=embed, lm_head=KO.fragment_major(lm), final_norm=torch.ones(H, dtype=bf, device=dev),
+             layers=[layer() for _ in range(cfg["n_layers"])])
+    fc = torch.zeros(H, 2 * H, dtype=torch.float32, device=dev)
+    fc[:, :H] = torch.eye(H, device=dev)
+    if sigma:
+        fc[:, :H] += sigma / H ** 0.5 * torch.randn(H, H, generator=g, device=dev, dtype=torch.float32)
+    w["fc"] = KO.fragment_major(fc.to(bf))
+    w["draft"] = [t for _ in range(K) for t in layer()]
+    return w
+
+
+def generation_bench(args):
+    """Generation loop (sections 2.2, 4.1): tokens per second of speculative decoding against plain
+    autoregressive decoding with the same target on the same device, mean tokens per iteration and the
+    accepted-length histogram, for a synthetic weight pair of adjustable draft quality."""
+    import torch
+    import paper_2408_08146_amd as KO
+    from koala_synth import get_config, make_tree
+    dev = "cuda:0"
+    cfg = get_config(args.config)
+    assert cfg["dtype"] == "bf16" and cfg["draft"] == "eagle"
+    if cfg["batch"] != 1 or isinstance(cfg["ctx"], tuple):      # the loop runs one sequence: take the shape only
+        cfg["batch"], cfg["ctx"] = 1, 1024
+    if args.layers:
+        cfg["n_layers"] = args.layers
+    K = args.K if args.K > 0 else (1 if args.config == "cfg2" else cfg["K"])
+    tree = cfg["tree_template"]
+    T, D, H, V = tree.n_nodes, tree.depth, cfg["hidden"], cfg["vocab"]
+    C, N = int(cfg["ctx"]), args.generate
+    cap = C + N + D + T + 64
+    shape = dict(hidden=H, n_heads=cfg["n_heads"], head_dim=cfg["head_dim"], ffn=cfg["ffn"], vocab=V,
+                 n_layers=cfg["n_layers"], rms_eps=cfg["rms_eps"], rope_base=cfg["rope_base"], dtype=KO.KOALA_BF16)
+    w = (predictable_device_weights(cfg, torch, K, dev, args.sigma) if args.sigma >= 0
+         else device_weights(cfg, torch, K, dev))
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    kv = KO.alloc_kv(cfg, 1, cap, dev, K)
+    for name in ("target_k", "target_v", "draft_k", "draft_v"):
+        for l in range(kv[name].shape[0]):
+            view = kv[name][l, 0, :, :C]
+            view.copy_(torch.randn(view.shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16))
+    spec = KO.KoalaContext(shape, dict(kind=KO.KOALA_DRAFT_EAGLE, K=K, medusa_heads=0, max_m=D + 1), tree, 1)
+    plain = KO.KoalaContext(shape, dict(kind=KO.KOALA_DRAFT_EAGLE, K=K, medusa_heads=0, max_m=1),
+                            make_tree([], [1]), 1)
+    ws = torch.empty(max(spec.workspace_bytes(), plain.workspace_bytes()), dtype=torch.uint8, device=dev)
+    feat_in = torch.randn(1, H, generator=g, device=dev, dtype=torch.float32)
+    tok_in = torch.tensor([123], dtype=torch.int32, device=dev)
+    out = torch.zeros(N, dtype=torch.int32, device=dev)
+    res = {}
+    for name, c, use_draft in (("plain", plain, False), ("speculative", spec, True)):
+        c.bind(w, kv, ws)
+        best = None
+        for rep in range(args.warmup_gen + args.repeat_gen):
+            kv["ctx_len"].fill_(C)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st = c.generate(feat_in, tok_in, 1, C, N, out, use_draft=use_draft)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            if rep >= args.warmup_gen and (best is None or dt < best[0]):
+                best = (dt, st)
+        dt, st = best
+        res[name] = dict(seconds=dt, iterations=st["iterations"], tokens=st["tokens"],
+                         tokens_per_s=st["tokens"] / dt, ms_per_iteration=dt / st["iterations"] * 1e3,
+                         mean_tokens_per_iteration=st["tokens"] / st["iterations"],
+                         accept_hist=st["accept_hist"][:D + 1], first_tokens=out[:4].tolist())
+    ratio = res["speculative"]["tokens_per_s"] / res["plain"]["tokens_per_s"]
+    print(json.dumps({
+        "metric": "speedup_over_autoregressive_decoding", "value": ratio, "unit": "x", "n_gpus": 1,
+        "higher_is_better": True, "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config}: generation of {N} tokens after a {C}-token context, EAGLE-style K={K}, "
+                               f"T={T} depth {D}, {cfg['n_layers']} target layers, batch 1",
+                   "weights": (f"predictable pair, sigma={args.sigma}" if args.sigma >= 0 else "random"),
+                   "best_of": args.repeat_gen},
+        "speculative": res["speculative"], "plain": res["plain"]}))
+
+
 def cpu_baseline(cfg, tree, K, levels):
     """Time the unmodified fp32 oracle on a bounded sample: tree_verify over 2 of the target layers
     plus final norm / LM head / argmax, and one EAGLE draft pass (fc + K layers + LM head + top-k) for
@@ -143,10 +239,20 @@ def main():
     ap.add_argument("--graph", type=int, default=0, help="1: replay the iteration as a captured HIP graph")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="MiB: first run one plain device copy of this size (reference for counter scaling)")
+    ap.add_argument("--generate", type=int, default=0,
+                    help="N > 0: instead of the iteration benchmark, generate N tokens with and without the draft "
+                         "head and report the speed-up ratio and tokens per iteration")
+    ap.add_argument("--sigma", type=float, default=-1.0,
+                    help="--generate: draft-quality knob of the predictable weight pair (0 = perfect draft); "
+                         "negative = random weights (the draft is almost never right)")
+    ap.add_argument("--warmup-gen", type=int, default=1)
+    ap.add_argument("--repeat-gen", type=int, default=3)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    if args.generate > 0:
+        return generation_bench(args)
 
     import torch
     import paper_2408_08146_amd as KO
