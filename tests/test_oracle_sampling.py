@@ -1,0 +1,189 @@
+"""Pins for the oracle's non-greedy drafting and acceptance (sections 2.2 and 4.4).
+
+What fixes the rule from outside: the emitted tokens must be distributed exactly as samples of
+the target (checked by Monte Carlo on small vocabularies, for a chain and for trees with several
+children), the closed-form special cases d = q (always accept), disjoint supports (always
+reject, replacement from q), a one-hot draft (accept with probability q(x)), and the textbook
+frequencies of draws without replacement."""
+import numpy as np
+import pytest
+
+import oracle
+from koala_synth import make_tree, chain_tree
+
+
+def _rand_dist(rng, V, sharp=1.0):
+    return oracle.softmax_t(rng.normal(size=V) * sharp)
+
+
+def _simulate(tree, q_of, d_of, n_trials, rng, V):
+    """Draft by sampling children from d_of(prefix tokens), accept with q_of(prefix tokens).
+    Returns the emitted token sequences."""
+    T = tree.n_nodes
+    ch = [sorted(k, key=lambda c: tree.rank[c]) for k in oracle.children_lists(tree.parent)]
+    outs = []
+    for _ in range(n_trials):
+        tokens = np.zeros(T, np.int64)
+        prefix = {0: ()}
+        q_rows, d_rows = {}, {}
+        for u in range(T):                                   # BFS order: parents first
+            q_rows[u] = q_of(prefix[u])
+            if ch[u]:
+                d_rows[u] = d_of(prefix[u])
+                draws = oracle.draw_without_replacement(d_rows[u], rng.random(len(ch[u])))
+                for c, x in zip(ch[u], draws):
+                    tokens[c] = x
+                    prefix[c] = prefix[u] + (x,)
+        a, path, nxt = oracle.accept_sample(tokens, tree.parent, tree.rank, q_rows, d_rows, rng.random(T),
+                                            rng.random(T))
+        outs.append(tuple(int(tokens[p]) for p in path[1:]) + (nxt,))
+    return outs
+
+
+def _tables(V, seed):
+    rng = np.random.default_rng(seed)
+    q0, d0 = _rand_dist(rng, V, 1.5), _rand_dist(rng, V, 1.5)
+    q1 = {x: _rand_dist(rng, V, 1.5) for x in range(V)}
+    d1 = {x: _rand_dist(rng, V, 1.5) for x in range(V)}
+    q_of = lambda pre: q0 if len(pre) == 0 else q1[pre[-1]] if len(pre) == 1 else q0
+    d_of = lambda pre: d0 if len(pre) == 0 else d1[pre[-1]]
+    return q0, q1, q_of, d_of
+
+
+@pytest.mark.parametrize("tree", [chain_tree(2), make_tree([2, 2], [1, 2, 3]), make_tree([3], [1, 3])],
+                         ids=["chain2", "tree_2_2", "star3"])
+def test_emitted_tokens_are_distributed_as_the_target(tree):
+    V, n = 5, 40000
+    q0, q1, q_of, d_of = _tables(V, 11)
+    rng = np.random.default_rng(5)
+    outs = _simulate(tree, q_of, d_of, n, rng, V)
+    first = np.bincount([o[0] for o in outs], minlength=V) / n
+    sd = np.sqrt(q0 * (1 - q0) / n)
+    assert np.all(np.abs(first - q0) < 4.5 * sd), (first, q0)
+    # joint of the first two tokens: q0(x1) * q1[x1](x2)  (every trial emits at least one token;
+    # those that emit two or more are a biased subset, so condition on nothing: extend by sampling)
+    pair = np.zeros((V, V))
+    for o in outs:
+        x1 = o[0]
+        x2 = o[1] if len(o) > 1 else oracle.inverse_cdf(q1[x1], rng.random())
+        pair[x1, x2] += 1
+    pair /= n
+    want = np.array([[q0[a] * q1[a][b] for b in range(V)] for a in range(V)])
+    sd2 = np.sqrt(want * (1 - want) / n)
+    assert np.all(np.abs(pair - want) < 4.5 * sd2 + 1e-9)
+
+
+def test_identical_distributions_accept_everything():
+    tree = chain_tree(3)
+    rng = np.random.default_rng(1)
+    p = _rand_dist(rng, 7)
+    for _ in range(200):
+        toks = np.array([0] + [oracle.inverse_cdf(p, rng.random()) for _ in range(3)])
+        a, path, nxt = oracle.accept_sample(toks, tree.parent, tree.rank, {i: p for i in range(4)},
+                                            {i: p for i in range(4)}, rng.random(4), rng.random(4))
+        assert a == 3 and path == [0, 1, 2, 3]
+
+
+def test_disjoint_supports_reject_and_resample_from_the_target():
+    tree = make_tree([2], [1, 2])
+    q = np.array([0.5, 0.5, 0, 0, 0, 0.0])
+    d = np.array([0, 0, 0.25, 0.25, 0.25, 0.25])
+    rng = np.random.default_rng(2)
+    cnt = np.zeros(6)
+    for _ in range(4000):
+        draws = oracle.draw_without_replacement(d, rng.random(2))
+        toks = np.array([0] + draws)
+        a, path, nxt = oracle.accept_sample(toks, tree.parent, tree.rank, {0: q, 1: q, 2: q}, {0: d}, rng.random(3),
+                                            rng.random(3))
+        assert a == 0 and path == [0]
+        cnt[nxt] += 1
+    assert cnt[2:].sum() == 0 and abs(cnt[0] / 4000 - 0.5) < 0.04
+
+
+def test_one_hot_draft_is_kept_with_the_target_probability():
+    """d = point mass at x: keep x with probability q(x), otherwise draw from q without x."""
+    tree = chain_tree(1)
+    q = np.array([0.1, 0.6, 0.3])
+    d = np.array([0.0, 1.0, 0.0])
+    toks = np.array([0, 1])
+    qs = {0: q, 1: q}
+    a, _, _ = oracle.accept_sample(toks, tree.parent, tree.rank, qs, {0: d}, [0, 0.59], [0, 0])
+    assert a == 1
+    a, _, nxt = oracle.accept_sample(toks, tree.parent, tree.rank, qs, {0: d}, [0, 0.61], [0.2, 0])
+    assert a == 0 and nxt == 0          # residual = (0.25, 0, 0.75): u = 0.2 -> token 0
+    a, _, nxt = oracle.accept_sample(toks, tree.parent, tree.rank, qs, {0: d}, [0, 0.61], [0.3, 0])
+    assert a == 0 and nxt == 2
+
+
+def test_section_2_2_worked_example_by_hand():
+    """q = (.5,.3,.2), d = (.2,.2,.6), drafted token 2: keep with probability .2/.6 = 1/3;
+    on rejection the replacement comes from norm(max(0, q-d)) = (.75, .25, 0)."""
+    tree = chain_tree(1)
+    q, d = np.array([0.5, 0.3, 0.2]), np.array([0.2, 0.2, 0.6])
+    toks = np.array([0, 2])
+    a, _, _ = oracle.accept_sample(toks, tree.parent, tree.rank, {0: q, 1: q}, {0: d}, [0, 0.33], [0, 0])
+    assert a == 1
+    a, _, nxt = oracle.accept_sample(toks, tree.parent, tree.rank, {0: q, 1: q}, {0: d}, [0, 0.34], [0.74, 0])
+    assert (a, nxt) == (0, 0)
+    a, _, nxt = oracle.accept_sample(toks, tree.parent, tree.rank, {0: q, 1: q}, {0: d}, [0, 0.34], [0.76, 0])
+    assert (a, nxt) == (0, 1)
+
+
+def test_draws_without_replacement_have_textbook_frequencies():
+    rng = np.random.default_rng(3)
+    d = np.array([0.5, 0.3, 0.15, 0.05])
+    n = 40000
+    first = np.zeros(4)
+    pair = np.zeros((4, 4))
+    for _ in range(n):
+        i, j = oracle.draw_without_replacement(d, rng.random(2))
+        assert i != j
+        first[i] += 1
+        pair[i, j] += 1
+    assert np.all(np.abs(first / n - d) < 4.5 * np.sqrt(d * (1 - d) / n))
+    want = np.array([[0 if i == j else d[i] * d[j] / (1 - d[i]) for j in range(4)] for i in range(4)])
+    assert np.all(np.abs(pair / n - want) < 4.5 * np.sqrt(want * (1 - want) / n) + 1e-9)
+
+
+def test_inverse_cdf_against_brute_force():
+    rng = np.random.default_rng(4)
+    for _ in range(300):
+        p = rng.random(9) * (rng.random(9) > 0.3)
+        if p.sum() == 0:
+            continue
+        u = rng.random()
+        run, want = 0.0, None
+        for i, v in enumerate(p):
+            run += v
+            if run > u * p.sum():
+                want = i
+                break
+        assert oracle.inverse_cdf(p, u) == want
+        assert p[want] > 0
+    assert oracle.inverse_cdf([0.25, 0.25, 0.5], 0.0) == 0
+    assert oracle.inverse_cdf([0.25, 0.25, 0.5], 0.4999) == 1
+    assert oracle.inverse_cdf([0.25, 0.25, 0.5], 0.5) == 2
+
+
+def test_sampled_draft_reduces_to_top1_at_low_temperature():
+    """temperature -> 0 puts all mass on the argmax, so a chain drafted by sampling equals the
+    greedy draft's rank-0 chain."""
+    from helpers import NANO
+    from koala_synth.weights import target_weights, eagle_weights
+    cfg = dict(NANO)
+    Wt = target_weights(cfg, 2, norm_gain="random", cache=True)
+    Wd = eagle_weights(cfg, 2, norm_gain="random", cache=True)
+    ch = chain_tree(3)
+    tc = oracle.KVCache(cfg["n_layers"], cfg["n_heads"], 32, cfg["head_dim"])
+    prompt = [3, 9, 27, 31]
+    feats, logits = oracle.prefill(cfg, Wt, tc, prompt)
+    root = int(np.argmax(logits[-1]))
+    tok_in = np.array(prompt[1:] + [root])
+    d1 = oracle.KVCache(cfg["K"], cfg["n_heads"], 32, cfg["head_dim"])
+    d2 = oracle.KVCache(cfg["K"], cfg["n_heads"], 32, cfg["head_dim"])
+    g = oracle.eagle_expand(cfg, Wt, Wd, d1, 4, feats, tok_in, ch.parent, ch.rank, ch.topk_per_depth)
+    s = oracle.eagle_expand_sample(cfg, Wt, Wd, d2, 4, feats, tok_in, ch.parent, ch.rank,
+                                   np.random.default_rng(0).random(4), temperature=1e-7)
+    np.testing.assert_array_equal(g["tokens"], s["tokens"])
+    for u in (0, 1, 2):
+        np.testing.assert_allclose(g["logits"][u], s["logits"][u], rtol=1e-12)
