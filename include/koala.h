@@ -186,6 +186,41 @@ koala_status koala_accept_prefix(koala_ctx *ctx, void *hip_stream, int batch,
                                  int32_t *accept_len, int32_t *accept_path, int32_t *next_token,
                                  int commit);
 
+/* Non-greedy drafting (section 2.2: the drafted tokens are drawn from the draft distributions;
+ * section 4.4 evaluates temperature 1).  As koala_draft_expand for an EAGLE-style head, but the
+ * children of a node are draws without replacement from softmax(draft logits at the node /
+ * temperature): the child of lowest rank is drawn first, each later one from what is left after
+ * removing the earlier draws, by inverse CDF over ascending token id (first id at which the
+ * running sum exceeds u * total).
+ *   u_draw       device fp32 [batch, n_nodes]: uniform in [0,1) used for the draw of each node
+ *                (entry 0, the root, is not used);
+ *   draft_logits device fp32 [batch, n_nodes, vocab] (out): row i = draft logits at node i, written
+ *                for the nodes that have children; koala_accept_sample reads them.
+ * Medusa-style heads: KOALA_E_UNSUPPORTED. */
+koala_status koala_draft_expand_sample(koala_ctx *ctx, void *hip_stream, int batch,
+                                       const float *feat_in, const int32_t *tok_in, int m,
+                                       const float *u_draw, float temperature,
+                                       int32_t *tree_tokens, float *draft_logits);
+
+/* Stochastic acceptance (section 2.2), per sequence: at the current node, with q = softmax(target
+ * logits / temperature) and d = softmax(draft logits / temperature), try the children in draw
+ * order: child with token x is accepted if u_accept[child] < min(1, q(x)/d(x)) and becomes the
+ * current node; after a rejection q <- norm(max(0, q - d)) (unchanged if that is all zero), x is
+ * removed from d and d renormalised.  Where no child is accepted, or the node has none,
+ * next_token is drawn from q by inverse CDF with u_resample[node].  On a chain template this is
+ * the rule of section 2.2 as printed; trying several children in turn is this build's reading for
+ * trees.  With the children drawn by koala_draft_expand_sample the emitted tokens are distributed
+ * as the target's own samples.
+ *   target_logits device fp32 [batch, n_nodes, vocab]: logits_out of koala_tree_verify;
+ *   draft_logits  device fp32 [batch, n_nodes, vocab]: from koala_draft_expand_sample;
+ *   u_accept, u_resample device fp32 [batch, n_nodes]: uniforms in [0,1);
+ *   outputs and commit as in koala_accept_prefix. */
+koala_status koala_accept_sample(koala_ctx *ctx, void *hip_stream, int batch,
+                                 const int32_t *tree_tokens, const float *target_logits,
+                                 const float *draft_logits, const float *u_accept,
+                                 const float *u_resample, float temperature, int32_t *accept_len,
+                                 int32_t *accept_path, int32_t *next_token, int commit);
+
 /* Statistics of a generation run.  accept_hist[a] counts the iterations that accepted exactly a
  * drafted tokens; from it follow the average number of tokens per iteration (section 4.1:
  * sum_a (a+1) accept_hist[a] / iterations) and, for a chain template, the n-alpha acceptance rates

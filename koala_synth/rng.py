@@ -62,6 +62,14 @@ def tensor_uniform_int(seed: int, name: str, shape, lo: int, hi: int) -> np.ndar
     return out.reshape(shape)
 
 
+def tensor_uniform01(seed: int, name: str, shape) -> np.ndarray:
+    """fp32 tensor uniform in [0, 1) (the random numbers of sampling tests; fp32 so that both
+    consumers read the very same values)."""
+    out = np.empty(int(np.prod(shape)), dtype=np.float32)
+    _fill(out, seed, name, lambda g, k: g.random(k, dtype=np.float32))
+    return out.reshape(shape)
+
+
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """Round fp32 to bfloat16 (nearest, ties to even); returns the uint16 bit patterns."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)

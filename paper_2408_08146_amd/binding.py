@@ -8,7 +8,8 @@ KOALA_FP32, KOALA_BF16 = 0, 1
 KOALA_DRAFT_EAGLE, KOALA_DRAFT_MEDUSA = 0, 1
 
 EXPORTS = ("koala_create", "koala_workspace_bytes", "koala_bind", "koala_draft_expand",
-           "koala_tree_verify", "koala_accept_prefix", "koala_generate", "koala_profile_begin",
+           "koala_tree_verify", "koala_accept_prefix", "koala_generate", "koala_draft_expand_sample",
+           "koala_accept_sample", "koala_profile_begin",
            "koala_profile_end", "koala_last_error", "koala_destroy")
 
 _STATUS = {0: "KOALA_OK", -1: "KOALA_E_NULL", -2: "KOALA_E_SHAPE", -3: "KOALA_E_ALIGN",
@@ -77,13 +78,15 @@ def load_library():
     lib.koala_tree_verify.argtypes = [vp, vp, ip, vp, vp, vp, vp]
     lib.koala_accept_prefix.argtypes = [vp, vp, ip, vp, vp, vp, vp, vp, ip]
     lib.koala_generate.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp, C.POINTER(_GenStats)]
+    lib.koala_draft_expand_sample.argtypes = [vp, vp, ip, vp, vp, ip, vp, C.c_float, vp, vp]
+    lib.koala_accept_sample.argtypes = [vp, vp, ip, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, ip]
     lib.koala_profile_begin.argtypes = [vp, ip]
     lib.koala_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(ip), C.POINTER(C.c_double)]
     lib.koala_last_error.argtypes = [vp]
     lib.koala_last_error.restype = C.c_char_p
     lib.koala_destroy.argtypes = [vp]
     lib.koala_destroy.restype = None
-    for n in EXPORTS[:9]:
+    for n in EXPORTS[:11]:
         getattr(lib, n).restype = C.c_int
     _LIB = lib
     return lib
@@ -173,6 +176,19 @@ class KoalaContext:
         self._check(self.lib.koala_generate(self._h, _stream(stream), _ptr(feat_in), _ptr(tok_in), m, ctx_len0,
                                             max_new, 1 if use_draft else 0, _ptr(out_tokens), C.byref(st)))
         return dict(iterations=st.iterations, tokens=st.tokens, accept_hist=list(st.accept_hist))
+
+    def draft_expand_sample(self, batch, feat_in, tok_in, m, u_draw, temperature, tree_tokens, draft_logits,
+                            stream=None):
+        self._check(self.lib.koala_draft_expand_sample(self._h, _stream(stream), batch, _ptr(feat_in), _ptr(tok_in), m,
+                                                       _ptr(u_draw), float(temperature), _ptr(tree_tokens),
+                                                       _ptr(draft_logits)))
+
+    def accept_sample(self, batch, tree_tokens, target_logits, draft_logits, u_accept, u_resample, temperature,
+                      accept_len, accept_path, next_token, commit, stream=None):
+        self._check(self.lib.koala_accept_sample(self._h, _stream(stream), batch, _ptr(tree_tokens),
+                                                 _ptr(target_logits), _ptr(draft_logits), _ptr(u_accept),
+                                                 _ptr(u_resample), float(temperature), _ptr(accept_len),
+                                                 _ptr(accept_path), _ptr(next_token), 1 if commit else 0))
 
     def profile_begin(self, max_launches=4096):
         self._check(self.lib.koala_profile_begin(self._h, max_launches))

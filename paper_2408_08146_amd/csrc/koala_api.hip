@@ -88,6 +88,8 @@ size_t carve(koala_ctx *c, char *base) {
         c->gen_next = w.take<int32_t>(1);
         c->gen_tok_in = w.take<int32_t>(gm);
     }
+    c->acc_q = w.take<float>((size_t)c->max_batch * V);
+    c->acc_d = w.take<float>((size_t)c->max_batch * V);
     c->xf = nullptr;
     c->part = nullptr;
     c->xf_bytes = c->part_bytes = 0;
@@ -409,14 +411,26 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
     return KOALA_OK;
 }
 
-koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const float *feat_in,
-                                const int32_t *tok_in, int m, int32_t *tree_tokens, float *tree_scores) {
+// u_draw == nullptr: children are the parent's top-k tokens by rank.  Otherwise they are draws without
+// replacement from softmax(draft logits / temperature) with the uniforms u_draw[b][child], and the logits of
+// every node that has children are stored to draft_logits[b][node][:].
+static koala_status draft_expand_impl(koala_ctx *c, void *hip_stream, int batch, const float *feat_in,
+                                      const int32_t *tok_in, int m, int32_t *tree_tokens, float *tree_scores,
+                                      const float *u_draw, float temperature, float *draft_logits) {
     koala_status st0 = check_call(c, batch);
     if (st0 != KOALA_OK) return st0;
     if (!feat_in || !tok_in || !tree_tokens) return fail(c, KOALA_E_NULL, "feat_in, tok_in, tree_tokens required");
     if (m < 1 || m > c->draft.max_m) return fail(c, KOALA_E_SHAPE, "m must be in 1..max_m");
-    if (!aligned16(feat_in) || !aligned16(tok_in) || !aligned16(tree_tokens) || !aligned16(tree_scores))
+    if (!aligned16(feat_in) || !aligned16(tok_in) || !aligned16(tree_tokens) || !aligned16(tree_scores) ||
+        !aligned16(u_draw) || !aligned16(draft_logits))
         return fail(c, KOALA_E_ALIGN, "device pointers must be 16-byte aligned");
+    const bool sampling = u_draw != nullptr;
+    if (sampling) {
+        if (!draft_logits) return fail(c, KOALA_E_NULL, "draft_logits is required when sampling");
+        if (!(temperature > 0.f)) return fail(c, KOALA_E_SHAPE, "temperature must be positive");
+        if (c->draft.kind != KOALA_DRAFT_EAGLE)
+            return fail(c, KOALA_E_UNSUPPORTED, "sampled drafting is implemented for the EAGLE-style head only");
+    }
     hipStream_t st = (hipStream_t)hip_stream;
     const koala_shape &s = c->shape;
     const bool bf = s.dtype == KOALA_BF16;
@@ -478,14 +492,25 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
                               (char *)c->kv.draft_v + ls * k);
         }
     };
-    // LM head + top-k on `rows` fp32 rows at a (row stride lda)
-    auto head_topk = [&](float *a, int lda, int rows, int k) {
+    // LM head on `rows` fp32 rows at a (row stride lda), then the children of the level's nodes: their
+    // parent's top-k tokens by rank, or draws from the parent's distribution
+    auto head_children = [&](float *a, int lda, int rows, int d, const int32_t *lv, int nl) {
+        const int k = c->topk[d];
         if (bf) {
-            bf_lm_head_topk(c, st, a, lda, rows, k, c->topk_idx, c->topk_val);
+            const int MT = kb::mt_of(rows), Vp = kb::pad64(V);
+            rows_to_frags(c, st, a, lda, rows, H, MT);
+            const int S = bf_gemm(c, st, c->w.lm_head, V, H, MT);
+            kb::logits_topk(st, c->part, S, MT * 16, Vp, no_scale(), sampling ? c->logits : nullptr, V, rows, V,
+                            sampling ? 1 : k, c->cand_val, c->cand_idx, c->topk_idx, c->topk_val);
         } else {
             kg::gemm(st, bf, a, lda, c->w.lm_head, c->logits, V, rows, V, H, false);
-            kg::topk_rows(st, c->logits, V, rows, V, k, c->topk_idx, c->topk_val);
+            if (!sampling) kg::topk_rows(st, c->logits, V, rows, V, k, c->topk_idx, c->topk_val);
         }
+        if (sampling)
+            ks::sample_children(st, c->logits, lv, nl, c->tt, T, V, temperature, u_draw, tree_tokens, draft_logits,
+                                batch);
+        else
+            kg::fill_children(st, c->topk_idx, c->topk_val, k, lv, nl, c->tt, d, tree_tokens, tree_scores, batch, T);
     };
     kg::setup_catchup(st, c, batch, m);
     kg::fc_input(st, bf, tok_in, c->w.embed, feat_in, c->act, batch * m, H);
@@ -493,9 +518,7 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
     if (D > 0) {
         // root's predicted feature -> fhat[b][0]; its logits decide the depth-1 tokens
         kg::gather_last_rows(st, c->x, c->fhat, (size_t)T * H, batch, m, H);
-        head_topk(c->fhat, T * H, batch, c->topk[0]);
-        kg::fill_children(st, c->topk_idx, c->topk_val, c->topk[0], c->tt.level_nodes, 1, c->tt, 0, tree_tokens,
-                          tree_scores, batch, T);
+        head_children(c->fhat, T * H, batch, 0, c->tt.level_nodes, 1);
     }
     for (int d = 1; d < D; ++d) {
         const int nl = (int)c->level_exp[d].size();
@@ -505,9 +528,44 @@ koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const
         kg::level_inputs(st, bf, tree_tokens, c->w.embed, c->fhat, lv, c->tt.parent, c->act, batch, nl, T, H);
         run_head(nl);
         kg::store_fhat(st, c->x, c->fhat, lv, batch, nl, T, H);
-        head_topk(c->x, H, batch * nl, c->topk[d]);
-        kg::fill_children(st, c->topk_idx, c->topk_val, c->topk[d], lv, nl, c->tt, d, tree_tokens, tree_scores,
-                          batch, T);
+        head_children(c->x, H, batch * nl, d, lv, nl);
+    }
+    KOALA_CHECK_LAUNCH(c);
+    return KOALA_OK;
+}
+
+koala_status koala_draft_expand(koala_ctx *c, void *hip_stream, int batch, const float *feat_in,
+                                const int32_t *tok_in, int m, int32_t *tree_tokens, float *tree_scores) {
+    return draft_expand_impl(c, hip_stream, batch, feat_in, tok_in, m, tree_tokens, tree_scores, nullptr, 1.f,
+                             nullptr);
+}
+
+koala_status koala_draft_expand_sample(koala_ctx *c, void *hip_stream, int batch, const float *feat_in,
+                                       const int32_t *tok_in, int m, const float *u_draw, float temperature,
+                                       int32_t *tree_tokens, float *draft_logits) {
+    if (c && !u_draw) return fail(c, KOALA_E_NULL, "u_draw is required");
+    return draft_expand_impl(c, hip_stream, batch, feat_in, tok_in, m, tree_tokens, nullptr, u_draw, temperature,
+                             draft_logits);
+}
+
+koala_status koala_accept_sample(koala_ctx *c, void *hip_stream, int batch, const int32_t *tree_tokens,
+                                 const float *target_logits, const float *draft_logits, const float *u_accept,
+                                 const float *u_resample, float temperature, int32_t *accept_len,
+                                 int32_t *accept_path, int32_t *next_token, int commit) {
+    koala_status st0 = check_call(c, batch);
+    if (st0 != KOALA_OK) return st0;
+    if (!tree_tokens || !target_logits || !u_accept || !u_resample || !accept_len || !accept_path || !next_token ||
+        (c->T > 1 && !draft_logits))
+        return fail(c, KOALA_E_NULL, "all accept_sample pointers are required");
+    if (!(temperature > 0.f)) return fail(c, KOALA_E_SHAPE, "temperature must be positive");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const koala_shape &s = c->shape;
+    ks::accept_sample(st, c->tt, c->T, c->D, s.vocab, temperature, tree_tokens, target_logits, draft_logits,
+                      u_accept, u_resample, c->acc_q, c->acc_d, accept_len, accept_path, next_token, batch);
+    if (commit) {
+        kg::kv_commit(st, s.dtype == KOALA_BF16, c->kv.target_k, c->kv.target_v, c->kv.ctx_len, accept_len,
+                      accept_path, c->D, s.n_layers, c->max_batch, batch, s.n_heads, c->kv.capacity, s.head_dim);
+        kg::advance_ctx(st, c->kv.ctx_len, accept_len, batch);
     }
     KOALA_CHECK_LAUNCH(c);
     return KOALA_OK;

@@ -60,6 +60,7 @@ struct koala_ctx {
     // generation loop state of sequence 0 (koala_generate)
     float *gen_feat, *gen_feat_in;                       // [T][H] verify features; [max(D+1, max_m)][H] next draft inputs
     int32_t *gen_tree, *gen_greedy, *gen_acc, *gen_path, *gen_next, *gen_tok_in;
+    float *acc_q, *acc_d;                                // [max_batch][V] distributions of the stochastic acceptance walk
     // bf16 path: GEMM input as hi/lo bf16 MFMA fragments, and the split-K partial sums
     void *xf;
     float *part;
@@ -139,6 +140,23 @@ void gen_next(hipStream_t s, const float *feat_out, const int32_t *tree_tokens, 
               int32_t *tok_next, int32_t *out_tokens, int n_done, int max_new);
 
 }  // namespace kg
+
+// ---------------------------------------------------------------------------------------------
+// launchers implemented in kernels_sampling.hip (non-greedy drafting and acceptance, section 2.2)
+// ---------------------------------------------------------------------------------------------
+namespace ks {
+
+// logits: [batch * n_level][V] draft logits of the level's nodes (overwritten); children of those nodes get
+// draws without replacement from softmax(logits / temperature); the logits are copied to draft_logits[b][node]
+void sample_children(hipStream_t st, float *logits, const int32_t *level_nodes, int n_level, const TreeTables &tt,
+                     int T, int V, float temperature, const float *u_draw, int32_t *tree_tokens,
+                     float *draft_logits, int batch);
+void accept_sample(hipStream_t st, const TreeTables &tt, int T, int D, int V, float temperature,
+                   const int32_t *tree_tokens, const float *target_logits, const float *draft_logits,
+                   const float *u_accept, const float *u_resample, float *qv, float *dv, int32_t *accept_len,
+                   int32_t *accept_path, int32_t *next_token, int batch);
+
+}  // namespace ks
 
 // ---------------------------------------------------------------------------------------------
 // launchers implemented in kernels_bf16.hip (fragment-major bf16 weights, hi/lo bf16 activations)

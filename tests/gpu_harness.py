@@ -173,6 +173,36 @@ class Case:
         torch.cuda.synchronize()
         return out.cpu().numpy(), stats
 
+    def gpu_draft_sample(self, feat_in, tok_in, u_draw, temperature=1.0):
+        """koala_draft_expand_sample.  Returns (tokens[B,T], draft_logits[B,T,V])."""
+        torch = self.torch
+        B, T = self.B, self.T
+        feat_in = np.asarray(feat_in, np.float32).reshape(B, -1, self.H)
+        tok_in = np.asarray(tok_in, np.int32).reshape(B, -1)
+        m = tok_in.shape[1]
+        tokens = torch.full((B, T), -1, dtype=torch.int32, device=self.device)
+        dl = torch.zeros(B, T, self.V, dtype=torch.float32, device=self.device)
+        self.gpu.draft_expand_sample(B, self.t(feat_in), self.t(tok_in), m,
+                                     self.t(np.asarray(u_draw, np.float32).reshape(B, T)), temperature, tokens, dl)
+        torch.cuda.synchronize()
+        return tokens.cpu().numpy(), dl
+
+    def gpu_accept_sample(self, tree_tokens, target_logits, draft_logits, u_accept, u_resample, temperature=1.0,
+                          commit=False):
+        """koala_accept_sample; logits may be numpy arrays or device tensors [B,T,V]."""
+        torch = self.torch
+        B, T, D = self.B, self.T, self.D
+        as_dev = lambda x: x if isinstance(x, torch.Tensor) else self.t(np.asarray(x, np.float32).reshape(B, T, self.V))
+        a = torch.full((B,), -7, dtype=torch.int32, device=self.device)
+        path = torch.full((B, D + 1), -7, dtype=torch.int32, device=self.device)
+        nxt = torch.full((B,), -7, dtype=torch.int32, device=self.device)
+        self.gpu.accept_sample(B, self.t(np.asarray(tree_tokens, np.int32).reshape(B, T)), as_dev(target_logits),
+                               as_dev(draft_logits), self.t(np.asarray(u_accept, np.float32).reshape(B, T)),
+                               self.t(np.asarray(u_resample, np.float32).reshape(B, T)), temperature, a, path, nxt,
+                               commit)
+        torch.cuda.synchronize()
+        return a.cpu().numpy(), path.cpu().numpy(), nxt.cpu().numpy()
+
     def gpu_draft(self, feat_in, tok_in):
         torch = self.torch
         B, T = self.B, self.T
