@@ -245,6 +245,8 @@ def main():
     ap.add_argument("--sigma", type=float, default=-1.0,
                     help="--generate: draft-quality knob of the predictable weight pair (0 = perfect draft); "
                          "negative = random weights (the draft is almost never right)")
+    ap.add_argument("--sample", type=int, default=0,
+                    help="1: time the non-greedy iteration (sampled draft, stochastic acceptance) instead of the greedy one")
     ap.add_argument("--warmup-gen", type=int, default=1)
     ap.add_argument("--repeat-gen", type=int, default=3)
     args = ap.parse_args()
@@ -308,14 +310,28 @@ def main():
     ctx0 = torch.tensor(ctx_lens, dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
 
+    if args.sample:                                              # non-greedy iteration (section 2.2 rule, temperature 1)
+        assert eagle, "--sample needs an EAGLE-style draft head"
+        u_draw = torch.rand(B, T, generator=g, device=dev, dtype=torch.float32)
+        u_acc = torch.rand(B, T, generator=g, device=dev, dtype=torch.float32)
+        u_res = torch.rand(B, T, generator=g, device=dev, dtype=torch.float32)
+        draft_logits = torch.zeros(B, T, V, dtype=torch.float32, device=dev)
+        target_logits = torch.zeros(B, T, V, dtype=torch.float32, device=dev)
+
     def step(events=None):
         kv["ctx_len"].copy_(ctx0)                                # same workload every step
         if events: events[0].record(stream)
-        ctx.draft_expand(B, feat_in, tok_in, 1, tree_tokens, scores)
+        if args.sample:
+            ctx.draft_expand_sample(B, feat_in, tok_in, 1, u_draw, 1.0, tree_tokens, draft_logits)
+        else:
+            ctx.draft_expand(B, feat_in, tok_in, 1, tree_tokens, scores)
         if events: events[1].record(stream)
-        ctx.tree_verify(B, tree_tokens, feat_out, None, greedy)
+        ctx.tree_verify(B, tree_tokens, feat_out, target_logits if args.sample else None, greedy)
         if events: events[2].record(stream)
-        ctx.accept_prefix(B, tree_tokens, greedy, a_len, path, nxt, True)
+        if args.sample:
+            ctx.accept_sample(B, tree_tokens, target_logits, draft_logits, u_acc, u_res, 1.0, a_len, path, nxt, True)
+        else:
+            ctx.accept_prefix(B, tree_tokens, greedy, a_len, path, nxt, True)
         if events: events[3].record(stream)
         # feed the result back (device side): the root's feature and the target's next token
         feat_in.copy_(feat_out[:, :1])
@@ -385,7 +401,8 @@ def main():
         "config": {"workload": f"{args.config}: hidden {H}, {'EAGLE' if eagle else 'Medusa'}-style K={K}, T={T} depth "
                                f"{D}, ctx {ctx_lens if B > 1 else C}, {cfg['n_layers']} target layers, batch {B}",
                    "K": K, "tree_nodes": T, "ctx": C, "batch": B,
-                   "launch": "hip_graph" if args.graph else "stream"},
+                   "launch": "hip_graph" if args.graph else "stream",
+                   "acceptance": "stochastic, temperature 1" if args.sample else "greedy"},
         "tokens_per_s": 1e3 / ms_per_step * mean_tokens * B, "mean_tokens_per_iteration": mean_tokens,
         "ms_draft_expand": parts[0], "ms_tree_verify": parts[1], "ms_accept_prefix": parts[2],
         "verify_bytes": vb, "draft_bytes": db,

@@ -3,86 +3,147 @@
 //   * the acceptance walk keeps child x with probability min(1, q(x)/d(x)); after a rejection the target
 //     distribution becomes norm(max(0, q - d)), the rejected token leaves the draft distribution, and the
 //     next child (in draw order) is tried; where the walk stops, one token is drawn from what q has become.
-// Every uniform random number is an input.  One workgroup of 256 threads per row / sequence; sums that
-// decide a token are accumulated in double in a fixed order (thread t owns the contiguous index range
-// [t*CH, (t+1)*CH), ranges are added in order of t), so results do not depend on scheduling.
+// Every uniform random number is an input.  One workgroup of 1024 threads per row / sequence.
+//
+// A draw is an inverse CDF over ascending token id: the first id at which the running sum of the weights
+// exceeds u * total.  The vocabulary is cut into segments of 256 consecutive ids; a wave sums a segment
+// with lane l holding ids 4l..4l+3 (fp64, fixed shuffle order), the segment sums are added in id order, and
+// inside the chosen segment a wave-wide inclusive scan in lane order finds the id.  All orders are fixed,
+// so a draw does not depend on scheduling.
 #include "koala_internal.h"
 
 namespace {
 
-constexpr int NT = 256;
+constexpr int NT = 1024;         // threads per workgroup
+constexpr int NW = NT / 64;      // waves per workgroup
+constexpr int SEG = 256;          // ids per segment
+constexpr int MAX_SEG = 1024;     // vocabularies up to 262144
+constexpr int UNR = 4;            // independent loads in flight per thread in the vocabulary-wide passes
 
 struct Shared {
-    double part[NT];
+    double seg[MAX_SEG];
+    double red[NW];
+    float fmax_[NW];
     double total, base, target;
-    float fmax_[4];
-    float rowmax;
-    int chunk, idx, fallback;
+    int sidx, idx, fallback;
     int kids[64];
     int nk;
 };
+
+__device__ __forceinline__ double wave_sum(double v) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// every thread gets the sum of v over the workgroup (waves added in order)
+__device__ __forceinline__ double block_sum(double v, Shared &sh) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh.red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double t = 0.0;
+    for (int k = 0; k < NW; ++k) t += sh.red[k];
+    return t;
+}
 
 __device__ __forceinline__ float block_max(float v, Shared &sh) {
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
     __syncthreads();
     if ((threadIdx.x & 63) == 0) sh.fmax_[threadIdx.x >> 6] = v;
     __syncthreads();
-    return fmaxf(fmaxf(sh.fmax_[0], sh.fmax_[1]), fmaxf(sh.fmax_[2], sh.fmax_[3]));
+    float t = sh.fmax_[0];
+    for (int k = 1; k < NW; ++k) t = fmaxf(t, sh.fmax_[k]);
+    return t;
 }
 
-// sum of sh.part[0..NT) in index order; every thread gets it
-__device__ __forceinline__ double block_total(Shared &sh) {
+// the four weights of lane l in segment s (zero past V)
+__device__ __forceinline__ void seg_load(const float *w, int V, int s, int l, float *x) {
+    const int i = s * SEG + 4 * l;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] = i + e < V ? w[i + e] : 0.f;
+}
+
+__device__ __forceinline__ double seg_lane_sum(const float *x) {
+    return (((double)x[0] + (double)x[1]) + (double)x[2]) + (double)x[3];
+}
+
+// sh.seg[s] = sum of w over segment s, for all segments (wave k takes segments k, k+NW, ...)
+__device__ void segment_sums(const float *w, int V, Shared &sh) {
+    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, nseg = (V + SEG - 1) / SEG;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        double t = 0.0;
-        for (int i = 0; i < NT; ++i) t += sh.part[i];
-        sh.total = t;
+    for (int s0 = wave; s0 < nseg; s0 += 4 * NW) {   // four segments' loads in flight per wave
+        float x[4][4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) seg_load(w, V, s0 + NW * k, l, x[k]);   // past the last segment: zeros
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const double t = wave_sum(seg_lane_sum(x[k]));
+            if (l == 0 && s0 + NW * k < nseg) sh.seg[s0 + NW * k] = t;
+        }
     }
     __syncthreads();
-    return sh.total;
 }
 
-// Index of the first element at which the running sum of w[0..V) exceeds u * sum(w); the last positive
-// element if rounding leaves none; 0 if nothing is positive.  sh.part must hold the chunk sums of w.
-__device__ int block_inverse_cdf(const float *w, int V, int CH, double u, Shared &sh) {
-    const int tid = threadIdx.x;
+// Index of the first id at which the running sum of w exceeds u * sum(w); the last positive id if rounding
+// leaves none; 0 if nothing is positive.  sh.seg must hold the segment sums of w.  Every thread gets it.
+__device__ int block_inverse_cdf(const float *w, int V, double u, Shared &sh) {
+    const int tid = threadIdx.x, nseg = (V + SEG - 1) / SEG;
     __syncthreads();
     if (tid == 0) {
         double total = 0.0;
-        for (int i = 0; i < NT; ++i) total += sh.part[i];
+        for (int s = 0; s < nseg; ++s) total += sh.seg[s];
         const double target = u * total;
         double run = 0.0;
         int t = -1;
-        for (int i = 0; i < NT; ++i) {
-            if (run + sh.part[i] > target) { t = i; break; }
-            run += sh.part[i];
+        for (int s = 0; s < nseg; ++s) {
+            if (run + sh.seg[s] > target) { t = s; break; }
+            run += sh.seg[s];
         }
         sh.fallback = 0;
-        if (t < 0) {   // rounding: take the last chunk that holds anything
+        if (t < 0) {   // rounding: the last segment that holds anything
             sh.fallback = 1;
-            for (int i = NT - 1; i >= 0; --i)
-                if (sh.part[i] > 0.0) { t = i; break; }
+            for (int s = nseg - 1; s >= 0; --s)
+                if (sh.seg[s] > 0.0) { t = s; break; }
         }
-        sh.chunk = t;
+        sh.sidx = t;
         sh.base = run;
         sh.target = target;
         sh.idx = 0;
     }
     __syncthreads();
-    if (tid == sh.chunk) {
-        const int i0 = tid * CH, i1 = min(V, i0 + CH);
-        double run = sh.base;
+    if (tid < 64 && sh.sidx >= 0) {   // wave 0 resolves the id inside the segment
+        const int s = sh.sidx, l = tid;
+        float x[4];
+        seg_load(w, V, s, l, x);
+        const double own = seg_lane_sum(x);
+        double incl = own;
+        for (int o = 1; o < 64; o <<= 1) {
+            const double t = __shfl_up(incl, o);
+            if (l >= o) incl += t;
+        }
+        const double lo = sh.base + (incl - own), hi = sh.base + incl;
         int pick = -1, lastpos = -1;
-        for (int i = i0; i < i1; ++i) {
-            const float wi = w[i];
-            if (wi > 0.f) {
-                lastpos = i;
-                run += (double)wi;
-                if (pick < 0 && !sh.fallback && run > sh.target) pick = i;
+        double run = lo;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (x[e] > 0.f) {
+                lastpos = s * SEG + 4 * l + e;
+                run += (double)x[e];
+                if (pick < 0 && run > sh.target) pick = lastpos;
             }
         }
-        if (pick < 0) pick = lastpos;
-        sh.idx = pick < 0 ? 0 : pick;
+        const bool mine = !sh.fallback && lo <= sh.target && hi > sh.target && pick >= 0;
+        // the first lane that claims the id wins; otherwise the last positive id of the segment
+        const unsigned long long claims = __ballot(mine);
+        int last_all = lastpos;
+        for (int o = 32; o > 0; o >>= 1) last_all = max(last_all, __shfl_xor(last_all, o));
+        if (claims) {
+            const int first = __ffsll((long long)claims) - 1;
+            const int got = __shfl(pick, first);
+            if (l == 0) sh.idx = got;
+        } else if (l == 0) {
+            sh.idx = last_all < 0 ? 0 : last_all;
+        }
     }
     __syncthreads();
     return sh.idx;
@@ -104,21 +165,48 @@ __device__ void list_children(const TreeTables &tt, int T, int p, Shared &sh) {
     __syncthreads();
 }
 
-// w[i] = exp((z[i] - max z) / tau) written to w, chunk sums to sh.part.  z and w may alias.
-__device__ void softmax_weights(const float *z, float *w, int V, int CH, float inv_tau, Shared &sh) {
+// w[i] = exp((z[i] - max z) / tau); returns sum(w).  z and w may alias.  copy: optional copy of z.
+__device__ double softmax_weights(const float *z, float *w, float *copy, int V, float inv_tau, Shared &sh) {
     const int tid = threadIdx.x;
     float m = -INFINITY;
-    for (int i = tid; i < V; i += NT) m = fmaxf(m, z[i]);
-    m = block_max(m, sh);
-    const int i0 = tid * CH, i1 = min(V, i0 + CH);
-    double s = 0.0;
-    for (int i = i0; i < i1; ++i) {
-        const float e = expf((z[i] - m) * inv_tau);
-        w[i] = e;
-        s += (double)e;
+    for (int i0 = tid; i0 < V; i0 += NT * UNR) {
+        float v[UNR];
+#pragma unroll
+        for (int k = 0; k < UNR; ++k) v[k] = i0 + k * NT < V ? z[i0 + k * NT] : -INFINITY;
+#pragma unroll
+        for (int k = 0; k < UNR; ++k) {
+            m = fmaxf(m, v[k]);
+            if (copy && i0 + k * NT < V) copy[i0 + k * NT] = v[k];
+        }
     }
-    sh.part[tid] = s;
-    __syncthreads();
+    m = block_max(m, sh);
+    double s = 0.0;
+    for (int i0 = tid; i0 < V; i0 += NT * UNR) {
+        float v[UNR];
+#pragma unroll
+        for (int k = 0; k < UNR; ++k) v[k] = i0 + k * NT < V ? z[i0 + k * NT] : -INFINITY;
+#pragma unroll
+        for (int k = 0; k < UNR; ++k) {
+            if (i0 + k * NT < V) {
+                const float e = expf((v[k] - m) * inv_tau);
+                w[i0 + k * NT] = e;
+                s += (double)e;
+            }
+        }
+    }
+    return block_sum(s, sh);
+}
+
+// w[i] /= total over the vocabulary
+__device__ void scale_by(float *w, int V, double total) {
+    for (int i0 = threadIdx.x; i0 < V; i0 += NT * UNR) {
+        float v[UNR];
+#pragma unroll
+        for (int k = 0; k < UNR; ++k) v[k] = i0 + k * NT < V ? w[i0 + k * NT] : 0.f;
+#pragma unroll
+        for (int k = 0; k < UNR; ++k)
+            if (i0 + k * NT < V) w[i0 + k * NT] = (float)((double)v[k] / total);
+    }
 }
 
 // grid: batch * n_level rows.  z: [rows][V] draft logits of the level's nodes (overwritten by weights).
@@ -132,22 +220,22 @@ __global__ __launch_bounds__(NT) void k_sample_children(float *z, const int32_t 
     if (p < 0 || p >= T) return;   // uniform; never for tables the host built
     list_children(tt, T, p, sh);
     float *zr = z + (size_t)row * V;
-    float *out = draft_logits + ((size_t)b * T + p) * V;
-    for (int i = tid; i < V; i += NT) out[i] = zr[i];
-    __syncthreads();
-    const int CH = (V + NT - 1) / NT;
-    softmax_weights(zr, zr, V, CH, inv_tau, sh);
+    (void)softmax_weights(zr, zr, draft_logits + ((size_t)b * T + p) * V, V, inv_tau, sh);
+    segment_sums(zr, V, sh);
     for (int j = 0; j < sh.nk; ++j) {
         const int c = sh.kids[j];
-        const double u = (double)u_draw[(size_t)b * T + c];
-        const int idx = block_inverse_cdf(zr, V, CH, u, sh);
-        if (tid == 0) tree_tokens[(size_t)b * T + c] = idx;
-        if (tid == idx / CH) {   // owner removes the token and recomputes its chunk sum
-            zr[idx] = 0.f;
-            const int i0 = tid * CH, i1 = min(V, i0 + CH);
-            double s = 0.0;
-            for (int i = i0; i < i1; ++i) s += (double)zr[i];
-            sh.part[tid] = s;
+        const int idx = block_inverse_cdf(zr, V, (double)u_draw[(size_t)b * T + c], sh);
+        if (tid == 0) {
+            tree_tokens[(size_t)b * T + c] = idx;
+            zr[idx] = 0.f;   // drawn without replacement
+        }
+        __syncthreads();
+        if (tid < 64) {      // wave 0 refreshes the sum of the segment that lost the token
+            const int s = idx / SEG;
+            float x[4];
+            seg_load(zr, V, s, tid, x);
+            const double t = wave_sum(seg_lane_sum(x));
+            if (tid == 0) sh.seg[s] = t;
         }
         __syncthreads();
     }
@@ -162,7 +250,6 @@ __global__ __launch_bounds__(NT) void k_accept_sample(TreeTables tt, int T, int 
                                                        int32_t *next_token) {
     __shared__ Shared sh;
     const int b = blockIdx.x, tid = threadIdx.x;
-    const int CH = (V + NT - 1) / NT, i0 = tid * CH, i1 = min(V, i0 + CH);
     float *qv = qv_all + (size_t)b * V, *dv = dv_all + (size_t)b * V;
     const int32_t *tok = tree_tokens + (size_t)b * T;
     int32_t *path = accept_path + (size_t)b * (D + 1);
@@ -170,17 +257,14 @@ __global__ __launch_bounds__(NT) void k_accept_sample(TreeTables tt, int T, int 
     if (tid == 0) path[0] = 0;
     for (;;) {
         // q = softmax(target logits at cur)
-        softmax_weights(target_logits + ((size_t)b * T + cur) * V, qv, V, CH, inv_tau, sh);
-        double tot = block_total(sh);
-        for (int i = i0; i < i1; ++i) qv[i] = (float)((double)qv[i] / tot);
-        __syncthreads();
+        double tot = softmax_weights(target_logits + ((size_t)b * T + cur) * V, qv, nullptr, V, inv_tau, sh);
+        scale_by(qv, V, tot);
         list_children(tt, T, cur, sh);
         const int nk = a < D ? sh.nk : 0;
         bool moved = false;
         if (nk > 0) {
-            softmax_weights(draft_logits + ((size_t)b * T + cur) * V, dv, V, CH, inv_tau, sh);
-            tot = block_total(sh);
-            for (int i = i0; i < i1; ++i) dv[i] = (float)((double)dv[i] / tot);
+            tot = softmax_weights(draft_logits + ((size_t)b * T + cur) * V, dv, nullptr, V, inv_tau, sh);
+            scale_by(dv, V, tot);
             __syncthreads();
             for (int j = 0; j < nk; ++j) {
                 const int c = sh.kids[j];
@@ -197,29 +281,45 @@ __global__ __launch_bounds__(NT) void k_accept_sample(TreeTables tt, int T, int 
                 }
                 // rejected: q <- norm(max(0, q - d)) (kept if that is all zero); d loses x and is renormalised
                 double rs = 0.0, ds = 0.0;
-                for (int i = i0; i < i1; ++i) {
-                    rs += (double)fmaxf(0.f, qv[i] - dv[i]);
-                    if (i != x) ds += (double)dv[i];
+                for (int i0 = tid; i0 < V; i0 += NT * UNR) {
+                    float qa[UNR], da[UNR];
+#pragma unroll
+                    for (int k = 0; k < UNR; ++k) {
+                        const bool in = i0 + k * NT < V;
+                        qa[k] = in ? qv[i0 + k * NT] : 0.f;
+                        da[k] = in ? dv[i0 + k * NT] : 0.f;
+                    }
+#pragma unroll
+                    for (int k = 0; k < UNR; ++k) {
+                        rs += (double)fmaxf(0.f, qa[k] - da[k]);
+                        if (i0 + k * NT != x) ds += (double)da[k];
+                    }
                 }
-                __syncthreads();
-                sh.part[tid] = rs;
-                const double R = block_total(sh);
-                __syncthreads();
-                sh.part[tid] = ds;
-                const double Dn = block_total(sh);
-                for (int i = i0; i < i1; ++i) {
-                    if (R > 0.0) qv[i] = (float)((double)fmaxf(0.f, qv[i] - dv[i]) / R);
-                    dv[i] = (i == x) ? 0.f : (Dn > 0.0 ? (float)((double)dv[i] / Dn) : dv[i]);
+                const double R = block_sum(rs, sh);
+                const double Dn = block_sum(ds, sh);
+                for (int i0 = tid; i0 < V; i0 += NT * UNR) {
+                    float qa[UNR], da[UNR];
+#pragma unroll
+                    for (int k = 0; k < UNR; ++k) {
+                        const bool in = i0 + k * NT < V;
+                        qa[k] = in ? qv[i0 + k * NT] : 0.f;
+                        da[k] = in ? dv[i0 + k * NT] : 0.f;
+                    }
+#pragma unroll
+                    for (int k = 0; k < UNR; ++k) {
+                        const int i = i0 + k * NT;
+                        if (i < V) {
+                            if (R > 0.0) qv[i] = (float)((double)fmaxf(0.f, qa[k] - da[k]) / R);
+                            dv[i] = (i == x) ? 0.f : (Dn > 0.0 ? (float)((double)da[k] / Dn) : da[k]);
+                        }
+                    }
                 }
                 __syncthreads();
             }
         }
         if (!moved) {
-            double s = 0.0;
-            for (int i = i0; i < i1; ++i) s += (double)qv[i];
-            __syncthreads();
-            sh.part[tid] = s;
-            const int idx = block_inverse_cdf(qv, V, CH, (double)u_resample[(size_t)b * T + cur], sh);
+            segment_sums(qv, V, sh);
+            const int idx = block_inverse_cdf(qv, V, (double)u_resample[(size_t)b * T + cur], sh);
             if (tid == 0) {
                 next_token[b] = idx;
                 accept_len[b] = a;
@@ -234,6 +334,8 @@ __global__ __launch_bounds__(NT) void k_accept_sample(TreeTables tt, int T, int 
 }  // namespace
 
 namespace ks {
+
+int max_vocab() { return MAX_SEG * SEG; }
 
 void sample_children(hipStream_t st, float *logits, const int32_t *level_nodes, int n_level, const TreeTables &tt,
                      int T, int V, float temperature, const float *u_draw, int32_t *tree_tokens,

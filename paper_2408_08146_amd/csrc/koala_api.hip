@@ -430,6 +430,8 @@ static koala_status draft_expand_impl(koala_ctx *c, void *hip_stream, int batch,
         if (!(temperature > 0.f)) return fail(c, KOALA_E_SHAPE, "temperature must be positive");
         if (c->draft.kind != KOALA_DRAFT_EAGLE)
             return fail(c, KOALA_E_UNSUPPORTED, "sampled drafting is implemented for the EAGLE-style head only");
+        if (c->shape.vocab > ks::max_vocab())
+            return fail(c, KOALA_E_UNSUPPORTED, "vocabulary too large for the sampling kernels");
     }
     hipStream_t st = (hipStream_t)hip_stream;
     const koala_shape &s = c->shape;
@@ -558,6 +560,8 @@ koala_status koala_accept_sample(koala_ctx *c, void *hip_stream, int batch, cons
         (c->T > 1 && !draft_logits))
         return fail(c, KOALA_E_NULL, "all accept_sample pointers are required");
     if (!(temperature > 0.f)) return fail(c, KOALA_E_SHAPE, "temperature must be positive");
+    if (c->shape.vocab > ks::max_vocab())
+        return fail(c, KOALA_E_UNSUPPORTED, "vocabulary too large for the sampling kernels");
     hipStream_t st = (hipStream_t)hip_stream;
     const koala_shape &s = c->shape;
     ks::accept_sample(st, c->tt, c->T, c->D, s.vocab, temperature, tree_tokens, target_logits, draft_logits,

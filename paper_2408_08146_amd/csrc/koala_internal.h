@@ -146,6 +146,8 @@ void gen_next(hipStream_t s, const float *feat_out, const int32_t *tree_tokens, 
 // ---------------------------------------------------------------------------------------------
 namespace ks {
 
+int max_vocab();   // largest vocabulary the sampling kernels handle
+
 // logits: [batch * n_level][V] draft logits of the level's nodes (overwritten); children of those nodes get
 // draws without replacement from softmax(logits / temperature); the logits are copied to draft_logits[b][node]
 void sample_children(hipStream_t st, float *logits, const int32_t *level_nodes, int n_level, const TreeTables &tt,
