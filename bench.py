@@ -364,17 +364,29 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
 
-    # per-call breakdown and accepted lengths (separate pass, events on the launch stream)
-    n_b = min(args.steps, 20)
+    # per-call breakdown, spread of the iteration time and accepted lengths (separate pass, events on the
+    # launch stream around every call)
+    n_b = min(args.steps, 200)
     parts = [0.0, 0.0, 0.0]
+    iter_ms = []
     for _ in range(n_b):
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         step(ev)
         torch.cuda.synchronize()
         for i in range(3):
             parts[i] += ev[i].elapsed_time(ev[i + 1]) / n_b
+        iter_ms.append(ev[0].elapsed_time(ev[3]))
         acc_sum += float(a_len.float().mean().item())
     mean_tokens = 1.0 + acc_sum / n_b
+    iter_ms.sort()
+    pct = lambda q: iter_ms[min(len(iter_ms) - 1, int(q * len(iter_ms)))]
+
+    # what this device delivers for a plain streaming read of 2 GiB (same load instructions as the GEMM)
+    probe = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    probe.fill_(1)
+    torch.cuda.synchronize()
+    stream_read_gbs = KO.measure_stream_read(probe, repeats=5)
+    del probe
 
     # dominant kernel: the weight-streaming GEMM; HIP events around each of its launches
     ctx.profile_begin(8192)
@@ -405,6 +417,9 @@ def main():
                    "acceptance": "stochastic, temperature 1" if args.sample else "greedy"},
         "tokens_per_s": 1e3 / ms_per_step * mean_tokens * B, "mean_tokens_per_iteration": mean_tokens,
         "ms_draft_expand": parts[0], "ms_tree_verify": parts[1], "ms_accept_prefix": parts[2],
+        "iteration_ms_p10_p50_p90": [pct(0.1), pct(0.5), pct(0.9)], "iterations_in_spread": n_b,
+        "measured_stream_read_GBs": stream_read_gbs,
+        "verify_frac_of_measured_stream_read": vb / (parts[1] * 1e-3) / 1e9 / stream_read_gbs,
         "verify_bytes": vb, "draft_bytes": db,
         "verify_hbm_frac": vb / (parts[1] * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "iteration_hbm_frac": (vb + db) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -413,6 +428,12 @@ def main():
                      "launches_timed": gemm_launches, "avg_launch_us": gemm_ms * 1e3 / max(1, gemm_launches),
                      "avg_launch_bytes": gemm_bytes / max(1, gemm_launches)},
     }
+    # context only: tokens/s this iteration rate would give at the average tokens per iteration the paper reports
+    # for a trained head of this kind on Vicuna 7B (Table 1: EAGLE 3.91 at K=1, 4.20 at K=2, 4.36 at K=3)
+    paper_l = {("cfg2", 1): 3.91, ("cfg2", 2): 4.20, ("cfg2", 3): 4.36}.get((args.config, K))
+    if paper_l and eagle and not args.sample:
+        out["projection_context_only"] = {"tokens_per_iteration_from_paper_table_1": paper_l,
+                                          "tokens_per_s": 1e3 / ms_per_step * paper_l}
     if not args.no_cpu_baseline and eagle and B == 1:
         out["cpu_baseline"] = cpu_baseline(cfg, tree, K, levels)
     print(json.dumps(out))

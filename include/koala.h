@@ -253,6 +253,14 @@ koala_status koala_generate(koala_ctx *ctx, void *hip_stream, const float *feat_
                             const int32_t *tok_in, int m, int ctx_len0, int max_new, int use_draft,
                             int32_t *out_tokens, koala_gen_stats *stats);
 
+/* Measurement aid (not part of the method): the rate at which this device streams `bytes` of
+ * `buffer` (device memory, 16-byte aligned) through a plain read kernel with the same load
+ * instructions the weight-streaming GEMM uses, averaged over `repeats` back-to-back launches after
+ * one warm-up; the attainable counterpart of the nominal HBM peak.  Allocates 256 bytes of device
+ * memory for the duration of the call and synchronises on its own events.  Host only. */
+koala_status koala_measure_stream_read(void *hip_stream, const void *buffer, size_t bytes,
+                                       int repeats, double *gb_per_s);
+
 /* Measurement aid for benchmarks (not part of the method).  Between koala_profile_begin and
  * koala_profile_end every weight-streaming GEMM launch of the bfloat16 path carries a pair
  * of HIP events bound to its own dispatch on the call's stream, which take the kernel's begin and

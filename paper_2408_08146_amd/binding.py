@@ -9,7 +9,7 @@ KOALA_DRAFT_EAGLE, KOALA_DRAFT_MEDUSA = 0, 1
 
 EXPORTS = ("koala_create", "koala_workspace_bytes", "koala_bind", "koala_draft_expand",
            "koala_tree_verify", "koala_accept_prefix", "koala_generate", "koala_draft_expand_sample",
-           "koala_accept_sample", "koala_profile_begin",
+           "koala_accept_sample", "koala_measure_stream_read", "koala_profile_begin",
            "koala_profile_end", "koala_last_error", "koala_destroy")
 
 _STATUS = {0: "KOALA_OK", -1: "KOALA_E_NULL", -2: "KOALA_E_SHAPE", -3: "KOALA_E_ALIGN",
@@ -80,16 +80,28 @@ def load_library():
     lib.koala_generate.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp, C.POINTER(_GenStats)]
     lib.koala_draft_expand_sample.argtypes = [vp, vp, ip, vp, vp, ip, vp, C.c_float, vp, vp]
     lib.koala_accept_sample.argtypes = [vp, vp, ip, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, ip]
+    lib.koala_measure_stream_read.argtypes = [vp, vp, C.c_size_t, ip, C.POINTER(C.c_double)]
     lib.koala_profile_begin.argtypes = [vp, ip]
     lib.koala_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(ip), C.POINTER(C.c_double)]
     lib.koala_last_error.argtypes = [vp]
     lib.koala_last_error.restype = C.c_char_p
     lib.koala_destroy.argtypes = [vp]
     lib.koala_destroy.restype = None
-    for n in EXPORTS[:11]:
+    for n in EXPORTS[:12]:
         getattr(lib, n).restype = C.c_int
     _LIB = lib
     return lib
+
+
+def measure_stream_read(buffer, repeats=5, stream=None):
+    """GB/s at which the device streams the whole tensor `buffer` through a plain read kernel."""
+    lib = load_library()
+    out = C.c_double()
+    rc = lib.koala_measure_stream_read(_stream(stream), C.c_void_p(buffer.data_ptr()),
+                                       buffer.numel() * buffer.element_size(), repeats, C.byref(out))
+    if rc != 0:
+        raise KoalaError(rc, "koala_measure_stream_read failed")
+    return out.value
 
 
 def _ptr(t):

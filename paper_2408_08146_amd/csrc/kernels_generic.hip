@@ -440,6 +440,24 @@ __global__ void k_gen_next(const float *feat_out, const int32_t *tree_tokens, co
     }
 }
 
+// Streaming read of n 16-byte words (measurement aid): every thread xors what it reads; the result is
+// stored only to keep the loads alive.
+typedef __attribute__((ext_vector_type(4))) unsigned int rd_u32x4;
+__global__ __launch_bounds__(256) void k_stream_read(const rd_u32x4 *src, size_t n, unsigned *sink) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    rd_u32x4 acc = {0u, 0u, 0u, 0u};
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const rd_u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+        const rd_u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride);
+        const rd_u32x4 d = __builtin_nontemporal_load(src + i + 3 * stride);
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    const unsigned r = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (r == 0x9e3779b9u) sink[0] = r;
+}
+
 inline int cdiv(size_t a, size_t b) { return (int)((a + b - 1) / b); }
 
 }  // namespace
@@ -592,6 +610,10 @@ void advance_ctx(hipStream_t s, int32_t *ctx_len, const int32_t *accept_len, int
 // dst[b * dst_stride + j] = x[(b*m + m-1) * H + j]: the newest row of every sequence
 void gather_last_rows(hipStream_t s, const float *x, float *dst, size_t dst_stride, int batch, int m, int H) {
     k_gather_last<<<batch, 256, 0, s>>>(x, dst, dst_stride, m, H);
+}
+
+void stream_read(hipStream_t s, const void *src, size_t bytes, unsigned *sink) {
+    k_stream_read<<<2048, 256, 0, s>>>((const rd_u32x4 *)src, bytes / 16, sink);
 }
 
 void gen_next(hipStream_t s, const float *feat_out, const int32_t *tree_tokens, const int32_t *accept_len,

@@ -662,6 +662,33 @@ koala_status koala_generate(koala_ctx *c, void *hip_stream, const float *feat_in
     return KOALA_OK;
 }
 
+koala_status koala_measure_stream_read(void *hip_stream, const void *buffer, size_t bytes, int repeats,
+                                       double *gb_per_s) {
+    if (!buffer || !gb_per_s) return KOALA_E_NULL;
+    if (bytes < 16 || repeats < 1 || ((uintptr_t)buffer & 15)) return KOALA_E_SHAPE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    unsigned *sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    koala_status rc = KOALA_E_DEVICE;
+    if (hipMalloc((void **)&sink, 256) == hipSuccess && hipEventCreate(&e0) == hipSuccess &&
+        hipEventCreate(&e1) == hipSuccess) {
+        kg::stream_read(st, buffer, bytes, sink);   // warm-up
+        bool ok = hipEventRecord(e0, st) == hipSuccess;
+        for (int r = 0; r < repeats; ++r) kg::stream_read(st, buffer, bytes, sink);
+        float ms = 0.f;
+        ok = ok && hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+             hipEventElapsedTime(&ms, e0, e1) == hipSuccess && hipGetLastError() == hipSuccess;
+        if (ok && ms > 0.f) {
+            *gb_per_s = (double)(bytes / 16 * 16) * repeats / (ms * 1e-3) / 1e9;
+            rc = KOALA_OK;
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (sink) (void)hipFree(sink);
+    return rc;
+}
+
 koala_status koala_profile_begin(koala_ctx *c, int max_launches) {
     if (!c) return KOALA_E_NULL;
     c->err.clear();

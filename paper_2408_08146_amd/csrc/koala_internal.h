@@ -134,6 +134,8 @@ void kv_commit(hipStream_t s, bool bf16, void *kcache, void *vcache, const int32
                const int32_t *accept_len, const int32_t *accept_path, int D, int n_layers,
                int max_batch, int batch, int n_heads, int capacity, int head_dim);
 void advance_ctx(hipStream_t s, int32_t *ctx_len, const int32_t *accept_len, int batch);
+// measurement aid: read `bytes` (multiple of 16) once with streaming loads
+void stream_read(hipStream_t s, const void *src, size_t bytes, unsigned *sink);
 // generation loop: next draft inputs (rows 0..a) and emitted tokens from the accepted path of sequence 0
 void gen_next(hipStream_t s, const float *feat_out, const int32_t *tree_tokens, const int32_t *accept_len,
               const int32_t *accept_path, const int32_t *next_token, int T, int D, int H, float *feat_next,
