@@ -218,3 +218,57 @@ def test_sampling_argument_errors():
     with pytest.raises(K.KoalaError):    # temperature must be positive
         case2.gpu_draft_sample(np.zeros((1, 1, case2.H), np.float32), np.zeros((1, 1), np.int32),
                                np.zeros((1, case2.T), np.float32), temperature=0.0)
+
+
+def test_first_emitted_token_follows_the_target_distribution():
+    """Distribution-level check on the device (section 2.2: the method samples from the target's
+    distribution): over 2048 independent trials of sampled draft -> verify -> stochastic acceptance
+    from the same state, the first token an iteration emits (the accepted depth-1 child, or the
+    replacement) is distributed as softmax(target logits at the root / temperature), which the
+    oracle computes by plain decoding.  Temperature 0.1 concentrates the mass of the random model
+    enough that single tokens have measurable frequencies, while the draft's and the target's
+    distributions still overlap, so that accepted and replaced tokens both contribute."""
+    TEMP, B, CALLS = 0.1, 16, 128
+    case = Case("cfg1", batch=B, max_m=16)
+    cfg, tree, T = case.cfg, case.tree, case.T
+    prompt = tensor_uniform_int(1, "ctx", (64,), 0, case.V)[:12]
+    feats, logits = oracle.prefill(cfg, case.Wt, case.tc[0], prompt)
+    for b in range(1, B):
+        case.tc[b] = case.tc[0].copy()
+    case.ctx_lens = [len(prompt)] * B
+    case.upload_kv()
+    C = len(prompt)
+    root = int(np.argmax(logits[-1]))
+    tok_in = np.tile(np.concatenate([prompt[1:], [root]]).astype(np.int32), (B, 1))
+    feat_in = np.tile(feats.astype(np.float32), (B, 1, 1))
+    _, root_logits = oracle.decode_one(cfg, case.Wt, case.tc[0].copy(), C, root)
+    q0 = oracle.softmax_t(root_logits, TEMP)
+    counts = np.zeros(case.V)
+    accepted = 0
+    for call in range(CALLS):
+        ud = tensor_uniform01(41, f"ud{call}", (B, T))
+        ua = tensor_uniform01(41, f"ua{call}", (B, T))
+        ur = tensor_uniform01(41, f"ur{call}", (B, T))
+        tokens, dl_dev = case.gpu_draft_sample(feat_in, tok_in, ud, TEMP)
+        assert (tokens[:, 0] == root).all()
+        torch = case.torch
+        tl_dev = torch.empty(B, T, case.V, dtype=torch.float32, device=case.device)
+        feat = torch.empty(B, T, case.H, dtype=torch.float32, device=case.device)
+        greedy = torch.empty(B, T, dtype=torch.int32, device=case.device)
+        case.gpu.tree_verify(B, case.t(tokens), feat, tl_dev, greedy)
+        a, path, nxt = case.gpu_accept_sample(tokens, tl_dev, dl_dev, ua, ur, TEMP)
+        for b in range(B):
+            if a[b] >= 1:
+                counts[tokens[b, path[b, 1]]] += 1
+                accepted += 1
+            else:
+                counts[nxt[b]] += 1
+    n = B * CALLS
+    assert 0.1 * n < accepted < 0.9 * n, accepted        # both branches are exercised
+    top = np.argsort(-q0)[:8]
+    assert q0[top].sum() > 0.4, q0[top]
+    freq = counts / n
+    sd = np.sqrt(q0 * (1 - q0) / n)
+    assert np.all(np.abs(freq[top] - q0[top]) < 4.5 * sd[top]), (freq[top], q0[top])
+    rest_q, rest_f = 1 - q0[top].sum(), 1 - freq[top].sum()
+    assert abs(rest_f - rest_q) < 4.5 * np.sqrt(rest_q * (1 - rest_q) / n)
