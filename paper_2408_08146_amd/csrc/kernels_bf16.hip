@@ -597,7 +597,7 @@ typedef unsigned short __attribute__((may_alias)) u16_alias;
 struct __attribute__((may_alias)) u64_alias { unsigned int x, y; };
 
 template <int DH, int MT>
-__global__ __launch_bounds__(256) void k_attn_mfma(const float *__restrict__ qrot, RowMeta meta,
+__global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float *__restrict__ qrot, RowMeta meta,
                                                    const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc,
                                                    float *__restrict__ o_part, float *__restrict__ ml,
                                                    int rows_per_seq, int n_heads, int cap, int nsplit, int H) {
