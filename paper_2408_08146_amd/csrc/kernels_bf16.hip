@@ -35,7 +35,7 @@ __device__ __forceinline__ uint32_t f2bf(float v) {  // round to nearest even
 // Workgroup = 4 waves; wave w owns row block wb*4 + w (64 rows); the X chunk is shared in LDS.
 // ---------------------------------------------------------------------------------------------
 template <int MT>
-__global__ __launch_bounds__(256, MT == 4 ? 2 : 1) void k_gemm_packed(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
+__global__ __launch_bounds__(256, MT == 4 ? 2 : 3) void k_gemm_packed(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
                                                      float *__restrict__ P, int Npad, int K, int S, int nwb,
                                                      int MTT, int mt0) {
     extern __shared__ u32x4 xs[];            // [2][XCH]
@@ -89,7 +89,6 @@ __global__ __launch_bounds__(256, MT == 4 ? 2 : 1) void k_gemm_packed(const u32x
                 bf16x8 a[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) a[j] = __builtin_bit_cast(bf16x8, wr[bb][j]);
-                if (MT < 4 && 2 * c + bb + 2 < nb) wload(2 * c + bb + 2, bb);
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
                     const u32x4 *xk = xc + (bb * 2 + s) * (MT * 2 * 64);
@@ -110,7 +109,9 @@ __global__ __launch_bounds__(256, MT == 4 ? 2 : 1) void k_gemm_packed(const u32x
                         for (int m = 0; m < MT; ++m)
                             acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t * 2 + s], xl[m], acc[t][m], 0, 0, 0);
                 }
-                if (MT == 4 && 2 * c + bb + 2 < nb) wload(2 * c + bb + 2, bb);   // keeps the register count at two workgroups per CU
+                // reloading a batch only after its MFMAs keeps the register count low enough for three (MT <= 2)
+                // or two (MT = 4) workgroups per CU; the other batch is in flight meanwhile
+                if (2 * c + bb + 2 < nb) wload(2 * c + bb + 2, bb);
             }
         }
         if (more) {
