@@ -16,11 +16,16 @@
  *    stored in the model dtype (fp32 or bfloat16); features, logits and scores
  *    are always fp32; token ids, node ids and lengths are int32.
  *  - Linear layers are [out_features, in_features] and have no bias.
- *  - Every compute call only enqueues work on the given hipStream_t (passed as
- *    void*); it never synchronises and never reads results back.  Calls on one
- *    context must be issued on one stream, or otherwise ordered by the caller.
+ *  - The iteration calls (draft_expand, tree_verify, accept_prefix and their
+ *    non-greedy counterparts) only enqueue work on the given hipStream_t
+ *    (passed as void*); they never synchronise and never read results back, so
+ *    they can be captured into a HIP graph.  koala_generate and the measurement
+ *    aids are the exceptions and say so.  Calls on one context must be issued
+ *    on one stream, or otherwise ordered by the caller; a context is not safe
+ *    for concurrent use from several host threads.
  *  - Arguments are validated on the host before anything is launched; a call
- *    that returns an error has had no effect on device memory.  Errors are
+ *    that returns an error has had no effect on device memory (koala_generate:
+ *    none from the failing iteration on; earlier iterations stay committed).  Errors are
  *    returned as negative koala_status values; koala_last_error() gives text.
  *  - Limits: at most 64 tree nodes per sequence, at most 64 catch-up rows (m),
  *    head_dim 64 or 128, hidden = n_heads * head_dim; for bfloat16 hidden and
