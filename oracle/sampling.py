@@ -34,13 +34,15 @@ def softmax_t(logits, temperature=1.0):
 
 def inverse_cdf(p, u):
     """Index of the first element at which the running sum of the (unnormalised, non-negative)
-    weights p exceeds u * sum(p); the last positive element if rounding leaves none."""
+    weights p exceeds u * sum(p); the last positive element if rounding leaves none; 0 if no
+    element is positive (a distribution that has been drawn empty)."""
     p = np.asarray(p, np.float64)
     c = np.cumsum(p)
     hit = np.nonzero(c > u * c[-1])[0]
     if len(hit):
         return int(hit[0])
-    return int(np.nonzero(p > 0)[0][-1])
+    pos = np.nonzero(p > 0)[0]
+    return int(pos[-1]) if len(pos) else 0
 
 
 def draw_without_replacement(d, uniforms):
@@ -126,3 +128,37 @@ def eagle_expand_sample(cfg, Wt, Wd, dcache, C, feat_in, tok_in, parent, rank, u
             for c, x in zip(kids, draws):
                 tokens[c] = x
     return dict(tokens=tokens, logits=logits)
+
+
+def generate_sampled(cfg, Wt, Wd, prompt, n_new, parent, rank, uniforms, temperature=1.0, dt=np.float64):
+    """Non-greedy generation loop with an EAGLE-style head: prefill, then repeat sampled draft ->
+    verify -> stochastic acceptance -> commit until n_new tokens exist (the first is drawn from the
+    prefill's last distribution with uniforms[0][2][0]).  uniforms[i] = (u_draw[T], u_accept[T],
+    u_resample[T]) of iteration i.  Returns dict(tokens, accept_lens, C)."""
+    from .spec import prefill, verify_tree, commit_path
+    from .llama import KVCache
+    T = len(parent)
+    cap = len(prompt) + n_new + 2 * T + 2
+    tcache = KVCache(cfg["n_layers"], cfg["n_heads"], cap, cfg["head_dim"], dt)
+    dcache = KVCache(cfg["K"], cfg["n_heads"], cap, cfg["head_dim"], dt)
+    feats, logits = prefill(cfg, Wt, tcache, prompt, dt)
+    root = inverse_cdf(softmax_t(logits[-1], temperature), uniforms[0][2][0])
+    out, accept_lens = [root], []
+    C = len(prompt)
+    feat_in, tok_in = feats, np.asarray(list(prompt[1:]) + [root], np.int32)
+    it = 0
+    while len(out) < n_new:
+        u_draw, u_acc, u_res = uniforms[it]
+        dr = eagle_expand_sample(cfg, Wt, Wd, dcache, C, feat_in, tok_in, parent, rank, u_draw, temperature, dt)
+        tokens = dr["tokens"]
+        feat, tl, _ = verify_tree(cfg, Wt, tcache, C, tokens, parent, dt)
+        q = {i: softmax_t(tl[i], temperature) for i in range(T)}
+        d = {u: softmax_t(row, temperature) for u, row in dr["logits"].items()}
+        a, path, nxt = accept_sample(tokens, parent, rank, q, d, u_acc, u_res)
+        C = commit_path(tcache, C, path)
+        emitted = [int(tokens[p]) for p in path[1:]] + [nxt]
+        out += emitted
+        accept_lens.append(a)
+        feat_in, tok_in = feat[path], np.asarray(emitted, np.int32)
+        it += 1
+    return dict(tokens=out[:n_new], accept_lens=accept_lens, C=C)

@@ -163,6 +163,8 @@ def test_inverse_cdf_against_brute_force():
     assert oracle.inverse_cdf([0.25, 0.25, 0.5], 0.0) == 0
     assert oracle.inverse_cdf([0.25, 0.25, 0.5], 0.4999) == 1
     assert oracle.inverse_cdf([0.25, 0.25, 0.5], 0.5) == 2
+    assert oracle.inverse_cdf([0.0, 0.0, 0.0], 0.3) == 0            # drawn empty
+    assert oracle.draw_without_replacement([0.0, 1.0, 0.0], [0.5, 0.5]) == [1, 0]
 
 
 def test_sampled_draft_reduces_to_top1_at_low_temperature():
@@ -187,3 +189,34 @@ def test_sampled_draft_reduces_to_top1_at_low_temperature():
     np.testing.assert_array_equal(g["tokens"], s["tokens"])
     for u in (0, 1, 2):
         np.testing.assert_allclose(g["logits"][u], s["logits"][u], rtol=1e-12)
+
+
+def test_sampled_generation_reduces_to_greedy_generation_at_low_temperature():
+    """temperature -> 0: every distribution is one-hot, a drafted token is kept iff it is the target's
+    argmax and the replacement is the argmax, so the loop emits plain greedy decoding."""
+    from helpers import NANO
+    from koala_synth.weights import target_weights, eagle_weights
+    from koala_synth import make_tree
+    cfg = dict(NANO)
+    Wt = target_weights(cfg, 4, norm_gain="random", cache=True)
+    Wd = eagle_weights(cfg, 4, norm_gain="random", cache=True)
+    tree = make_tree([2, 2], [1, 2, 3])
+    prompt = np.array([8, 3, 41, 7])
+    rng = np.random.default_rng(9)
+    uniforms = [(rng.random(tree.n_nodes), rng.random(tree.n_nodes), rng.random(tree.n_nodes)) for _ in range(16)]
+    got = oracle.generate_sampled(cfg, Wt, Wd, prompt, 9, tree.parent, tree.rank, uniforms, temperature=1e-7)
+    assert got["tokens"] == oracle.greedy_reference(cfg, Wt, prompt, 9)
+
+
+def test_sampled_generation_with_a_perfect_draft_accepts_everything_it_can():
+    """Draft distribution == target distribution along the chain (the predictable pair at sigma = 0 has
+    identical one-hot-like distributions at low temperature): all chain drafts are accepted."""
+    from koala_synth import get_config, predictable_pair
+    cfg = get_config("cfg1")
+    ch = chain_tree(3)
+    Wt, Wd = predictable_pair(cfg, 0, sigma=0.0, cache=True)
+    rng = np.random.default_rng(10)
+    uniforms = [(rng.random(4), rng.random(4), rng.random(4)) for _ in range(8)]
+    got = oracle.generate_sampled(cfg, Wt, Wd, np.array([5, 6, 7]), 12, ch.parent, ch.rank, uniforms, temperature=0.02)
+    assert got["tokens"] == [(8 + i) % 1000 for i in range(12)]
+    assert all(a == 3 for a in got["accept_lens"])
