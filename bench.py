@@ -135,6 +135,8 @@ def generation_bench(args):
     tok_in = torch.tensor([123], dtype=torch.int32, device=dev)
     out = torch.zeros(N, dtype=torch.int32, device=dev)
     res = {}
+    Tp = (T + 3) // 4 * 4
+    uniforms = torch.rand(N + 1, 3, Tp, generator=g, device=dev, dtype=torch.float32)
     for name, c, use_draft in (("plain", plain, False), ("speculative", spec, True)):
         c.bind(w, kv, ws)
         best = None
@@ -142,7 +144,10 @@ def generation_bench(args):
             kv["ctx_len"].fill_(C)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            st = c.generate(feat_in, tok_in, 1, C, N, out, use_draft=use_draft)
+            if use_draft and args.sample:
+                st = c.generate_sample(feat_in, tok_in, 1, C, N, uniforms, 1.0, out)
+            else:
+                st = c.generate(feat_in, tok_in, 1, C, N, out, use_draft=use_draft)
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
             if rep >= args.warmup_gen and (best is None or dt < best[0]):
@@ -159,7 +164,8 @@ def generation_bench(args):
         "config": {"workload": f"{args.config}: generation of {N} tokens after a {C}-token context, EAGLE-style K={K}, "
                                f"T={T} depth {D}, {cfg['n_layers']} target layers, batch 1",
                    "weights": (f"predictable pair, sigma={args.sigma}" if args.sigma >= 0 else "random"),
-                   "best_of": args.repeat_gen},
+                   "best_of": args.repeat_gen,
+                   "acceptance": "stochastic, temperature 1" if args.sample else "greedy"},
         "speculative": res["speculative"], "plain": res["plain"]}))
 
 

@@ -258,6 +258,21 @@ koala_status koala_generate(koala_ctx *ctx, void *hip_stream, const float *feat_
                             const int32_t *tok_in, int m, int ctx_len0, int max_new, int use_draft,
                             int32_t *out_tokens, koala_gen_stats *stats);
 
+/* Non-greedy generation loop (sections 2.2 and 4.4): as koala_generate with an EAGLE-style head,
+ * but every iteration is koala_draft_expand_sample -> koala_tree_verify -> koala_accept_sample
+ * (commit) at the given temperature.
+ *   uniforms device fp32 [max_iters, 3, n_nodes_padded], n_nodes_padded = n_nodes rounded up to a
+ *            multiple of 4: iteration i uses row [i,0] as u_draw, [i,1] as u_accept, [i,2] as
+ *            u_resample (entries >= n_nodes unused);
+ *   max_iters: KOALA_E_CAPACITY is returned (iterations so far stay committed) if that many
+ *            iterations did not produce max_new tokens; max_iters >= max_new always suffices.
+ * tok_in[m-1], the root of the first tree, is the caller's choice (e.g. its own draw from the
+ * prefill's last distribution).  Other arguments, outputs and statistics as in koala_generate. */
+koala_status koala_generate_sample(koala_ctx *ctx, void *hip_stream, const float *feat_in,
+                                   const int32_t *tok_in, int m, int ctx_len0, int max_new,
+                                   const float *uniforms, int max_iters, float temperature,
+                                   int32_t *out_tokens, koala_gen_stats *stats);
+
 /* Measurement aid (not part of the method): the rate at which this device streams `bytes` of
  * `buffer` (device memory, 16-byte aligned) through a plain read kernel with the same load
  * instructions the weight-streaming GEMM uses, averaged over `repeats` back-to-back launches after

@@ -9,7 +9,7 @@ KOALA_DRAFT_EAGLE, KOALA_DRAFT_MEDUSA = 0, 1
 
 EXPORTS = ("koala_create", "koala_workspace_bytes", "koala_bind", "koala_draft_expand",
            "koala_tree_verify", "koala_accept_prefix", "koala_generate", "koala_draft_expand_sample",
-           "koala_accept_sample", "koala_measure_stream_read", "koala_profile_begin",
+           "koala_accept_sample", "koala_generate_sample", "koala_measure_stream_read", "koala_profile_begin",
            "koala_profile_end", "koala_last_error", "koala_destroy")
 
 _STATUS = {0: "KOALA_OK", -1: "KOALA_E_NULL", -2: "KOALA_E_SHAPE", -3: "KOALA_E_ALIGN",
@@ -80,6 +80,7 @@ def load_library():
     lib.koala_generate.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp, C.POINTER(_GenStats)]
     lib.koala_draft_expand_sample.argtypes = [vp, vp, ip, vp, vp, ip, vp, C.c_float, vp, vp]
     lib.koala_accept_sample.argtypes = [vp, vp, ip, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, ip]
+    lib.koala_generate_sample.argtypes = [vp, vp, vp, vp, ip, ip, ip, vp, ip, C.c_float, vp, C.POINTER(_GenStats)]
     lib.koala_measure_stream_read.argtypes = [vp, vp, C.c_size_t, ip, C.POINTER(C.c_double)]
     lib.koala_profile_begin.argtypes = [vp, ip]
     lib.koala_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(ip), C.POINTER(C.c_double)]
@@ -87,7 +88,7 @@ def load_library():
     lib.koala_last_error.restype = C.c_char_p
     lib.koala_destroy.argtypes = [vp]
     lib.koala_destroy.restype = None
-    for n in EXPORTS[:12]:
+    for n in EXPORTS[:13]:
         getattr(lib, n).restype = C.c_int
     _LIB = lib
     return lib
@@ -187,6 +188,14 @@ class KoalaContext:
         st = _GenStats()
         self._check(self.lib.koala_generate(self._h, _stream(stream), _ptr(feat_in), _ptr(tok_in), m, ctx_len0,
                                             max_new, 1 if use_draft else 0, _ptr(out_tokens), C.byref(st)))
+        return dict(iterations=st.iterations, tokens=st.tokens, accept_hist=list(st.accept_hist))
+
+    def generate_sample(self, feat_in, tok_in, m, ctx_len0, max_new, uniforms, temperature, out_tokens, stream=None):
+        """uniforms: device fp32 [max_iters, 3, n_nodes rounded up to 4].  Returns the statistics dict."""
+        st = _GenStats()
+        self._check(self.lib.koala_generate_sample(self._h, _stream(stream), _ptr(feat_in), _ptr(tok_in), m, ctx_len0,
+                                                   max_new, _ptr(uniforms), int(uniforms.shape[0]), float(temperature),
+                                                   _ptr(out_tokens), C.byref(st)))
         return dict(iterations=st.iterations, tokens=st.tokens, accept_hist=list(st.accept_hist))
 
     def draft_expand_sample(self, batch, feat_in, tok_in, m, u_draw, temperature, tree_tokens, draft_logits,

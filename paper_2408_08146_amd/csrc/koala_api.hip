@@ -88,6 +88,8 @@ size_t carve(koala_ctx *c, char *base) {
         c->gen_next = w.take<int32_t>(1);
         c->gen_tok_in = w.take<int32_t>(gm);
     }
+    c->gen_dlogits = w.take<float>((size_t)T * V);
+    c->gen_tlogits = w.take<float>((size_t)T * V);
     c->acc_q = w.take<float>((size_t)c->max_batch * V);
     c->acc_d = w.take<float>((size_t)c->max_batch * V);
     c->xf = nullptr;
@@ -594,10 +596,22 @@ koala_status koala_accept_prefix(koala_ctx *c, void *hip_stream, int batch, cons
     return KOALA_OK;
 }
 
-koala_status koala_generate(koala_ctx *c, void *hip_stream, const float *feat_in, const int32_t *tok_in, int m,
-                            int ctx_len0, int max_new, int use_draft, int32_t *out_tokens, koala_gen_stats *stats) {
+// uniforms == nullptr: greedy loop.  Otherwise iteration i draws with uniforms[i][0..2][n_nodes]
+// (children, acceptance, replacement) at the given temperature; at most max_iters iterations.
+static koala_status generate_impl(koala_ctx *c, void *hip_stream, const float *feat_in, const int32_t *tok_in, int m,
+                                  int ctx_len0, int max_new, int use_draft, const float *uniforms, int max_iters,
+                                  float temperature, int32_t *out_tokens, koala_gen_stats *stats) {
     koala_status st0 = check_call(c, 1);
     if (st0 != KOALA_OK) return st0;
+    const bool sampling = uniforms != nullptr;
+    const int Tp = (c->T + 3) & ~3;   // row stride of the uniforms: rows stay 16-byte aligned
+    if (sampling) {
+        if (c->draft.kind != KOALA_DRAFT_EAGLE || !use_draft)
+            return fail(c, KOALA_E_UNSUPPORTED, "non-greedy generation needs an EAGLE-style draft head");
+        if (!(temperature > 0.f)) return fail(c, KOALA_E_SHAPE, "temperature must be positive");
+        if (max_iters < 1) return fail(c, KOALA_E_SHAPE, "max_iters must be positive");
+        if (!aligned16(uniforms)) return fail(c, KOALA_E_ALIGN, "uniforms must be 16-byte aligned");
+    }
     if (!tok_in || !out_tokens || !stats || (use_draft && !feat_in))
         return fail(c, KOALA_E_NULL, "generate: tok_in, out_tokens and stats are required (feat_in too when drafting)");
     const koala_shape &s = c->shape;
@@ -628,15 +642,26 @@ koala_status koala_generate(koala_ctx *c, void *hip_stream, const float *feat_in
     int n_done = 0, cur_m = m;
     while (n_done < max_new) {
         koala_status r;
-        if (use_draft) {
+        const float *u = nullptr;
+        if (sampling) {
+            if (stats->iterations >= max_iters)
+                return fail(c, KOALA_E_CAPACITY, "generate: max_iters iterations were not enough for max_new tokens");
+            u = uniforms + (size_t)stats->iterations * 3 * Tp;
+            r = koala_draft_expand_sample(c, st, 1, c->gen_feat_in, c->gen_tok_in, cur_m, u, temperature, c->gen_tree,
+                                          c->gen_dlogits);
+            if (r != KOALA_OK) return r;
+        } else if (use_draft) {
             r = koala_draft_expand(c, st, 1, c->gen_feat_in, c->gen_tok_in, cur_m, c->gen_tree, nullptr);
             if (r != KOALA_OK) return r;
         } else {
             kg::set_root(st, c->gen_tok_in, cur_m, c->gen_tree, nullptr, 1, c->T);
         }
-        r = koala_tree_verify(c, st, 1, c->gen_tree, c->gen_feat, nullptr, c->gen_greedy);
+        r = koala_tree_verify(c, st, 1, c->gen_tree, c->gen_feat, sampling ? c->gen_tlogits : nullptr, c->gen_greedy);
         if (r != KOALA_OK) return r;
-        r = koala_accept_prefix(c, st, 1, c->gen_tree, c->gen_greedy, c->gen_acc, c->gen_path, c->gen_next, 1);
+        r = sampling ? koala_accept_sample(c, st, 1, c->gen_tree, c->gen_tlogits, c->gen_dlogits, u + Tp,
+                                           u + 2 * Tp, temperature, c->gen_acc, c->gen_path, c->gen_next, 1)
+                     : koala_accept_prefix(c, st, 1, c->gen_tree, c->gen_greedy, c->gen_acc, c->gen_path, c->gen_next,
+                                           1);
         if (r != KOALA_OK) return r;
         kg::gen_next(st, c->gen_feat, c->gen_tree, c->gen_acc, c->gen_path, c->gen_next, c->T, c->D, s.hidden,
                      c->gen_feat_in, c->gen_tok_in, out_tokens, n_done, max_new);
@@ -660,6 +685,20 @@ koala_status koala_generate(koala_ctx *c, void *hip_stream, const float *feat_in
     }
     stats->tokens = n_done;
     return KOALA_OK;
+}
+
+koala_status koala_generate(koala_ctx *c, void *hip_stream, const float *feat_in, const int32_t *tok_in, int m,
+                            int ctx_len0, int max_new, int use_draft, int32_t *out_tokens, koala_gen_stats *stats) {
+    return generate_impl(c, hip_stream, feat_in, tok_in, m, ctx_len0, max_new, use_draft, nullptr, 0, 1.f, out_tokens,
+                         stats);
+}
+
+koala_status koala_generate_sample(koala_ctx *c, void *hip_stream, const float *feat_in, const int32_t *tok_in,
+                                   int m, int ctx_len0, int max_new, const float *uniforms, int max_iters,
+                                   float temperature, int32_t *out_tokens, koala_gen_stats *stats) {
+    if (c && !uniforms) return fail(c, KOALA_E_NULL, "uniforms are required");
+    return generate_impl(c, hip_stream, feat_in, tok_in, m, ctx_len0, max_new, 1, uniforms, max_iters, temperature,
+                         out_tokens, stats);
 }
 
 koala_status koala_measure_stream_read(void *hip_stream, const void *buffer, size_t bytes, int repeats,

@@ -58,6 +58,7 @@ struct koala_ctx {
     float *x, *act, *qkv, *qrot, *attn_out, *gu, *o_part, *ml, *logits, *fhat, *topk_val;
     int32_t *topk_idx, *tok_tmp;
     // generation loop state of sequence 0 (koala_generate)
+    float *gen_dlogits, *gen_tlogits;                    // [T][V] draft / target logits of the non-greedy loop
     float *gen_feat, *gen_feat_in;                       // [T][H] verify features; [max(D+1, max_m)][H] next draft inputs
     int32_t *gen_tree, *gen_greedy, *gen_acc, *gen_path, *gen_next, *gen_tok_in;
     float *acc_q, *acc_d;                                // [max_batch][V] distributions of the stochastic acceptance walk

@@ -128,3 +128,56 @@ def test_generate_argument_errors():
     case2.ctx_lens = [5]                # host's idea of the context length is wrong
     with pytest.raises(K.KoalaError):
         case2.gpu_generate(feats, np.array([2, 3]), 4)
+
+
+@pytest.mark.parametrize("temperature", [1.0, 0.3])
+def test_nongreedy_generation_matches_oracle_loop(temperature):
+    """koala_generate_sample against the oracle's non-greedy loop with the same uniforms.  The oracle's
+    whole run is repeated with every uniform moved by +-2e-5; only if nothing changes (it does not
+    for these seeds: the predictable weights give concentrated distributions) is the device run
+    compared, and then exactly."""
+    from koala_synth import tensor_uniform01
+    case = Case("cfg1", max_m=16, weights=lambda cfg: predictable_pair(cfg, 0, sigma=5.0, cache=True))
+    tree, T = case.tree, case.T
+    Tp = (T + 3) // 4 * 4
+    prompt = np.arange(5, 13)
+    n, iters = 24, 40
+    U = tensor_uniform01(52, "gen_uniforms", (iters, 3, Tp))
+
+    def run(delta):
+        us = [tuple(np.clip(U[i, j, :T].astype(np.float64) + delta, 0.0, 1.0 - 1e-12) for j in range(3))
+              for i in range(iters)]
+        r = oracle.generate_sampled(case.cfg, case.Wt, case.Wd, prompt, n, tree.parent, tree.rank, us, temperature)
+        return r["tokens"], r["accept_lens"], r["C"]
+    ref = run(0.0)
+    assert ref == run(-2e-5) == run(2e-5), "pick another seed: the oracle's own decisions are within the margin"
+    assert len(set(ref[1])) >= 3                      # several accepted lengths occur
+    feats, logits = case.prefill_oracle(prompt)
+    case.upload_kv()
+    root = oracle.inverse_cdf(oracle.softmax_t(logits[-1], temperature), U[0, 2, 0])
+    assert root == ref[0][0]
+    torch = case.torch
+    out = torch.full((n - 1,), -1, dtype=torch.int32, device=case.device)
+    stats = case.gpu.generate_sample(case.t(feats.astype(np.float32)),
+                                     case.t(np.concatenate([prompt[1:], [root]]).astype(np.int32)), len(prompt),
+                                     len(prompt), n - 1, case.t(U), temperature, out)
+    got = [root] + [int(t) for t in out.cpu().numpy()]
+    assert got == ref[0]
+    assert stats["accept_hist"] == _hist(ref[1]) and stats["iterations"] == len(ref[1])
+    assert int(case.kv["ctx_len"][0].item()) == ref[2]
+
+
+def test_nongreedy_generation_runs_out_of_uniforms_cleanly():
+    import paper_2408_08146_amd as K
+    from koala_synth import tensor_uniform01
+    case = Case("cfg1", max_m=16)
+    prompt = np.arange(5, 13)
+    feats, logits = case.prefill_oracle(prompt)
+    case.upload_kv()
+    torch = case.torch
+    out = torch.full((30,), -1, dtype=torch.int32, device=case.device)
+    U = case.t(tensor_uniform01(53, "few", (2, 3, 8)))       # two iterations cannot yield 30 tokens
+    with pytest.raises(K.KoalaError):
+        case.gpu.generate_sample(case.t(feats.astype(np.float32)),
+                                 case.t(np.concatenate([prompt[1:], [3]]).astype(np.int32)), len(prompt), len(prompt),
+                                 30, U, 1.0, out)
