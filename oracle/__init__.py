@@ -21,4 +21,4 @@ from .spec import (target_rows, decode_one, prefill, verify_tree, accept_greedy,
                    topk_desc, eagle_rows, eagle_expand, medusa_expand, iteration_eagle,
                    greedy_reference, generate_speculative, mean_tokens_per_iteration, n_alpha)
 from .sampling import (softmax_t, inverse_cdf, draw_without_replacement, accept_sample,  # noqa: F401
-                       eagle_expand_sample, generate_sampled)
+                       eagle_expand_sample, generate_sampled, medusa_expand_sample)

@@ -162,3 +162,35 @@ def generate_sampled(cfg, Wt, Wd, prompt, n_new, parent, rank, uniforms, tempera
         feat_in, tok_in = feat[path], np.asarray(emitted, np.int32)
         it += 1
     return dict(tokens=out[:n_new], accept_lens=accept_lens, C=C)
+
+
+def medusa_expand_sample(cfg, Wt, Wm, feat_last, root_token, parent, rank, n_heads_used, u_draw, temperature=1.0,
+                         dt=np.float64):
+    """Medusa-style draft with sampled children: head j (one per depth, K residual blocks, shared
+    LM head; section 3.1) gives one distribution for all nodes of depth j; the children of every
+    node of depth j-1 are draws without replacement from it, each parent with the uniforms of its
+    own children (draw order = rank).  Returns dict(tokens[T], logits{u: [V]} for nodes with
+    children: the logits of the head that drafts u's children)."""
+    from .llama import silu
+    T = len(parent)
+    depth = tree_depths(parent)
+    ch = children_lists(parent)
+    lm = _w(Wt, "lm_head", dt)
+    head_logits = []
+    for j in range(n_heads_used):
+        x = np.asarray(feat_last, dt)
+        for k in range(cfg["K"]):
+            x = x + silu(_w(Wm, f"medusa.{j}.{k}", dt) @ x)
+        head_logits.append(lm @ x)
+    tokens = np.zeros(T, np.int32)
+    tokens[0] = root_token
+    logits = {}
+    for u in range(T):                                   # parents precede children
+        if not ch[u]:
+            continue
+        logits[u] = head_logits[int(depth[u])]
+        kids = sorted(ch[u], key=lambda c: rank[c])
+        draws = draw_without_replacement(softmax_t(logits[u], temperature), [u_draw[c] for c in kids])
+        for c, x in zip(kids, draws):
+            tokens[c] = x
+    return dict(tokens=tokens, logits=logits)

@@ -220,3 +220,32 @@ def test_sampled_generation_with_a_perfect_draft_accepts_everything_it_can():
     got = oracle.generate_sampled(cfg, Wt, Wd, np.array([5, 6, 7]), 12, ch.parent, ch.rank, uniforms, temperature=0.02)
     assert got["tokens"] == [(8 + i) % 1000 for i in range(12)]
     assert all(a == 3 for a in got["accept_lens"])
+
+
+def test_medusa_sampled_draft_special_cases():
+    """Chain template at vanishing temperature == the top-1 Medusa draft; two parents of one depth
+    draw from the same distribution: equal uniforms give equal children, and the stored logits of a
+    parent are those of the head of the next depth."""
+    from helpers import NANO
+    from koala_synth.weights import target_weights, medusa_weights
+    cfg = dict(NANO, draft="medusa")
+    Wt = target_weights(cfg, 6, norm_gain="random", cache=True)
+    Wm = medusa_weights(cfg, 6, cache=True)
+    rng = np.random.default_rng(12)
+    feat = rng.normal(size=cfg["hidden"])
+    ch = chain_tree(3)
+    g = oracle.medusa_expand(cfg, Wt, Wm, feat, 7, ch.parent, ch.rank, ch.topk_per_depth)
+    s = oracle.medusa_expand_sample(cfg, Wt, Wm, feat, 7, ch.parent, ch.rank, 3, rng.random(4), temperature=1e-7)
+    np.testing.assert_array_equal(g["tokens"], s["tokens"])
+    tree = make_tree([2, 2], [1, 2, 4])
+    u = rng.random(tree.n_nodes)
+    kids = oracle.children_lists(tree.parent)
+    a, b = [x for x in range(tree.n_nodes) if tree.parent[x] == 0]           # the two depth-1 parents
+    for ca, cb in zip(sorted(kids[a], key=lambda c: tree.rank[c]), sorted(kids[b], key=lambda c: tree.rank[c])):
+        u[cb] = u[ca]
+    s = oracle.medusa_expand_sample(cfg, Wt, Wm, feat, 7, tree.parent, tree.rank, 2, u, temperature=1.0)
+    assert [s["tokens"][c] for c in sorted(kids[a])] == [s["tokens"][c] for c in sorted(kids[b])]
+    np.testing.assert_array_equal(s["logits"][a], s["logits"][b])
+    np.testing.assert_allclose(s["logits"][0], g["logits"][0])
+    np.testing.assert_allclose(s["logits"][a], g["logits"][1])
+    assert len(set(int(s["tokens"][c]) for c in kids[a])) == len(kids[a])     # without replacement
