@@ -192,7 +192,7 @@ koala_status koala_accept_prefix(koala_ctx *ctx, void *hip_stream, int batch,
                                  int commit);
 
 /* Non-greedy drafting (section 2.2: the drafted tokens are drawn from the draft distributions;
- * section 4.4 evaluates temperature 1).  As koala_draft_expand for an EAGLE-style head, but the
+ * section 4.4 evaluates temperature 1).  As koala_draft_expand, but the
  * children of a node are draws without replacement from softmax(draft logits at the node /
  * temperature): the child of lowest rank is drawn first, each later one from what is left after
  * removing the earlier draws, by inverse CDF over ascending token id (first id at which the
@@ -201,7 +201,9 @@ koala_status koala_accept_prefix(koala_ctx *ctx, void *hip_stream, int batch,
  *                (entry 0, the root, is not used);
  *   draft_logits device fp32 [batch, n_nodes, vocab] (out): row i = draft logits at node i, written
  *                for the nodes that have children; koala_accept_sample reads them.
- * Medusa-style heads: KOALA_E_UNSUPPORTED. */
+ * Medusa-style heads: the head of depth j gives one distribution for all nodes of that depth;
+ * every parent draws its own children from it (with its children's uniforms), and row i of
+ * draft_logits is the logits of the head that drafts node i's children. */
 koala_status koala_draft_expand_sample(koala_ctx *ctx, void *hip_stream, int batch,
                                        const float *feat_in, const int32_t *tok_in, int m,
                                        const float *u_draw, float temperature,

@@ -209,6 +209,15 @@ __device__ void scale_by(float *w, int V, double total) {
     }
 }
 
+// dst row (b * n_level + li) = src row (src_row0 + b), for every li: the shared per-depth logits of a
+// Medusa-style head get one private copy per parent node.  grid: batch * n_level.
+__global__ __launch_bounds__(256) void k_repeat_rows(const float *src, int src_row0, float *dst, int V, int n_level) {
+    const int row = blockIdx.x, b = row / n_level;
+    const float *s = src + (size_t)(src_row0 + b) * V;
+    float *d = dst + (size_t)row * V;
+    for (int i = threadIdx.x; i < V; i += 256) d[i] = s[i];
+}
+
 // grid: batch * n_level rows.  z: [rows][V] draft logits of the level's nodes (overwritten by weights).
 __global__ __launch_bounds__(NT) void k_sample_children(float *z, const int32_t *level_nodes, int n_level,
                                                          TreeTables tt, int T, int V, float inv_tau,
@@ -336,6 +345,10 @@ __global__ __launch_bounds__(NT) void k_accept_sample(TreeTables tt, int T, int 
 namespace ks {
 
 int max_vocab() { return MAX_SEG * SEG; }
+
+void repeat_rows(hipStream_t st, const float *src, int src_row0, float *dst, int V, int n_level, int batch) {
+    k_repeat_rows<<<batch * n_level, 256, 0, st>>>(src, src_row0, dst, V, n_level);
+}
 
 void sample_children(hipStream_t st, float *logits, const int32_t *level_nodes, int n_level, const TreeTables &tt,
                      int T, int V, float temperature, const float *u_draw, int32_t *tree_tokens,

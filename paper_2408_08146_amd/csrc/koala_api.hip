@@ -90,6 +90,7 @@ size_t carve(koala_ctx *c, char *base) {
     }
     c->gen_dlogits = w.take<float>((size_t)T * V);
     c->gen_tlogits = w.take<float>((size_t)T * V);
+    c->med_logits = c->draft.kind == KOALA_DRAFT_MEDUSA ? w.take<float>((size_t)D * c->max_batch * V) : nullptr;
     c->acc_q = w.take<float>((size_t)c->max_batch * V);
     c->acc_d = w.take<float>((size_t)c->max_batch * V);
     c->xf = nullptr;
@@ -430,8 +431,6 @@ static koala_status draft_expand_impl(koala_ctx *c, void *hip_stream, int batch,
     if (sampling) {
         if (!draft_logits) return fail(c, KOALA_E_NULL, "draft_logits is required when sampling");
         if (!(temperature > 0.f)) return fail(c, KOALA_E_SHAPE, "temperature must be positive");
-        if (c->draft.kind != KOALA_DRAFT_EAGLE)
-            return fail(c, KOALA_E_UNSUPPORTED, "sampled drafting is implemented for the EAGLE-style head only");
         if (c->shape.vocab > ks::max_vocab())
             return fail(c, KOALA_E_UNSUPPORTED, "vocabulary too large for the sampling kernels");
     }
@@ -461,7 +460,26 @@ static koala_status draft_expand_impl(koala_ctx *c, void *hip_stream, int batch,
                 }
             }
         }
-        if (D > 0) {
+        if (D > 0 && sampling) {
+            // logits of the D heads (row j * batch + b), then per depth one private copy per parent node, from
+            // which that node's children are drawn
+            if (bf) {
+                const int MT = kb::mt_of(D * batch), Vp = kb::pad64(V);
+                rows_to_frags(c, st, c->x, H, D * batch, H, MT);
+                const int S = bf_gemm(c, st, c->w.lm_head, V, H, MT);
+                kb::logits_topk(st, c->part, S, MT * 16, Vp, no_scale(), c->med_logits, V, D * batch, V, 1,
+                                c->cand_val, c->cand_idx, c->topk_idx, c->topk_val);
+            } else {
+                kg::gemm(st, bf, c->x, H, c->w.lm_head, c->med_logits, V, D * batch, V, H, false);
+            }
+            for (int d = 0; d < D; ++d) {
+                const int nl = (int)c->level_exp[d].size();
+                if (nl == 0) continue;
+                ks::repeat_rows(st, c->med_logits, d * batch, c->logits, V, nl, batch);
+                ks::sample_children(st, c->logits, c->tt.level_nodes + (size_t)d * 64, nl, c->tt, T, V, temperature,
+                                    u_draw, tree_tokens, draft_logits, batch);
+            }
+        } else if (D > 0) {
             if (bf) {
                 bf_lm_head_topk(c, st, c->x, H, D * batch, kmax, c->topk_idx, c->topk_val);
             } else {

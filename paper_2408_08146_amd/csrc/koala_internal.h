@@ -61,6 +61,7 @@ struct koala_ctx {
     float *gen_dlogits, *gen_tlogits;                    // [T][V] draft / target logits of the non-greedy loop
     float *gen_feat, *gen_feat_in;                       // [T][H] verify features; [max(D+1, max_m)][H] next draft inputs
     int32_t *gen_tree, *gen_greedy, *gen_acc, *gen_path, *gen_next, *gen_tok_in;
+    float *med_logits;                                   // [D * max_batch][V] per-depth logits of Medusa-style heads (sampled drafting)
     float *acc_q, *acc_d;                                // [max_batch][V] distributions of the stochastic acceptance walk
     // bf16 path: GEMM input as hi/lo bf16 MFMA fragments, and the split-K partial sums
     void *xf;
@@ -156,6 +157,8 @@ int max_vocab();   // largest vocabulary the sampling kernels handle
 void sample_children(hipStream_t st, float *logits, const int32_t *level_nodes, int n_level, const TreeTables &tt,
                      int T, int V, float temperature, const float *u_draw, int32_t *tree_tokens,
                      float *draft_logits, int batch);
+// dst[b * n_level + li][:] = src[src_row0 + b][:] for all li < n_level
+void repeat_rows(hipStream_t st, const float *src, int src_row0, float *dst, int V, int n_level, int batch);
 void accept_sample(hipStream_t st, const TreeTables &tt, int T, int D, int V, float temperature,
                    const int32_t *tree_tokens, const float *target_logits, const float *draft_logits,
                    const float *u_accept, const float *u_resample, float *qv, float *dv, int32_t *accept_len,

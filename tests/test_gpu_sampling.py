@@ -208,12 +208,32 @@ def test_bf16_sampled_draft_matches_oracle():
     assert compared >= 0.5 * total
 
 
+@pytest.mark.parametrize("K", [1, 2])
+def test_medusa_sampled_draft_matches_oracle(K):
+    """Medusa-style heads (bf16 path, 64-node tree): every parent draws its children from the
+    distribution of the next depth's head; also the stored logits equal that head's."""
+    TEMP = 0.05
+    case = Case("cfg3_small", K=K)
+    cfg, tree, T = case.cfg, case.tree, case.T
+    feat = tensor_normal(1, "medusa_feat", (1, 1, case.H))
+    tok = np.array([[11]], np.int32)
+    compared = total = 0
+    for trial in range(3):
+        ud = tensor_uniform01(33, f"ud{trial}", (1, T))
+        tokens, dl_dev = case.gpu_draft_sample(feat, tok, ud, TEMP)
+        ref = oracle.medusa_expand_sample(cfg, case.Wt, case.Wd, feat[0, 0].astype(np.float64), 11, tree.parent,
+                                          tree.rank, tree.depth, ud[0], TEMP)
+        n_cmp, n_all = _compare_sampled_tree(tree, ref, tokens[0], ud[0], TEMP, 5e-5)
+        compared += n_cmp
+        total += n_all
+        dl = dl_dev.cpu().numpy()
+        for u, row in ref["logits"].items():
+            assert rel_err_rows(dl[0, u][None], row[None]).max() < case.tol
+    assert compared >= 0.5 * total
+
+
 def test_sampling_argument_errors():
     import paper_2408_08146_amd as K
-    case = Case("cfg3_small")            # Medusa-style: sampled drafting is not implemented
-    with pytest.raises(K.KoalaError):
-        case.gpu_draft_sample(np.zeros((1, 1, case.H), np.float32), np.zeros((1, 1), np.int32),
-                              np.zeros((1, case.T), np.float32))
     case2 = Case("cfg1")
     with pytest.raises(K.KoalaError):    # temperature must be positive
         case2.gpu_draft_sample(np.zeros((1, 1, case2.H), np.float32), np.zeros((1, 1), np.int32),
