@@ -93,3 +93,35 @@ def test_unbound_context_refuses_compute_calls():
         ctx._check(st)
     assert e.value.status == -6
     ctx.close()
+
+
+def test_every_compute_entry_point_refuses_an_unbound_or_missing_context():
+    """No compute call may touch the device before a successful bind: each returns
+    KOALA_E_WORKSPACE (-6) for an unbound context and KOALA_E_NULL (-1) for a null one, on the host."""
+    _built()
+    ctx = KoalaContext(SHAPE, DRAFT, get_config("cfg1")["tree_template"], 1)
+    lib = ctx.lib
+    stats = (C.c_int32 * 66)()
+    f1 = C.c_float(1.0)
+    calls = {
+        "koala_draft_expand": lambda h: lib.koala_draft_expand(h, None, 1, None, None, 1, None, None),
+        "koala_tree_verify": lambda h: lib.koala_tree_verify(h, None, 1, None, None, None, None),
+        "koala_accept_prefix": lambda h: lib.koala_accept_prefix(h, None, 1, None, None, None, None, None, 0),
+        "koala_draft_expand_sample": lambda h: lib.koala_draft_expand_sample(h, None, 1, None, None, 1, None, f1, None,
+                                                                             None),
+        "koala_accept_sample": lambda h: lib.koala_accept_sample(h, None, 1, None, None, None, None, None, f1, None,
+                                                                 None, None, 0),
+        "koala_generate": lambda h: lib.koala_generate(h, None, None, None, 1, 1, 1, 1, None,
+                                                       C.cast(stats, C.POINTER(K.binding._GenStats))),
+        "koala_generate_sample": lambda h: lib.koala_generate_sample(h, None, None, None, 1, 1, 1, None, 1, f1, None,
+                                                                     C.cast(stats, C.POINTER(K.binding._GenStats))),
+    }
+    for name, call in calls.items():
+        got = call(ctx._h)
+        assert got in (-6, -1), (name, got)          # unbound (-6), or a null argument found first (-1)
+        assert call(None) == -1, name
+    # with every pointer present the unbound context itself is what is refused
+    dummy = C.c_void_p(256)
+    assert lib.koala_tree_verify(ctx._h, None, 1, dummy, dummy, None, dummy) == -6
+    assert lib.koala_accept_prefix(ctx._h, None, 1, dummy, dummy, dummy, dummy, dummy, 0) == -6
+    ctx.close()
