@@ -610,7 +610,9 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4 *qf = (u32x4 *)smem;                                   // [MT][KS][2][64]
     unsigned char *vt_all = smem + (size_t)MT * KS * 2 * 64 * 16;  // [4 waves][32][VS]
-    const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // blockIdx.x = key split + nsplit * (group of MT row tiles): sequences of more than MT*16 rows are
+    // covered by several workgroups per (split, head), each with its own MT tiles of rows
+    const int s = blockIdx.x % nsplit, mt0 = (blockIdx.x / nsplit) * MT, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, li = l & 15, lg = l >> 4;
     unsigned char *vt = vt_all + (size_t)wave * 32 * VS;
     const float scale = rsqrtf((float)DH);
@@ -645,7 +647,7 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
     // Q fragments (B operand): lane (row%16, g) holds Q[row][32*ks + 8*g .. +8], scaled, as hi and lo
     for (int u = tid; u < MT * KS * 64; u += 256) {
         const int lane = u & 63, ks = (u >> 6) % KS, mt = (u >> 6) / KS;
-        const int row = mt * 16 + (lane & 15);
+        const int row = (mt0 + mt) * 16 + (lane & 15);
         float y[8];
         if (row < rows_per_seq) {
             const float *q = qrot + (size_t)(b * rows_per_seq + row) * H + h * DH + ks * 32 + 8 * (lane >> 4);
@@ -672,7 +674,7 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
     uint64_t mask[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int row = mt * 16 + li;
+        const int row = (mt0 + mt) * 16 + li;
         const bool ok = row < rows_per_seq;
         const int r = b * rows_per_seq + (ok ? row : 0);
         nvis[mt] = ok ? meta.row_nvis[r] : 0;
@@ -831,7 +833,7 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
                 acc_o[mt][dt][2] += aw * o[2]; acc_o[mt][dt][3] += aw * o[3];
             }
         }
-        const int row = mt * 16 + li;
+        const int row = (mt0 + mt) * 16 + li;
         if (row < rows_per_seq) {
             const size_t r = (size_t)b * rows_per_seq + row;
             float *o = o_part + ((r * n_heads + h) * nsplit + s) * DH;
@@ -859,7 +861,8 @@ void launch_attn(hipStream_t st, const float *qrot, const RowMeta &meta, const v
                                   (int)sm);
         done = true;
     }
-    k_attn_mfma<DH, MT><<<dim3(nsplit, n_heads, batch), 256, sm, st>>>(
+    const int groups = (rows_per_seq + MT * 16 - 1) / (MT * 16);   // row-tile groups per (split, head)
+    k_attn_mfma<DH, MT><<<dim3(nsplit * groups, n_heads, batch), 256, sm, st>>>(
         qrot, meta, (const bf16_t *)kc, (const bf16_t *)vc, o_part, ml, rows_per_seq, n_heads, cap, nsplit,
         n_heads * DH);
 }
@@ -872,7 +875,11 @@ namespace kb {
 void attention_mfma(hipStream_t st, const float *qrot, const RowMeta &meta, const void *kc, const void *vc,
                     float *o_part, float *ml, int batch, int rows_per_seq, int n_heads, int head_dim, int cap,
                     int nsplit) {
-    const int MT = rows_per_seq <= 16 ? 1 : rows_per_seq <= 32 ? 2 : 4;
+    // more than 32 rows: two workgroups of two row tiles each per (split, head) (the four-tile kernel needs so
+    // many registers that only one workgroup fits a CU).  KOALA_ATTN_MT = 1, 2 or 4 forces the tiles per workgroup.
+    static const int forced = getenv("KOALA_ATTN_MT") ? atoi(getenv("KOALA_ATTN_MT")) : 0;
+    int MT = rows_per_seq <= 16 ? 1 : 2;
+    if (forced == 1 || (forced == 2 && rows_per_seq > 16) || (forced == 4 && rows_per_seq > 32)) MT = forced;
 #define KOALA_ATT(DHV, MTV) \
     launch_attn<DHV, MTV>(st, qrot, meta, kc, vc, o_part, ml, batch, rows_per_seq, n_heads, cap, nsplit)
     if (head_dim == 128) {
