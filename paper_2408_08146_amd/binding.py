@@ -69,6 +69,9 @@ def load_library():
     if not os.path.exists(path):
         raise KoalaError(-7, f"{path} not found: build it with `python -m paper_2408_08146_amd.build` "
                              "(or __graft_entry__.build())")
+    # PyTorch first: it ships its own HIP runtime, and the pointers and streams handed to the library come
+    # from it.  Loading the library before torch would bring a second runtime into the process.
+    import torch  # noqa: F401
     lib = C.CDLL(path)
     vp, ip = C.c_void_p, C.c_int
     lib.koala_create.argtypes = [C.POINTER(_Shape), C.POINTER(_DraftShape), C.POINTER(_Tree), ip, C.POINTER(vp)]
