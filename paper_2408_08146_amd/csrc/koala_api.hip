@@ -102,6 +102,8 @@ size_t carve(koala_ctx *c, char *base) {
         size_t worst = 0;
         for (auto &sh : shapes)
             worst = std::max(worst, (size_t)kb::gemm_splits(kb::pad64(sh[0]), sh[1]) * kb::pad64(sh[0]));
+        // the persistent verification cuts its GEMMs stream-K over the CUs (sized for 256 of them)
+        worst = std::max(worst, kp::part_floats_per_row(H, F, 256));
         c->part_bytes = worst * MTmax * 16 * sizeof(float);
         c->xf_bytes = kb::xf_bytes(std::max(2 * H, F), MTmax);
         c->xf = w.take<char>(c->xf_bytes);
@@ -109,6 +111,9 @@ size_t carve(koala_ctx *c, char *base) {
         c->row_sums = w.take<float>((size_t)R * 64);
         c->cand_val = w.take<float>((size_t)R * ((V + 1023) / 1024) * KOALA_TOPK_MAX);
         c->cand_idx = w.take<int>((size_t)R * ((V + 1023) / 1024) * KOALA_TOPK_MAX);
+        c->pl_layers = w.take<kp::Layer>(s.n_layers);
+        c->pl_bar = w.take<unsigned long long>(9 * 16);
+        c->pl_abort = w.take<int>(4);
     }
     return w.off;
 }
@@ -148,6 +153,12 @@ int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) 
         c->prof_bytes += (double)Npad * K * 2.0;
     }
     return S;
+}
+
+// KOALA_PERSISTENT=1: verification of one sequence of at most 32 rows runs all layers in one cooperative kernel
+bool persistent_enabled() {
+    const char *v = getenv("KOALA_PERSISTENT");   // read per call, so that a process can compare both paths
+    return v && atoi(v) != 0;
 }
 
 kb::NormScale no_scale() { return kb::NormScale{nullptr, 0, 0, 1, 0.f}; }
@@ -363,6 +374,27 @@ koala_status koala_bind(koala_ctx *c, const koala_weights *w, const koala_kv *kv
     if (e == hipSuccess) e = upload(c->tt.exp_index, c->exp_index);
     if (e == hipSuccess) e = upload(c->tt.draft_mask, c->draft_mask);
     if (e == hipSuccess) e = upload(c->tt.level_nodes, levels);
+    if (e == hipSuccess && c->shape.dtype == KOALA_BF16) {
+        // persistent verification: device table of the layers' pointers, zeroed barrier counters, abort flags
+        const size_t ls = layer_stride_bytes(c);
+        std::vector<kp::Layer> lt(c->shape.n_layers);
+        for (int l = 0; l < c->shape.n_layers; ++l) {
+            const void *const *lw = c->w.layer_w + 6 * l;
+            lt[l] = kp::Layer{lw[1], lw[2], lw[4], lw[5], lw[0], lw[3], (char *)c->kv.target_k + ls * l,
+                              (char *)c->kv.target_v + ls * l};
+        }
+        e = upload(c->pl_layers, lt);
+        if (e == hipSuccess) e = hipMemset(c->pl_bar, 0, 9 * 16 * sizeof(unsigned long long));
+        if (e == hipSuccess) e = hipMemset(c->pl_abort, 0, 4 * sizeof(int));
+        c->pl_gen = 0;
+        if (e == hipSuccess && !c->pl_abort_host) e = hipHostMalloc((void **)&c->pl_abort_host, 64, hipHostMallocDefault);
+        if (e == hipSuccess) *c->pl_abort_host = 0;
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (e == hipSuccess) e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+        if (e == hipSuccess) c->n_cu = prop.multiProcessorCount;
+    }
     if (e != hipSuccess) {
         c->bound = false;
         c->err = std::string("table upload failed: ") + hipGetErrorString(e);
@@ -391,9 +423,45 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
     if (bf) {
         const int MT = kb::mt_of(rows), Mp = MT * 16;
         c->pend_S = 0;
-        for (int l = 0; l < s.n_layers; ++l)
-            decoder_layer_bf16(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,
-                               (char *)c->kv.target_v + ls * l);
+        if (persistent_enabled() && kp::supported(rows, batch, s.head_dim, s.n_layers) && c->n_cu >= 8 && c->n_cu % 8 == 0 &&
+            c->n_cu <= 256) {
+            if (*c->pl_abort_host != 0) {
+                // an earlier pass timed out inside the kernel: its results were wrong; start from clean counters
+                *c->pl_abort_host = 0;
+                (void)hipMemsetAsync(c->pl_bar, 0, 9 * 16 * sizeof(unsigned long long), st);
+                (void)hipMemsetAsync(c->pl_abort, 0, 4 * sizeof(int), st);
+                c->pl_gen = 0;
+                return fail(c, KOALA_E_DEVICE, "an earlier persistent verification pass timed out; its outputs are invalid");
+            }
+            kp::Params q{};
+            const int ns = attn_nsplit(c);
+            q.layers = c->pl_layers;
+            q.L = s.n_layers; q.H = H; q.F = s.ffn; q.n_heads = s.n_heads; q.rows = rows; q.cap = c->kv.capacity;
+            q.nsplit = ns; q.srows = c->max_rows; q.eps = s.rms_eps;
+            q.x = c->x; q.x_bytes = (unsigned)((size_t)c->max_rows * H * 4);
+            q.Xf = c->xf; q.xf_bytes = (unsigned)c->xf_bytes;
+            q.part = c->part; q.part_bytes = (unsigned)c->part_bytes;
+            q.sums = c->row_sums; q.sums_bytes = (unsigned)((size_t)c->max_rows * 64 * 4);
+            q.qrot = c->qrot; q.qrot_bytes = (unsigned)((size_t)c->max_rows * H * 4);
+            q.o_part = c->o_part; q.opart_bytes = (unsigned)((size_t)c->max_rows * H * ns * 4);
+            q.ml = c->ml; q.ml_bytes = (unsigned)((size_t)c->max_rows * s.n_heads * ns * 2 * 4);
+            q.kv_layer_bytes = (unsigned)ls;
+            q.meta = c->meta;
+            q.bar = c->pl_bar; q.bar_base = c->pl_gen;
+            q.abort_flag = c->pl_abort; q.abort_host = c->pl_abort_host;
+            if (ls > 0xFFFFFF00ull || c->part_bytes > 0xFFFFFF00ull)
+                return fail(c, KOALA_E_UNSUPPORTED, "buffers too large for the persistent verification kernel");
+            const hipError_t le = kp::launch(st, q, MT, c->n_cu);
+            if (le != hipSuccess) {
+                c->err = std::string("cooperative launch failed: ") + hipGetErrorString(le);
+                return KOALA_E_DEVICE;
+            }
+            c->pl_gen += (unsigned long long)kp::BARRIERS_PER_LAYER * s.n_layers;
+        } else {
+            for (int l = 0; l < s.n_layers; ++l)
+                decoder_layer_bf16(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,
+                                   (char *)c->kv.target_v + ls * l);
+        }
         // last down projection folded in; the LM head runs on gain * x and its logits take the row scale;
         // the features (an output) are normalised separately
         fold_pending(c, st, rows, MT, c->w.final_norm);
@@ -785,6 +853,7 @@ const char *koala_last_error(const koala_ctx *ctx) { return ctx ? ctx->err.c_str
 void koala_destroy(koala_ctx *ctx) {
     if (!ctx) return;
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+    if (ctx->pl_abort_host) (void)hipHostFree(ctx->pl_abort_host);
     delete ctx;
 }
 

@@ -35,6 +35,44 @@ struct TreeTables {
     int32_t *child_first, *child_count;  // unused by kernels that scan; kept for clarity
 };
 
+// ---------------------------------------------------------------------------------------------
+// kernels_persistent.hip: all decoder layers of a verification pass in one cooperative kernel
+// ---------------------------------------------------------------------------------------------
+namespace kp {
+
+struct Layer {   // device pointers of one decoder layer (array in the workspace)
+    const void *wqkv, *wo, *wgu, *wdown, *in_norm, *post_norm;
+    void *kc, *vc;
+};
+
+struct Params {
+    const Layer *layers;
+    int L, H, F, n_heads, rows, cap, nsplit, srows;
+    float eps;
+    float *x;       unsigned x_bytes;       // residual stream [rows][H]
+    void *Xf;       unsigned xf_bytes;      // GEMM input fragments
+    float *part;    unsigned part_bytes;    // partial sums [slot][MT*16][Npad]
+    float *sums;    unsigned sums_bytes;    // per-chunk sums of squares [chunk][srows]
+    float *qrot;    unsigned qrot_bytes;    // rotated queries [rows][H]
+    float *o_part;  unsigned opart_bytes;   // attention partial outputs
+    float *ml;      unsigned ml_bytes;      // their running max / sum
+    unsigned kv_layer_bytes;                // bytes of one layer of a KV cache
+    RowMeta meta;
+    unsigned long long *bar;                // grid barrier counters (9 x 128 B), monotonic across launches
+    unsigned long long bar_base;            // barrier generations used by earlier launches
+    int *abort_flag;                        // device: set when a wait timed out
+    int *abort_host;                        // pinned host memory: set by the kernel on abort
+};
+
+enum { BARRIERS_PER_LAYER = 10 };
+
+bool supported(int rows, int batch, int head_dim, int n_layers);
+// floats the partial-sum buffer needs per activation row for the stream-K cut over G workgroups
+size_t part_floats_per_row(int H, int F, int G);
+hipError_t launch(hipStream_t st, const Params &p, int MT, int G);
+
+}  // namespace kp
+
 struct koala_ctx {
     koala_shape shape;
     koala_draft_shape draft;
@@ -61,6 +99,13 @@ struct koala_ctx {
     float *gen_dlogits, *gen_tlogits;                    // [T][V] draft / target logits of the non-greedy loop
     float *gen_feat, *gen_feat_in;                       // [T][H] verify features; [max(D+1, max_m)][H] next draft inputs
     int32_t *gen_tree, *gen_greedy, *gen_acc, *gen_path, *gen_next, *gen_tok_in;
+    // persistent verification (kernels_persistent.hip)
+    kp::Layer *pl_layers;          // [n_layers] device copy of the layer pointers
+    unsigned long long *pl_bar;    // grid barrier counters
+    int *pl_abort;                 // device abort flag
+    int *pl_abort_host;            // pinned host abort flag
+    unsigned long long pl_gen;     // barrier generations consumed so far
+    int n_cu;                      // compute units of the device the context is bound on
     float *med_logits;                                   // [D * max_batch][V] per-depth logits of Medusa-style heads (sampled drafting)
     float *acc_q, *acc_d;                                // [max_batch][V] distributions of the stochastic acceptance walk
     // bf16 path: GEMM input as hi/lo bf16 MFMA fragments, and the split-K partial sums

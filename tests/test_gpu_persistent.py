@@ -1,0 +1,84 @@
+"""The single-kernel verification path (all decoder layers in one cooperative kernel, switched on by
+KOALA_PERSISTENT=1) against the oracle and against the per-layer kernels, through the C ABI.
+
+The shapes are the reduced-width relatives of the bf16 configurations: their projections have fewer
+(row group, k tile) pairs than the chip has workgroups, a ragged last row group (cfg4_small) and one or
+two row tiles (1-node tree, 26-node tree), so the stream-K cut is exercised with idle workgroups, single
+tiles per workgroup and partial sums spread over several slots."""
+import numpy as np
+import pytest
+
+import oracle
+
+from gpu_harness import Case, rel_err_rows, compare_logits_and_greedy
+
+pytestmark = pytest.mark.gpu
+
+
+def _verify_both(case, tt, monkeypatch):
+    monkeypatch.setenv("KOALA_PERSISTENT", "0")
+    case.upload_kv()
+    base = case.gpu_verify(tt)
+    kv_base = case.download_kv("target")
+    monkeypatch.setenv("KOALA_PERSISTENT", "1")
+    case.upload_kv()
+    pers = case.gpu_verify(tt)
+    kv_pers = case.download_kv("target")
+    monkeypatch.setenv("KOALA_PERSISTENT", "0")
+    return base, kv_base, pers, kv_pers
+
+
+@pytest.mark.parametrize("cfgname", ["cfg2_small", "cfg4_small"])
+def test_persistent_verify_matches_oracle_and_layer_kernels(cfgname, monkeypatch):
+    case = Case(cfgname)
+    case.fill_kv_normal()
+    tt = case.random_tree_tokens()
+    (bfeat, blogits, bgreedy), kv_base, (feat, logits, greedy), kv_pers = _verify_both(case, tt, monkeypatch)
+    rfeat, rlogits, rgreedy = case.oracle_verify(tt)
+    skipped, err = compare_logits_and_greedy(case, logits, greedy, rlogits, rgreedy)
+    assert skipped <= max(1, case.B * case.T // 10)
+    assert rel_err_rows(feat, rfeat).max() < case.tol
+    # both device paths do the same arithmetic up to the order of the partial sums
+    assert rel_err_rows(logits, blogits).max() < 1e-3
+    assert rel_err_rows(feat, bfeat).max() < 1e-3
+    # the tree rows' keys and values land in the same cache slots (bf16 storage: equal up to one rounding step)
+    for a, b in zip(kv_pers, kv_base):
+        a, b = np.asarray(a, np.float32), np.asarray(b, np.float32)
+        assert a.shape == b.shape
+        assert np.abs(a - b).max() <= 2.0 ** -6 * max(1.0, float(np.abs(b).max()))
+
+
+def test_persistent_single_node_tree_is_plain_decoding(monkeypatch):
+    """One row tile, one row: three autoregressive steps (Eq. 1) with commit in between."""
+    case = Case("cfg2_small", tree=dict(topk=[], widths=[1]))
+    case.fill_kv_normal()
+    case.upload_kv()
+    monkeypatch.setenv("KOALA_PERSISTENT", "1")
+    tok = 17
+    C0 = case.ctx_lens[0]
+    for step in range(3):
+        feat, logits, greedy = case.gpu_verify(np.array([[tok]], np.int32))
+        f, l = oracle.decode_one(case.cfg, case.Wt, case.tc[0], C0 + step, tok)
+        assert rel_err_rows(logits[0], l[None]).max() < case.tol
+        a, path, nxt = case.gpu_accept(np.array([[tok]], np.int32), greedy, commit=True)
+        assert a[0] == 0 and int(case.kv["ctx_len"][0].item()) == C0 + step + 1
+        tok = int(np.argmax(l))
+        assert tok == greedy[0, 0]
+    monkeypatch.setenv("KOALA_PERSISTENT", "0")
+
+
+def test_persistent_repeated_calls_are_bitwise_stable(monkeypatch):
+    """The partial sums are added in a fixed order: two passes over the same inputs give the same bits,
+    and the barrier counters carry over from one launch to the next."""
+    case = Case("cfg2_small")
+    case.fill_kv_normal()
+    tt = case.random_tree_tokens()
+    monkeypatch.setenv("KOALA_PERSISTENT", "1")
+    outs = []
+    for _ in range(3):
+        case.upload_kv()
+        outs.append(case.gpu_verify(tt))
+    monkeypatch.setenv("KOALA_PERSISTENT", "0")
+    for o in outs[1:]:
+        np.testing.assert_array_equal(o[1], outs[0][1])
+        np.testing.assert_array_equal(o[2], outs[0][2])
