@@ -33,8 +33,11 @@ typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef unsigned short __attribute__((may_alias)) u16_alias;
 typedef unsigned long long __attribute__((may_alias)) u64_lds;
 
-constexpr int NS = 4;                 // weight tiles a stream wave keeps in registers / in flight
-constexpr int XR = 3;                 // activation tiles in the LDS ring
+#ifndef KOALA_PL_NS
+#define KOALA_PL_NS 4
+#endif
+constexpr int NS = KOALA_PL_NS;       // weight tiles a stream wave keeps in registers / in flight (3..6)
+constexpr int XR = 8;                 // activation tiles in the LDS ring
 constexpr int AUX_SC1 = 16, AUX_NT = 2;
 constexpr int MAX_LAYERS = 96;        // layers the weight address table in LDS holds
 constexpr long long TIMEOUT_TICKS = 25000000LL;   // 0.25 s of the 100 MHz wall clock
@@ -95,7 +98,7 @@ struct Kind {
 
 struct __attribute__((aligned(16))) Ctl {
     Kind kind[4];
-    int xflag[4];     // xflag[s] = seq + 1 of the activation tile in ring slot s (XR <= 4)
+    int xflag[XR];    // xflag[s] = seq + 1 of the activation tile in ring slot s
     int done[4];      // tiles finished by stream wave w (monotonic)
     int p_ready[4];   // flushes staged by stream wave w
     int p_taken[4];   // flushes written out by chain wave w
@@ -117,14 +120,18 @@ __device__ __forceinline__ int sk_slots(int rg, const Kind &k) {
     return sk_owner((rg + 1) * k.KT - 1, k.total, k.geff) - sk_owner(rg * k.KT, k.total, k.geff) + 1;
 }
 
+// LDS of a workgroup (dynamic, above the 64 KiB a static allocation may have): the activation ring and the
+// partial-sum staging (the attention step reuses both), then the control block and the weight addresses.
+constexpr int AREA_BYTES = XR * 2 * 4096 + 4 * 2 * 4096;   // sized for MT = 2
 struct Shared {
-    // activation ring and partial-sum staging; the attention step reuses the whole area
-    unsigned char area[XR * 2 * 4096 + 4 * 2 * 4096];   // sized for MT = 2
+    unsigned char area[AREA_BYTES];
     Ctl ctl;
     // weight addresses (low, high word) of phase g = 4 * layer + projection: the stream waves read them from
     // here, because a global load in their instruction stream would have to wait for the whole weight queue
     unsigned wtab[MAX_LAYERS * 4][2];
+    long long tl[64][3];   // diagnostic: per-tile timestamps of stream wave 0 in one layer
 };
+constexpr int TRACE_LAYER = 5;
 
 // ---------------------------------------------------------------------------------------------
 // helpers of the chain waves
@@ -153,7 +160,11 @@ __device__ void chain_sync(Chain &k) {
 
 // all global stores of this workgroup's chain waves are complete, then every workgroup has arrived
 __device__ void grid_barrier(Chain &k) {
+    const bool tracer = k.p.trace && k.w == 0 && k.c == 0 && k.l == 0;
+    const int ntr = 2 + 10 * k.p.L;
+    if (tracer) k.p.trace[ntr + (k.gen + 1 - k.p.bar_base)] = wall_clock64();         // work of the step issued
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    if (tracer) k.p.trace[2 * ntr + (k.gen + 1 - k.p.bar_base)] = wall_clock64();     // stores acknowledged
     LDS_RELEASE();
     chain_sync(k);
     ++k.gen;
@@ -188,6 +199,7 @@ __device__ void grid_barrier(Chain &k) {
         }
     }
     LDS_ACQUIRE();
+    if (k.p.trace && k.w == 0 && k.c == 0 && k.l == 0) k.p.trace[k.gen - k.p.bar_base] = wall_clock64();
     if (LDS_LD(&k.ctl->abort_l)) {
         // tell the workgroups that still wait at a barrier
         if (k.l == 0) __hip_atomic_store(k.p.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -195,38 +207,63 @@ __device__ void grid_barrier(Chain &k) {
     }
 }
 
-// sum over the slots of row group rg of 8 consecutive columns (col % 8 == 0) of row m
-__device__ __forceinline__ void psum8(rsrc_t rP, int Mp, const Kind &kd, int m, int col, float *v) {
+// Loads of partial sums are issued in deep batches with unconditional instructions: a slot that does not
+// exist gets an offset past the end of the buffer, which reads zeros without touching memory.  A sum then
+// costs one memory round trip per batch instead of one per slot; the order of the additions is fixed.
+constexpr unsigned OOB = 0xFFFFFF00u;
+
+// NV consecutive float4 (col % 4 == 0) of row m summed over the slots of the columns' row group
+template <int NV, int NB>
+__device__ __forceinline__ void psumv(rsrc_t rP, int Mp, const Kind &kd, int m, int col, f32x4 *out) {
     const int S = sk_slots(col >> 8, kd);
-    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-    for (int s0 = 0; s0 < S; s0 += 4) {   // four slots' loads in flight
-        f32x4 a[4], b[4];
+    const unsigned stride = (unsigned)Mp * (unsigned)kd.Npad * 4u;
+    const unsigned base = ((unsigned)m * (unsigned)kd.Npad + (unsigned)col) * 4u;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const unsigned off = (unsigned)((((size_t)(s0 + u) * Mp + m) * kd.Npad + col) * 4);
-            const bool in = s0 + u < S;
-            a[u] = in ? ldf4<AUX_SC1>(rP, off) : (f32x4){0.f, 0.f, 0.f, 0.f};
-            b[u] = in ? ldf4<AUX_SC1>(rP, off + 16) : (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < NV; ++i) out[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < S; s0 += NB) {
+        f32x4 t[NB][NV];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const unsigned off = s0 + u < S ? base + (unsigned)(s0 + u) * stride : OOB;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) t[u][i] = ldf4<AUX_SC1>(rP, off + 16u * i);
         }
-        lo += (a[0] + a[1]) + (a[2] + a[3]);
-        hi += (b[0] + b[1]) + (b[2] + b[3]);
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
+#pragma unroll
+            for (int i = 0; i < NV; ++i) out[i] += t[u][i];
     }
-    v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
-    v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
 }
 
-// one column of row m
-__device__ __forceinline__ float psum1(rsrc_t rP, int Mp, const Kind &kd, int m, int col) {
-    const int S = sk_slots(col >> 8, kd);
-    float acc = 0.f;
-    for (int s0 = 0; s0 < S; s0 += 4) {
-        float t[4];
+// NC single columns of row m, all in the same row group as cols[0]
+template <int NC, int NB>
+__device__ __forceinline__ void psumc(rsrc_t rP, int Mp, const Kind &kd, int m, const int *cols, float *out) {
+    const unsigned stride = (unsigned)Mp * (unsigned)kd.Npad * 4u;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            t[u] = s0 + u < S ? ldf1<AUX_SC1>(rP, (unsigned)((((size_t)(s0 + u) * Mp + m) * kd.Npad + col) * 4)) : 0.f;
-        acc += (t[0] + t[1]) + (t[2] + t[3]);
+    for (int i = 0; i < NC; ++i) out[i] = 0.f;
+    int S[NC];
+    int Smax = 0;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        S[i] = sk_slots(cols[i] >> 8, kd);
+        Smax = max(Smax, S[i]);
     }
-    return acc;
+    for (int s0 = 0; s0 < Smax; s0 += NB) {
+        float t[NB][NC];
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                const unsigned off = s0 + u < S[i]
+                                         ? ((unsigned)m * (unsigned)kd.Npad + (unsigned)cols[i]) * 4u + (unsigned)(s0 + u) * stride
+                                         : OOB;
+                t[u][i] = ldf1<AUX_SC1>(rP, off);
+            }
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
+#pragma unroll
+            for (int i = 0; i < NC; ++i) out[i] += t[u][i];
+    }
 }
 
 // 8 consecutive k of row m (k0 % 8 == 0) as hi/lo fragments
@@ -247,12 +284,24 @@ __device__ __forceinline__ void store_frag8(rsrc_t rX, int m, int k0, const floa
     st128(rX, o + 64 * 16, q);
 }
 
-// 1 / sqrt(mean(x^2) + eps) of row m from the per-512-column sums of squares
-__device__ __forceinline__ float row_scale(rsrc_t rS, int nparts, int srows, int H, float eps, int m) {
-    float tot = 0.f;
-    for (int c = 0; c < nparts; ++c) tot += ldf1<AUX_SC1>(rS, (unsigned)(((size_t)c * srows + m) * 4));
-    return 1.0f / sqrtf(tot / (float)H + eps);
-}
+// 1 / sqrt(mean(x^2) + eps) of row m from the per-512-column sums of squares.  The loads are issued by
+// the constructor and consumed by get(), so that they share a round trip with whatever is loaded in between.
+struct RowScale {
+    float t[16];
+    float rest;
+    __device__ __forceinline__ RowScale(rsrc_t rS, int nparts, int srows, int m) {
+#pragma unroll
+        for (int c = 0; c < 16; ++c) t[c] = ldf1<AUX_SC1>(rS, c < nparts ? (unsigned)(c * srows + m) * 4u : OOB);
+        rest = 0.f;
+        for (int c = 16; c < nparts; ++c) rest += ldf1<AUX_SC1>(rS, (unsigned)(c * srows + m) * 4u);
+    }
+    __device__ __forceinline__ float get(int H, float eps) const {
+        float tot = rest;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) tot += t[c];
+        return 1.0f / sqrtf(tot / (float)H + eps);
+    }
+};
 
 // ---------------------------------------------------------------------------------------------
 // the small steps, executed by the chain waves of all workgroups; unit = one wave
@@ -271,8 +320,14 @@ __device__ void step_fold(Chain &k, int mode, const Kind &prev, const void *gain
         float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if (j < p.H) {
             const unsigned xo = (unsigned)(((size_t)m * p.H + j) * 4);
-            if (mode != 0) psum8(rP, MT * 16, prev, m, j, v);
             const f32x4 a = ldf4<AUX_SC1>(rx, xo), b = ldf4<AUX_SC1>(rx, xo + 16);
+            const u32x4 g = ld128<0>(rg, frags ? (unsigned)j * 2 : OOB);
+            if (mode != 0) {
+                f32x4 ps[2];
+                psumv<2, 10>(rP, MT * 16, prev, m, j, ps);
+                v[0] = ps[0][0]; v[1] = ps[0][1]; v[2] = ps[0][2]; v[3] = ps[0][3];
+                v[4] = ps[1][0]; v[5] = ps[1][1]; v[6] = ps[1][2]; v[7] = ps[1][3];
+            }
             v[0] += a[0]; v[1] += a[1]; v[2] += a[2]; v[3] += a[3];
             v[4] += b[0]; v[5] += b[1]; v[6] += b[2]; v[7] += b[3];
             if (mode != 0) {
@@ -280,7 +335,6 @@ __device__ void step_fold(Chain &k, int mode, const Kind &prev, const void *gain
                 stf4(rx, xo + 16, (f32x4){v[4], v[5], v[6], v[7]});
             }
             if (frags) {
-                const u32x4 g = ld128<0>(rg, (unsigned)j * 2);
                 const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
                 float y[8];
 #pragma unroll
@@ -310,10 +364,12 @@ __device__ void step_rope(Chain &k, const Kind &kq, rsrc_t rK, rsrc_t rV) {
         const int b = p.meta.row_b[r], slot = p.meta.row_slot[r];
         const float cs = p.meta.rope_cos[(size_t)r * half + i], sn = p.meta.rope_sin[(size_t)r * half + i];
         const int c0 = h * DH + i;
-        const float sc = row_scale(rS, (H + 511) / 512, p.srows, H, p.eps, r);
-        const float q0 = sc * psum1(rP, MT * 16, kq, r, c0), q1 = sc * psum1(rP, MT * 16, kq, r, c0 + half);
-        const float k0 = sc * psum1(rP, MT * 16, kq, r, H + c0), k1 = sc * psum1(rP, MT * 16, kq, r, H + c0 + half);
-        const float v0 = sc * psum1(rP, MT * 16, kq, r, 2 * H + c0), v1 = sc * psum1(rP, MT * 16, kq, r, 2 * H + c0 + half);
+        const RowScale rsc(rS, (H + 511) / 512, p.srows, r);
+        const int cols[6] = {c0, c0 + half, H + c0, H + c0 + half, 2 * H + c0, 2 * H + c0 + half};
+        float t6[6];
+        psumc<6, 8>(rP, MT * 16, kq, r, cols, t6);
+        const float sc = rsc.get(H, p.eps);
+        const float q0 = sc * t6[0], q1 = sc * t6[1], k0 = sc * t6[2], k1 = sc * t6[3], v0 = sc * t6[4], v1 = sc * t6[5];
         const unsigned qo = (unsigned)(((size_t)r * H + c0) * 4);
         stf1(rq, qo, q0 * cs - q1 * sn);
         stf1(rq, qo + half * 4, q1 * cs + q0 * sn);
@@ -386,10 +442,13 @@ __device__ void step_silu(Chain &k, const Kind &kgu) {
     for (int u = k.w * 4 + k.c; u < nch * p.rows; u += k.G * 4) {
         const int c = u % nch, r = u / nch, g = c * 64 + k.l;
         if (g >= p.F / 8) continue;
+        const RowScale rsc(rS, (p.H + 511) / 512, p.srows, r);
+        f32x4 gv[4];
+        psumv<4, 4>(rP, MT * 16, kgu, r, g * 16, gv);
         float gu[16];
-        psum8(rP, MT * 16, kgu, r, g * 16, gu);
-        psum8(rP, MT * 16, kgu, r, g * 16 + 8, gu + 8);
-        const float sc = row_scale(rS, (p.H + 511) / 512, p.srows, p.H, p.eps, r);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) gu[e] = gv[e >> 2][e & 3];
+        const float sc = rsc.get(p.H, p.eps);
         float y[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -643,7 +702,8 @@ __device__ void attn_unit(Chain &k, unsigned char *smem, int s, int h, rsrc_t rK
 // ---------------------------------------------------------------------------------------------
 template <int MT>
 __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
-    __shared__ Shared sh;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    Shared &sh = *(Shared *)lds_raw;
     constexpr int XT = MT * 256;                        // 16-byte words per activation tile (64 k)
     u32x4 *xring = (u32x4 *)sh.area;                    // [XR][XT]
     f32x4 *pstage = (f32x4 *)(sh.area + XR * XT * 16);  // [4 stream waves][4 * MT * 64]
@@ -721,8 +781,18 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
         ISSUE(0)
         ISSUE(1)
         ISSUE(2)
+#if KOALA_PL_NS > 3
         ISSUE(3)
+#endif
+#if KOALA_PL_NS > 4
+        ISSUE(4)
+#endif
+#if KOALA_PL_NS > 5
+        ISSUE(5)
+#endif
         int seq = 0, nflush = 0, dead = 0;
+        long long xw0 = 0, xw1 = 0, xw2 = 0, xw3 = 0;   // ticks spent waiting for activation tiles, per projection
+        int tli = 0;
         f32x4 acc[4][MT];
 #pragma unroll
         for (int t = 0; t < 4; ++t)
@@ -766,11 +836,19 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
         if (cg < ng && !dead) {                                                                          \
             const int xs = seq % XR;                                                                     \
             const long long tb = wall_clock64();                                                         \
+            const bool ttile = p.trace && w == 0 && wave == 0 && l == 0 && (cg >> 2) == TRACE_LAYER && tli < 64; \
+            if (ttile) sh.tl[tli][0] = tb;                                                               \
             while (LDS_LD(&ctl->xflag[xs]) != seq + 1) {                                                 \
                 __builtin_amdgcn_s_sleep(1);                                                             \
                 if (LDS_LD(&ctl->abort_l) || wall_clock64() - tb > TIMEOUT_TICKS) { dead = 1; LDS_ST(&ctl->abort_l, 1); break; } \
             }                                                                                            \
             LDS_ACQUIRE();                                                                               \
+            {                                                                                            \
+                const long long dtx = wall_clock64() - tb;                                               \
+                const int kx = cg & 3;                                                                   \
+                xw0 += kx == 0 ? dtx : 0; xw1 += kx == 1 ? dtx : 0; xw2 += kx == 2 ? dtx : 0; xw3 += kx == 3 ? dtx : 0; \
+            }                                                                                            \
+            if (ttile) sh.tl[tli][1] = wall_clock64();                                                   \
             if (!dead) {                                                                                 \
                 const u32x4 *xt = xring + xs * XT;                                                       \
                 if (c_rg * 4 + wave < c_nrb) {                                                           \
@@ -791,6 +869,7 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
                 ++seq;                                                                                   \
                 LDS_RELEASE();                                                                           \
                 if (l == 0) LDS_ST(&ctl->done[wave], seq);                                               \
+                if (ttile) { sh.tl[tli][2] = wall_clock64() | ((long long)(cg & 3) << 60); ++tli; }       \
                 ++ci; ++c_k;                                                                             \
                 if (c_k == c_KT || ci == cn) { FLUSH() c_k = 0; ++c_rg; }                                \
                 if (ci == cn) { C_NEXT_PHASE() }                                                         \
@@ -801,7 +880,21 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
             STEP(0)
             STEP(1)
             STEP(2)
+#if KOALA_PL_NS > 3
             STEP(3)
+#endif
+#if KOALA_PL_NS > 4
+            STEP(4)
+#endif
+#if KOALA_PL_NS > 5
+            STEP(5)
+#endif
+        }
+        if (p.trace && w == 0 && wave == 0 && l == 0) {
+            long long *tx = p.trace + 3 * (2 + 10 * p.L);
+            tx[0] = xw0; tx[1] = xw1; tx[2] = xw2; tx[3] = xw3;
+            tx[4] = tli;
+            for (int i = 0; i < tli; ++i) { tx[5 + 3 * i] = sh.tl[i][0]; tx[6 + 3 * i] = sh.tl[i][1]; tx[7 + 3 * i] = sh.tl[i][2]; }
         }
     } else {
         // ============================================================== chain wave
@@ -826,8 +919,18 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
                 const int rg0 = t0 / d.KT, rg1 = (t0 + n - 1) / d.KT;
                 int feed = c, drg = rg0;
                 long long tb = wall_clock64();
+                // the next activation tile of this wave is requested before its ring slot is free
+                u32x4 v[MT * 4];
+                bool loaded = false;
                 while ((feed < n || drg <= rg1) && !k.dead) {
                     bool progressed = false;
+                    if (feed < n && !loaded) {
+                        const int kt = (t0 + feed) % d.KT;
+#pragma unroll
+                        for (int u = 0; u < MT * 4; ++u)
+                            v[u] = ld128<AUX_SC1>(rX, (unsigned)(((size_t)kt * XT + u * 64 + l) * 16));
+                        loaded = true;
+                    }
                     if (feed < n) {
                         const int seq = seq_base + feed;
                         int md = LDS_LD(&ctl->done[0]);
@@ -836,17 +939,13 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
                         md = min(md, LDS_LD(&ctl->done[3]));
                         if (seq < XR || md >= seq - XR + 1) {
                             LDS_ACQUIRE();
-                            const int kt = (t0 + feed) % d.KT;
-                            u32x4 v[MT * 4];
-#pragma unroll
-                            for (int u = 0; u < MT * 4; ++u)
-                                v[u] = ld128<AUX_SC1>(rX, (unsigned)(((size_t)kt * XT + u * 64 + l) * 16));
                             u32x4 *dst = xring + (seq % XR) * XT;
 #pragma unroll
                             for (int u = 0; u < MT * 4; ++u) dst[u * 64 + l] = v[u];
                             LDS_RELEASE();
                             if (l == 0) LDS_ST(&ctl->xflag[seq % XR], seq + 1);
                             feed += 4;
+                            loaded = false;
                             progressed = true;
                         }
                     }
@@ -884,6 +983,7 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
             }
             grid_barrier(k);
         };
+        if (p.trace && w == 0 && c == 0 && l == 0) p.trace[0] = wall_clock64();
         for (int ly = 0; ly < p.L && !k.dead; ++ly) {
             const kp::Layer &L = p.layers[ly];
             const rsrc_t rK = make_rsrc(L.kc, p.kv_layer_bytes), rV = make_rsrc(L.vc, p.kv_layer_bytes);
@@ -911,6 +1011,7 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
         }
         if (!k.dead) step_fold<MT>(k, 1, kd[G_DOWN], nullptr, false);   // the last down projection into x
         __builtin_amdgcn_s_waitcnt(0x0F70);
+        if (p.trace && w == 0 && c == 0 && l == 0) p.trace[1 + 10 * p.L] = wall_clock64();
         if (k.dead && l == 0 && c == 0 && p.abort_host) *p.abort_host = 1;
     }
 }
@@ -947,7 +1048,13 @@ hipError_t launch(hipStream_t st, const Params &p, int MT, int G) {
     Params q = p;
     void *args[] = {&q};
     const void *fn = MT == 1 ? (const void *)k_layers_persistent<1> : (const void *)k_layers_persistent<2>;
-    return hipLaunchCooperativeKernel(fn, dim3(G), dim3(512), args, 0, st);
+    static bool attr_done[2] = {false, false};
+    if (!attr_done[MT - 1]) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Shared));
+        if (e != hipSuccess) return e;
+        attr_done[MT - 1] = true;
+    }
+    return hipLaunchCooperativeKernel(fn, dim3(G), dim3(512), args, sizeof(Shared), st);
 }
 
 }  // namespace kp

@@ -451,7 +451,58 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
             q.abort_flag = c->pl_abort; q.abort_host = c->pl_abort_host;
             if (ls > 0xFFFFFF00ull || c->part_bytes > 0xFFFFFF00ull)
                 return fail(c, KOALA_E_UNSUPPORTED, "buffers too large for the persistent verification kernel");
+            // KOALA_PERSISTENT_TRACE=1 (diagnostic): time of every step as workgroup 0 sees it, printed per call
+            static long long *trace_dev = nullptr;
+            const char *tr = getenv("KOALA_PERSISTENT_TRACE");
+            const size_t n_tr = 2 + (size_t)kp::BARRIERS_PER_LAYER * s.n_layers;
+            if (tr && atoi(tr) != 0) {
+                if (!trace_dev && hipMalloc((void **)&trace_dev, (3 * (2 + kp::BARRIERS_PER_LAYER * 1024) + 4 + 1 + 3 * 64) * sizeof(long long)) != hipSuccess)
+                    trace_dev = nullptr;
+                if (s.n_layers <= 1024) q.trace = trace_dev;
+            }
             const hipError_t le = kp::launch(st, q, MT, c->n_cu);
+            if (q.trace && le == hipSuccess) {
+                std::vector<long long> t(3 * n_tr + 4 + 1 + 3 * 64);
+                if (hipStreamSynchronize(st) == hipSuccess &&
+                    hipMemcpy(t.data(), trace_dev, (3 * n_tr + 4 + 1 + 3 * 64) * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess) {
+                    static const char *names[10] = {"fold_in", "qkv", "rope", "attn", "combine", "o", "fold_post", "gu", "silu", "down"};
+                    double acc[10] = {0};
+                    for (int l = 0; l < s.n_layers; ++l)
+                        for (int j = 0; j < 10; ++j) acc[j] += (double)(t[1 + 10 * l + j + 0] - t[10 * l + j]) * 0.01;
+                    fprintf(stderr, "persistent trace (us per layer):");
+                    for (int j = 0; j < 10; ++j) fprintf(stderr, " %s %.2f", names[j], acc[j] / s.n_layers);
+                    fprintf(stderr, " | total %.1f us\n", (double)(t[n_tr - 1] - t[0]) * 0.01);
+                    // the same steps split into: work issued | stores acknowledged | barrier passed (workgroup 0)
+                    double wk[10] = {0}, ak[10] = {0}, br[10] = {0};
+                    for (int l = 0; l < s.n_layers; ++l)
+                        for (int j = 0; j < 10; ++j) {
+                            const size_t b = 1 + 10 * l + j;
+                            wk[j] += (double)(t[n_tr + b] - t[b - 1]) * 0.01;
+                            ak[j] += (double)(t[2 * n_tr + b] - t[n_tr + b]) * 0.01;
+                            br[j] += (double)(t[b] - t[2 * n_tr + b]) * 0.01;
+                        }
+                    fprintf(stderr, "  stream wave 0 waited for activation tiles (us per layer): qkv %.2f o %.2f gu %.2f down %.2f\n",
+                            t[3 * n_tr] * 0.01 / s.n_layers, t[3 * n_tr + 1] * 0.01 / s.n_layers,
+                            t[3 * n_tr + 2] * 0.01 / s.n_layers, t[3 * n_tr + 3] * 0.01 / s.n_layers);
+                    {
+                        const long long *tx = t.data() + 3 * n_tr + 4;
+                        const int nt = (int)std::min<long long>(tx[0], 64);
+                        const long long t0 = t[10 * 5];   // barrier before layer 5
+                        fprintf(stderr, "  layer 5 tiles of stream wave 0 (kind: start x-ready done, us after the layer's start):");
+                        for (int i = 0; i < nt; ++i)
+                            fprintf(stderr, " [%d: %.2f %.2f %.2f]", (int)((unsigned long long)tx[3 + 3 * i] >> 60),
+                                    (tx[1 + 3 * i] - t0) * 0.01, (tx[2 + 3 * i] - t0) * 0.01,
+                                    ((tx[3 + 3 * i] & 0x0FFFFFFFFFFFFFFFll) - t0) * 0.01);
+                        fprintf(stderr, "\n  layer 5 barriers (us after the layer's start):");
+                        for (int j = 1; j <= 10; ++j) fprintf(stderr, " %.2f", (t[10 * 5 + j] - t0) * 0.01);
+                        fprintf(stderr, "\n");
+                    }
+                    fprintf(stderr, "  work/ack/barrier:");
+                    for (int j = 0; j < 10; ++j)
+                        fprintf(stderr, " %s %.1f/%.1f/%.1f", names[j], wk[j] / s.n_layers, ak[j] / s.n_layers, br[j] / s.n_layers);
+                    fprintf(stderr, "\n");
+                }
+            }
             if (le != hipSuccess) {
                 c->err = std::string("cooperative launch failed: ") + hipGetErrorString(le);
                 return KOALA_E_DEVICE;

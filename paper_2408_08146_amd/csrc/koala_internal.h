@@ -62,6 +62,7 @@ struct Params {
     unsigned long long bar_base;            // barrier generations used by earlier launches
     int *abort_flag;                        // device: set when a wait timed out
     int *abort_host;                        // pinned host memory: set by the kernel on abort
+    long long *trace;                       // optional [1 + 10 * L + 1] wall-clock ticks: start, after every barrier, end
 };
 
 enum { BARRIERS_PER_LAYER = 10 };
