@@ -1,14 +1,16 @@
 // All decoder layers of one verification pass in a single cooperative kernel (bf16 path, one sequence,
-// at most 32 rows).
+// at most 32 rows).  Opt-in (KOALA_PERSISTENT=1): on the 7B shape it runs as fast as the per-layer kernels,
+// not faster; the measurements that explain why are kept with the design notes.
 //
 // Why: with one kernel per step a layer costs ten dependent launches, and every weight-streaming GEMM starts
 // with an empty memory pipeline and ends with a drain.  Here one workgroup per CU stays resident for the whole
 // stack and its eight waves split into two roles:
 //   * waves 0-3 ("stream" waves) do nothing but load weight tiles (64 rows x 64 k, 8 KiB, fragment-major) into
-//     a ring of NS register slots and multiply them with activation tiles that wait in LDS.  Their loads run
-//     ahead across phase boundaries: while the small steps between two GEMMs execute, the next matrix is
-//     already on its way.  Loads of one wave return in order, so a wave with a deep weight queue cannot also
-//     do latency-critical loads; hence the second role;
+//     a ring of NS register slots and multiply them with activation tiles that wait in LDS.  Per projection
+//     they first fill all NS slots (as soon as the chain waves allow it: right after this workgroup arrived at
+//     the barrier that ends the previous projection, so that the tiles travel while the small step between the
+//     two projections runs), then compute and reload slot by slot.  Loads of one wave return in order, so a
+//     wave with a deep weight queue cannot also do latency-critical loads; hence the second role;
 //   * waves 4-7 ("chain" waves) run everything on the dependency chain: they copy activation tiles from
 //     global memory into the LDS ring, write the stream waves' partial sums out, execute the small steps
 //     (fold + RMSNorm gain, RoPE + KV append, tree attention, split merge, SwiGLU) and meet the other
@@ -39,6 +41,7 @@ typedef unsigned long long __attribute__((may_alias)) u64_lds;
 constexpr int NS = KOALA_PL_NS;       // weight tiles a stream wave keeps in registers / in flight (3..6)
 constexpr int XR = 8;                 // activation tiles in the LDS ring
 constexpr int AUX_SC1 = 16, AUX_NT = 2;
+constexpr int AUX_X = AUX_SC1;   // activation tiles: written by other workgroups inside the kernel
 constexpr int MAX_LAYERS = 96;        // layers the weight address table in LDS holds
 constexpr long long TIMEOUT_TICKS = 25000000LL;   // 0.25 s of the 100 MHz wall clock
 
@@ -105,7 +108,7 @@ struct __attribute__((aligned(16))) Ctl {
     int cbar;         // chain-wave barrier counter
     int gbar;         // grid barrier generation reached
     int abort_l;
-    int pad_;
+    int go;           // projections (counted from the first layer) whose first weight loads may be issued
 };
 
 __device__ __forceinline__ int sk_start(int w, int total, int geff) {
@@ -129,18 +132,18 @@ struct Shared {
     // weight addresses (low, high word) of phase g = 4 * layer + projection: the stream waves read them from
     // here, because a global load in their instruction stream would have to wait for the whole weight queue
     unsigned wtab[MAX_LAYERS * 4][2];
-    long long tl[64][3];   // diagnostic: per-tile timestamps of stream wave 0 in one layer
+    unsigned ltab[MAX_LAYERS * 4][2];   // per layer: input norm gain, post-attention norm gain, key cache, value cache
 };
-constexpr int TRACE_LAYER = 5;
 
 // ---------------------------------------------------------------------------------------------
 // helpers of the chain waves
 // ---------------------------------------------------------------------------------------------
 struct Chain {
-    kp::Params p;
+    const kp::Params &p;
     Ctl *ctl;
     int c, l, w, G;            // chain wave 0..3, lane, workgroup, grid size
     unsigned long long gen;    // grid barrier generation
+    unsigned long long shard_target;   // arrivals a shard counter shows when the current barrier is complete
     int cgen;                  // chain barrier generation
     bool dead;
 };
@@ -158,23 +161,31 @@ __device__ void chain_sync(Chain &k) {
     LDS_ACQUIRE();
 }
 
-// all global stores of this workgroup's chain waves are complete, then every workgroup has arrived
-__device__ void grid_barrier(Chain &k) {
+// Grid barrier.  `all`: every workgroup arrives; otherwise only the first p.nclean workgroups (those that run the
+// small steps) arrive and the others just wait for them.  Arriving means: all global stores of this workgroup's
+// chain waves are complete.  go_after > 0: once the arrival is on its way, the stream waves of this workgroup
+// may issue the first loads of projections < go_after.  Ordering matters here, because the memory pipeline of a
+// CU serves its requests in issue order: whatever is issued after a burst of weight loads waits for the burst.
+__device__ void grid_barrier(Chain &k, bool all, int go_after) {
     const bool tracer = k.p.trace && k.w == 0 && k.c == 0 && k.l == 0;
     const int ntr = 2 + 10 * k.p.L;
+    const bool arrives = all || k.w < k.p.nclean;
     if (tracer) k.p.trace[ntr + (k.gen + 1 - k.p.bar_base)] = wall_clock64();         // work of the step issued
+
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     if (tracer) k.p.trace[2 * ntr + (k.gen + 1 - k.p.bar_base)] = wall_clock64();     // stores acknowledged
     LDS_RELEASE();
     chain_sync(k);
     ++k.gen;
+    k.shard_target += (unsigned long long)((all ? k.G : k.p.nclean) / 8);
     if (k.c == 0) {
         if (k.l == 0) {
             unsigned long long *bar = k.p.bar;
-            const unsigned shard = k.w & 7, per = k.G / 8;
-            const unsigned long long old =
-                __hip_atomic_fetch_add(bar + shard * 16, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (old + 1 == k.gen * per)
+            const unsigned shard = k.w & 7;
+            unsigned long long old = 0;
+            if (arrives) old = __hip_atomic_fetch_add(bar + shard * 16, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (go_after > 0) LDS_ST(&k.ctl->go, go_after);
+            if (arrives && old + 1 == k.shard_target)
                 __hip_atomic_fetch_add(bar + 8 * 16, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const long long tb = wall_clock64();
             while (__hip_atomic_load(bar + 8 * 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < k.gen * 8) {
@@ -199,7 +210,7 @@ __device__ void grid_barrier(Chain &k) {
         }
     }
     LDS_ACQUIRE();
-    if (k.p.trace && k.w == 0 && k.c == 0 && k.l == 0) k.p.trace[k.gen - k.p.bar_base] = wall_clock64();
+    if (tracer) k.p.trace[k.gen - k.p.bar_base] = wall_clock64();
     if (LDS_LD(&k.ctl->abort_l)) {
         // tell the workgroups that still wait at a barrier
         if (k.l == 0) __hip_atomic_store(k.p.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -212,7 +223,8 @@ __device__ void grid_barrier(Chain &k) {
 // costs one memory round trip per batch instead of one per slot; the order of the additions is fixed.
 constexpr unsigned OOB = 0xFFFFFF00u;
 
-// NV consecutive float4 (col % 4 == 0) of row m summed over the slots of the columns' row group
+// NV consecutive float4 (col % 4 == 0) of row m summed over the slots of the columns' row group; 2 * NB slots
+// per round trip (two arrays, because one of twice the size is not kept in registers)
 template <int NV, int NB>
 __device__ __forceinline__ void psumv(rsrc_t rP, int Mp, const Kind &kd, int m, int col, f32x4 *out) {
     const int S = sk_slots(col >> 8, kd);
@@ -220,18 +232,28 @@ __device__ __forceinline__ void psumv(rsrc_t rP, int Mp, const Kind &kd, int m, 
     const unsigned base = ((unsigned)m * (unsigned)kd.Npad + (unsigned)col) * 4u;
 #pragma unroll
     for (int i = 0; i < NV; ++i) out[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    for (int s0 = 0; s0 < S; s0 += NB) {
-        f32x4 t[NB][NV];
+    for (int s0 = 0; s0 < S; s0 += 2 * NB) {
+        f32x4 ta[NB][NV], tb[NB][NV];
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
             const unsigned off = s0 + u < S ? base + (unsigned)(s0 + u) * stride : OOB;
 #pragma unroll
-            for (int i = 0; i < NV; ++i) t[u][i] = ldf4<AUX_SC1>(rP, off + 16u * i);
+            for (int i = 0; i < NV; ++i) ta[u][i] = ldf4<AUX_SC1>(rP, off + 16u * i);
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const unsigned off = s0 + NB + u < S ? base + (unsigned)(s0 + NB + u) * stride : OOB;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) tb[u][i] = ldf4<AUX_SC1>(rP, off + 16u * i);
         }
 #pragma unroll
         for (int u = 0; u < NB; ++u)
 #pragma unroll
-            for (int i = 0; i < NV; ++i) out[i] += t[u][i];
+            for (int i = 0; i < NV; ++i) out[i] += ta[u][i];
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
+#pragma unroll
+            for (int i = 0; i < NV; ++i) out[i] += tb[u][i];
     }
 }
 
@@ -315,7 +337,7 @@ __device__ void step_fold(Chain &k, int mode, const Kind &prev, const void *gain
     const rsrc_t rX = make_rsrc(p.Xf, p.xf_bytes), rS = make_rsrc(p.sums, p.sums_bytes);
     const rsrc_t rg = make_rsrc(gain, gain ? (unsigned)p.H * 2 : 0);
     const int nch = (p.H + 511) / 512;
-    for (int u = k.w * 4 + k.c; u < nch * p.rows; u += k.G * 4) {
+    for (int u = k.w * 4 + k.c; u < nch * p.rows && k.w < p.nclean; u += p.nclean * 4) {
         const int c = u % nch, m = u / nch, j = (c * 64 + k.l) * 8;
         float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if (j < p.H) {
@@ -359,7 +381,7 @@ __device__ void step_rope(Chain &k, const Kind &kq, rsrc_t rK, rsrc_t rV) {
     const rsrc_t rP = make_rsrc(p.part, p.part_bytes), rS = make_rsrc(p.sums, p.sums_bytes);
     const rsrc_t rq = make_rsrc(p.qrot, p.qrot_bytes);
     const int H = p.H, DH = 128, half = 64, i = k.l;
-    for (int u = k.w * 4 + k.c; u < p.rows * p.n_heads; u += k.G * 4) {
+    for (int u = k.w * 4 + k.c; u < p.rows * p.n_heads && k.w < p.nclean; u += p.nclean * 4) {
         const int r = u / p.n_heads, h = u % p.n_heads;
         const int b = p.meta.row_b[r], slot = p.meta.row_slot[r];
         const float cs = p.meta.rope_cos[(size_t)r * half + i], sn = p.meta.rope_sin[(size_t)r * half + i];
@@ -390,7 +412,7 @@ __device__ void step_combine(Chain &k) {
     const rsrc_t ro = make_rsrc(p.o_part, p.opart_bytes), rm = make_rsrc(p.ml, p.ml_bytes);
     const rsrc_t rX = make_rsrc(p.Xf, p.xf_bytes);
     const int nch = (p.H + 511) / 512, DH = 128, ns = p.nsplit;
-    for (int u = k.w * 4 + k.c; u < nch * p.rows; u += k.G * 4) {
+    for (int u = k.w * 4 + k.c; u < nch * p.rows && k.w < p.nclean; u += p.nclean * 4) {
         const int c = u % nch, r = u / nch, g = c * 64 + k.l;
         if (g >= p.H / 8) continue;
         const int h = (g * 8) / DH, d0 = (g * 8) % DH;
@@ -439,12 +461,12 @@ __device__ void step_silu(Chain &k, const Kind &kgu) {
     const rsrc_t rP = make_rsrc(p.part, p.part_bytes), rS = make_rsrc(p.sums, p.sums_bytes);
     const rsrc_t rX = make_rsrc(p.Xf, p.xf_bytes);
     const int nch = (p.F / 8 + 63) / 64;
-    for (int u = k.w * 4 + k.c; u < nch * p.rows; u += k.G * 4) {
+    for (int u = k.w * 4 + k.c; u < nch * p.rows && k.w < p.nclean; u += p.nclean * 4) {
         const int c = u % nch, r = u / nch, g = c * 64 + k.l;
         if (g >= p.F / 8) continue;
         const RowScale rsc(rS, (p.H + 511) / 512, p.srows, r);
         f32x4 gv[4];
-        psumv<4, 4>(rP, MT * 16, kgu, r, g * 16, gv);
+        psumv<4, 2>(rP, MT * 16, kgu, r, g * 16, gv);
         float gu[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) gu[e] = gv[e >> 2][e & 3];
@@ -718,6 +740,9 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
             (unsigned long long)(kx == G_QKV ? ly.wqkv : kx == G_O ? ly.wo : kx == G_GU ? ly.wgu : ly.wdown);
         sh.wtab[i][0] = (unsigned)a;
         sh.wtab[i][1] = (unsigned)(a >> 32);
+        const unsigned long long b = (unsigned long long)(kx == 0 ? ly.in_norm : kx == 1 ? ly.post_norm : kx == 2 ? ly.kc : ly.vc);
+        sh.ltab[i][0] = (unsigned)b;
+        sh.ltab[i][1] = (unsigned)(b >> 32);
     }
     __syncthreads();
     if (threadIdx.x < 4) {
@@ -740,80 +765,28 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
     if (wave < 4) {
         // ============================================================== stream wave
         u32x4 wr[NS][8];
-        // load cursor over (phase, tile); phase g = 4 * layer + projection
-        int lg = -1, li = 0, ln = 0, l_rg = 0, l_k = 0, l_KT = 1, l_nrb = 0;
-        unsigned l_bytes = 0;
-        rsrc_t l_rs = make_rsrc(p.layers, 0);
-#define L_NEXT_PHASE()                                                                                   \
-        for (;;) {                                                                                       \
-            ++lg;                                                                                        \
-            if (lg >= ng) { ln = 0; break; }                                                             \
-            const int kx = lg & 3;                                                                       \
-            const int n_ = LDS_LD(&ctl->kind[kx].n);                                                     \
-            if (n_ > 0) {                                                                                \
-                const int t0_ = LDS_LD(&ctl->kind[kx].t0);                                               \
-                ln = n_; li = 0; l_KT = LDS_LD(&ctl->kind[kx].KT); l_nrb = LDS_LD(&ctl->kind[kx].nrb);   \
-                l_rg = t0_ / l_KT; l_k = t0_ % l_KT;                                                     \
-                const unsigned a_lo = (unsigned)LDS_LD((int *)&sh.wtab[lg][0]);                          \
-                const unsigned a_hi = (unsigned)LDS_LD((int *)&sh.wtab[lg][1]);                          \
-                const void *wp = (const void *)(((unsigned long long)a_hi << 32) | (unsigned long long)a_lo); \
-                l_bytes = (unsigned)l_nrb * 64u * (unsigned)l_KT * 64u * 2u;                             \
-                l_rs = make_rsrc(wp, l_bytes);                                                           \
-                break;                                                                                   \
-            }                                                                                            \
-        }
-        L_NEXT_PHASE()
-        // always 8 loads per slot so that the waits the compiler derives are static; where there is no tile the
-        // offset lies past the end of the buffer: such a load touches no memory and returns zeros
-#define ISSUE(S)                                                                                         \
-        {                                                                                                \
-            const int rb = l_rg * 4 + wave;                                                              \
-            const bool ok = lg < ng && rb < l_nrb;                                                       \
-            const unsigned off = ok ? (unsigned)(((size_t)rb * l_KT + l_k) * 8192u) + (unsigned)l * 16u  \
-                                    : 0xFFFFFF00u;                                                       \
-            _Pragma("unroll") for (int j = 0; j < 8; ++j) wr[S][j] = ld128<AUX_NT>(l_rs, off + (ok ? j * 1024u : 0u)); \
-            if (lg < ng) {                                                                               \
-                ++li; ++l_k;                                                                             \
-                if (l_k == l_KT) { l_k = 0; ++l_rg; }                                                    \
-                if (li == ln) { L_NEXT_PHASE() }                                                         \
-            }                                                                                            \
-        }
-        ISSUE(0)
-        ISSUE(1)
-        ISSUE(2)
-#if KOALA_PL_NS > 3
-        ISSUE(3)
-#endif
-#if KOALA_PL_NS > 4
-        ISSUE(4)
-#endif
-#if KOALA_PL_NS > 5
-        ISSUE(5)
-#endif
         int seq = 0, nflush = 0, dead = 0;
-        long long xw0 = 0, xw1 = 0, xw2 = 0, xw3 = 0;   // ticks spent waiting for activation tiles, per projection
-        int tli = 0;
         f32x4 acc[4][MT];
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int m = 0; m < MT; ++m) acc[t][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        // compute cursor
-        int cg = -1, ci = 0, cn = 0, c_rg = 0, c_k = 0, c_KT = 1, c_nrb = 0;
-#define C_NEXT_PHASE()                                                                                   \
-        for (;;) {                                                                                       \
-            ++cg;                                                                                        \
-            if (cg >= ng) { cn = 0; break; }                                                             \
-            const int kx = cg & 3;                                                                       \
-            const int n_ = LDS_LD(&ctl->kind[kx].n);                                                     \
-            if (n_ > 0) {                                                                                \
-                const int t0_ = LDS_LD(&ctl->kind[kx].t0);                                               \
-                cn = n_; ci = 0; c_KT = LDS_LD(&ctl->kind[kx].KT); c_nrb = LDS_LD(&ctl->kind[kx].nrb);   \
-                c_rg = t0_ / c_KT; c_k = t0_ % c_KT;                                                     \
-                break;                                                                                   \
+        // tile cursors of the current projection: loads run NS tiles ahead of the products
+        int n = 0, KT = 1, nrb = 0, li = 0, l_rg = 0, l_k = 0, ci = 0, c_rg = 0, c_k = 0;
+        rsrc_t rs = make_rsrc(p.layers, 0);
+        // always 8 loads per slot so that the waits the compiler derives are static; where there is no tile the
+        // offset lies past the end of the buffer: such a load touches no memory and returns zeros
+#define ISSUE(S)                                                                                         \
+        {                                                                                                \
+            const int rb = l_rg * 4 + wave;                                                              \
+            const bool ok = li < n && rb < nrb;                                                          \
+            const unsigned off = ok ? (unsigned)(((size_t)rb * KT + l_k) * 8192u) + (unsigned)l * 16u : OOB; \
+            _Pragma("unroll") for (int j = 0; j < 8; ++j) wr[S][j] = ld128<AUX_NT>(rs, off + (ok ? j * 1024u : 0u)); \
+            if (li < n) {                                                                                \
+                ++li; ++l_k;                                                                             \
+                if (l_k == KT) { l_k = 0; ++l_rg; }                                                      \
             }                                                                                            \
         }
-        C_NEXT_PHASE()
 #define FLUSH()                                                                                          \
         {                                                                                                \
             const long long tb = wall_clock64();                                                         \
@@ -833,25 +806,17 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
             if (l == 0) LDS_ST(&ctl->p_ready[wave], nflush);                                             \
         }
 #define STEP(S)                                                                                          \
-        if (cg < ng && !dead) {                                                                          \
+        if (ci < n && !dead) {                                                                           \
             const int xs = seq % XR;                                                                     \
             const long long tb = wall_clock64();                                                         \
-            const bool ttile = p.trace && w == 0 && wave == 0 && l == 0 && (cg >> 2) == TRACE_LAYER && tli < 64; \
-            if (ttile) sh.tl[tli][0] = tb;                                                               \
             while (LDS_LD(&ctl->xflag[xs]) != seq + 1) {                                                 \
                 __builtin_amdgcn_s_sleep(1);                                                             \
                 if (LDS_LD(&ctl->abort_l) || wall_clock64() - tb > TIMEOUT_TICKS) { dead = 1; LDS_ST(&ctl->abort_l, 1); break; } \
             }                                                                                            \
             LDS_ACQUIRE();                                                                               \
-            {                                                                                            \
-                const long long dtx = wall_clock64() - tb;                                               \
-                const int kx = cg & 3;                                                                   \
-                xw0 += kx == 0 ? dtx : 0; xw1 += kx == 1 ? dtx : 0; xw2 += kx == 2 ? dtx : 0; xw3 += kx == 3 ? dtx : 0; \
-            }                                                                                            \
-            if (ttile) sh.tl[tli][1] = wall_clock64();                                                   \
             if (!dead) {                                                                                 \
                 const u32x4 *xt = xring + xs * XT;                                                       \
-                if (c_rg * 4 + wave < c_nrb) {                                                           \
+                if (c_rg * 4 + wave < nrb) {                                                             \
                     _Pragma("unroll") for (int s = 0; s < 2; ++s) {                                      \
                         bf16x8 xh[MT], xl[MT];                                                           \
                         _Pragma("unroll") for (int m = 0; m < MT; ++m) {                                 \
@@ -869,40 +834,72 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
                 ++seq;                                                                                   \
                 LDS_RELEASE();                                                                           \
                 if (l == 0) LDS_ST(&ctl->done[wave], seq);                                               \
-                if (ttile) { sh.tl[tli][2] = wall_clock64() | ((long long)(cg & 3) << 60); ++tli; }       \
                 ++ci; ++c_k;                                                                             \
-                if (c_k == c_KT || ci == cn) { FLUSH() c_k = 0; ++c_rg; }                                \
-                if (ci == cn) { C_NEXT_PHASE() }                                                         \
+                if (c_k == KT || ci == n) { FLUSH() c_k = 0; ++c_rg; }                                   \
             }                                                                                            \
         }                                                                                                \
         ISSUE(S)
-        while (cg < ng && !dead) {
-            STEP(0)
-            STEP(1)
-            STEP(2)
+        for (int g = 0; g < ng && !dead; ++g) {
+            const int kx = g & 3;
+            n = LDS_LD(&ctl->kind[kx].n);
+            if (n == 0) continue;
+            const int t0 = LDS_LD(&ctl->kind[kx].t0);
+            KT = LDS_LD(&ctl->kind[kx].KT);
+            nrb = LDS_LD(&ctl->kind[kx].nrb);
+            li = 0; ci = 0;
+            l_rg = c_rg = t0 / KT;
+            l_k = c_k = t0 % KT;
+            {
+                const unsigned a_lo = (unsigned)LDS_LD((int *)&sh.wtab[g][0]);
+                const unsigned a_hi = (unsigned)LDS_LD((int *)&sh.wtab[g][1]);
+                const void *wp = (const void *)(((unsigned long long)a_hi << 32) | (unsigned long long)a_lo);
+                rs = make_rsrc(wp, (unsigned)nrb * 64u * (unsigned)KT * 64u * 2u);
+            }
+            // the chain waves say when this projection's first loads may enter the CU's memory pipeline
+            {
+                const long long tb = wall_clock64();
+                while (LDS_LD(&ctl->go) <= g) {
+                    __builtin_amdgcn_s_sleep(1);
+                    if (LDS_LD(&ctl->abort_l) || wall_clock64() - tb > TIMEOUT_TICKS) { dead = 1; LDS_ST(&ctl->abort_l, 1); break; }
+                }
+            }
+            if (dead) break;
+            ISSUE(0)
+            ISSUE(1)
+            ISSUE(2)
 #if KOALA_PL_NS > 3
-            STEP(3)
+            ISSUE(3)
 #endif
 #if KOALA_PL_NS > 4
-            STEP(4)
+            ISSUE(4)
 #endif
 #if KOALA_PL_NS > 5
-            STEP(5)
+            ISSUE(5)
 #endif
-        }
-        if (p.trace && w == 0 && wave == 0 && l == 0) {
-            long long *tx = p.trace + 3 * (2 + 10 * p.L);
-            tx[0] = xw0; tx[1] = xw1; tx[2] = xw2; tx[3] = xw3;
-            tx[4] = tli;
-            for (int i = 0; i < tli; ++i) { tx[5 + 3 * i] = sh.tl[i][0]; tx[6 + 3 * i] = sh.tl[i][1]; tx[7 + 3 * i] = sh.tl[i][2]; }
+            while (ci < n && !dead) {
+                STEP(0)
+                STEP(1)
+                STEP(2)
+#if KOALA_PL_NS > 3
+                STEP(3)
+#endif
+#if KOALA_PL_NS > 4
+                STEP(4)
+#endif
+#if KOALA_PL_NS > 5
+                STEP(5)
+#endif
+            }
         }
     } else {
         // ============================================================== chain wave
-        Chain k;
-        k.p = p; k.ctl = ctl; k.c = wave - 4; k.l = l; k.w = w; k.G = G;
-        k.gen = p.bar_base; k.cgen = 0; k.dead = false;
+        Chain k{p};
+        k.ctl = ctl; k.c = wave - 4; k.l = l; k.w = w; k.G = G;
+        k.gen = p.bar_base; k.shard_target = p.shard_base; k.cgen = 0; k.dead = false;
+        // workgroups that take no part in the small steps may fetch the first projection's weights at once
+        if (k.c == 0 && l == 0 && w >= p.pf_from) LDS_ST(&ctl->go, 1);
         const int c = k.c;
-        int seq_base = 0, ndrained = 0;
+        int seq_base = 0;
         const rsrc_t rX = make_rsrc(p.Xf, p.xf_bytes), rP = make_rsrc(p.part, p.part_bytes);
         Kind kd[4];
 #pragma unroll
@@ -913,13 +910,16 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
             kd[g].n = LDS_LD(&ctl->kind[g].n); kd[g].pad_ = 0;
         }
         // one GEMM phase: feed this workgroup's activation tiles to the ring, write its partial sums out
-        auto gemm_phase = [&](const Kind &d) {
+        // one GEMM phase: every chain wave feeds every fourth activation tile of this workgroup to the ring (requested
+        // before its ring slot is free) and writes out the partial sums of the stream wave with its number
+        int ndrained = 0;
+        auto gemm_phase = [&](const Kind &d, int g) {
             const int t0 = d.t0, n = d.n;
+            if (c == 0 && l == 0 && w < p.pf_from) LDS_ST(&ctl->go, g + 1);
             if (n > 0) {
                 const int rg0 = t0 / d.KT, rg1 = (t0 + n - 1) / d.KT;
                 int feed = c, drg = rg0;
                 long long tb = wall_clock64();
-                // the next activation tile of this wave is requested before its ring slot is free
                 u32x4 v[MT * 4];
                 bool loaded = false;
                 while ((feed < n || drg <= rg1) && !k.dead) {
@@ -928,7 +928,7 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
                         const int kt = (t0 + feed) % d.KT;
 #pragma unroll
                         for (int u = 0; u < MT * 4; ++u)
-                            v[u] = ld128<AUX_SC1>(rX, (unsigned)(((size_t)kt * XT + u * 64 + l) * 16));
+                            v[u] = ld128<AUX_X>(rX, (unsigned)(((size_t)kt * XT + u * 64 + l) * 16));
                         loaded = true;
                     }
                     if (feed < n) {
@@ -981,33 +981,41 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
                 }
                 seq_base += n;
             }
-            grid_barrier(k);
+            // the arrival goes first, then the next projection's first weight tiles (they overlap the small step
+            // that follows)
+            grid_barrier(k, true, (w >= p.pf_from && g + 1 < 4 * p.L) ? g + 2 : 0);
         };
         if (p.trace && w == 0 && c == 0 && l == 0) p.trace[0] = wall_clock64();
         for (int ly = 0; ly < p.L && !k.dead; ++ly) {
-            const kp::Layer &L = p.layers[ly];
-            const rsrc_t rK = make_rsrc(L.kc, p.kv_layer_bytes), rV = make_rsrc(L.vc, p.kv_layer_bytes);
-            step_fold<MT>(k, ly == 0 ? 0 : 1, kd[G_DOWN], L.in_norm, true);
-            grid_barrier(k);
-            gemm_phase(kd[G_QKV]);
+            const void *lp[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned a_lo = (unsigned)LDS_LD((int *)&sh.ltab[4 * ly + i][0]);
+                const unsigned a_hi = (unsigned)LDS_LD((int *)&sh.ltab[4 * ly + i][1]);
+                lp[i] = (const void *)(((unsigned long long)a_hi << 32) | (unsigned long long)a_lo);
+            }
+            const rsrc_t rK = make_rsrc(lp[2], p.kv_layer_bytes), rV = make_rsrc(lp[3], p.kv_layer_bytes);
+            step_fold<MT>(k, ly == 0 ? 0 : 1, kd[G_DOWN], lp[0], true);
+            grid_barrier(k, false, 0);
+            gemm_phase(kd[G_QKV], 4 * ly + G_QKV);
             if (k.dead) break;
             step_rope<MT>(k, kd[G_QKV], rK, rV);
-            grid_barrier(k);
+            grid_barrier(k, false, 0);
             if (k.dead) break;
             for (int u = w; u < p.nsplit * p.n_heads; u += G) attn_unit<MT>(k, sh.area, u % p.nsplit, u / p.nsplit, rK, rV);
-            grid_barrier(k);
+            grid_barrier(k, true, 0);
             if (k.dead) break;
             step_combine<MT>(k);
-            grid_barrier(k);
-            gemm_phase(kd[G_O]);
+            grid_barrier(k, false, 0);
+            gemm_phase(kd[G_O], 4 * ly + G_O);
             if (k.dead) break;
-            step_fold<MT>(k, 1, kd[G_O], L.post_norm, true);
-            grid_barrier(k);
-            gemm_phase(kd[G_GU]);
+            step_fold<MT>(k, 1, kd[G_O], lp[1], true);
+            grid_barrier(k, false, 0);
+            gemm_phase(kd[G_GU], 4 * ly + G_GU);
             if (k.dead) break;
             step_silu<MT>(k, kd[G_GU]);
-            grid_barrier(k);
-            gemm_phase(kd[G_DOWN]);
+            grid_barrier(k, false, 0);
+            gemm_phase(kd[G_DOWN], 4 * ly + G_DOWN);
         }
         if (!k.dead) step_fold<MT>(k, 1, kd[G_DOWN], nullptr, false);   // the last down projection into x
         __builtin_amdgcn_s_waitcnt(0x0F70);

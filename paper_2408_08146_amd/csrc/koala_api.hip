@@ -387,6 +387,7 @@ koala_status koala_bind(koala_ctx *c, const koala_weights *w, const koala_kv *kv
         if (e == hipSuccess) e = hipMemset(c->pl_bar, 0, 9 * 16 * sizeof(unsigned long long));
         if (e == hipSuccess) e = hipMemset(c->pl_abort, 0, 4 * sizeof(int));
         c->pl_gen = 0;
+        c->pl_shard = 0;
         if (e == hipSuccess && !c->pl_abort_host) e = hipHostMalloc((void **)&c->pl_abort_host, 64, hipHostMallocDefault);
         if (e == hipSuccess) *c->pl_abort_host = 0;
         int dev = 0;
@@ -431,6 +432,7 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
                 (void)hipMemsetAsync(c->pl_bar, 0, 9 * 16 * sizeof(unsigned long long), st);
                 (void)hipMemsetAsync(c->pl_abort, 0, 4 * sizeof(int), st);
                 c->pl_gen = 0;
+                c->pl_shard = 0;
                 return fail(c, KOALA_E_DEVICE, "an earlier persistent verification pass timed out; its outputs are invalid");
             }
             kp::Params q{};
@@ -447,7 +449,17 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
             q.ml = c->ml; q.ml_bytes = (unsigned)((size_t)c->max_rows * s.n_heads * ns * 2 * 4);
             q.kv_layer_bytes = (unsigned)ls;
             q.meta = c->meta;
-            q.bar = c->pl_bar; q.bar_base = c->pl_gen;
+            q.bar = c->pl_bar; q.bar_base = c->pl_gen; q.shard_base = c->pl_shard;
+            {
+                // tuning knobs (measured best: every workgroup runs the small steps and every workgroup fetches the
+                // next projection's first tiles right after it arrived at the barrier that ends a projection)
+                int nc = c->n_cu;
+                if (const char *e = getenv("KOALA_PL_NCLEAN")) nc = atoi(e);
+                nc = std::max(8, std::min(c->n_cu, nc / 8 * 8));
+                q.nclean = nc;
+                q.pf_from = 0;
+                if (const char *e = getenv("KOALA_PL_PFFROM")) q.pf_from = std::max(0, atoi(e));
+            }
             q.abort_flag = c->pl_abort; q.abort_host = c->pl_abort_host;
             if (ls > 0xFFFFFF00ull || c->part_bytes > 0xFFFFFF00ull)
                 return fail(c, KOALA_E_UNSUPPORTED, "buffers too large for the persistent verification kernel");
@@ -456,15 +468,15 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
             const char *tr = getenv("KOALA_PERSISTENT_TRACE");
             const size_t n_tr = 2 + (size_t)kp::BARRIERS_PER_LAYER * s.n_layers;
             if (tr && atoi(tr) != 0) {
-                if (!trace_dev && hipMalloc((void **)&trace_dev, (3 * (2 + kp::BARRIERS_PER_LAYER * 1024) + 4 + 1 + 3 * 64) * sizeof(long long)) != hipSuccess)
+                if (!trace_dev && hipMalloc((void **)&trace_dev, 3 * (2 + kp::BARRIERS_PER_LAYER * 1024) * sizeof(long long)) != hipSuccess)
                     trace_dev = nullptr;
                 if (s.n_layers <= 1024) q.trace = trace_dev;
             }
             const hipError_t le = kp::launch(st, q, MT, c->n_cu);
             if (q.trace && le == hipSuccess) {
-                std::vector<long long> t(3 * n_tr + 4 + 1 + 3 * 64);
+                std::vector<long long> t(3 * n_tr);
                 if (hipStreamSynchronize(st) == hipSuccess &&
-                    hipMemcpy(t.data(), trace_dev, (3 * n_tr + 4 + 1 + 3 * 64) * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess) {
+                    hipMemcpy(t.data(), trace_dev, 3 * n_tr * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess) {
                     static const char *names[10] = {"fold_in", "qkv", "rope", "attn", "combine", "o", "fold_post", "gu", "silu", "down"};
                     double acc[10] = {0};
                     for (int l = 0; l < s.n_layers; ++l)
@@ -481,22 +493,6 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
                             ak[j] += (double)(t[2 * n_tr + b] - t[n_tr + b]) * 0.01;
                             br[j] += (double)(t[b] - t[2 * n_tr + b]) * 0.01;
                         }
-                    fprintf(stderr, "  stream wave 0 waited for activation tiles (us per layer): qkv %.2f o %.2f gu %.2f down %.2f\n",
-                            t[3 * n_tr] * 0.01 / s.n_layers, t[3 * n_tr + 1] * 0.01 / s.n_layers,
-                            t[3 * n_tr + 2] * 0.01 / s.n_layers, t[3 * n_tr + 3] * 0.01 / s.n_layers);
-                    {
-                        const long long *tx = t.data() + 3 * n_tr + 4;
-                        const int nt = (int)std::min<long long>(tx[0], 64);
-                        const long long t0 = t[10 * 5];   // barrier before layer 5
-                        fprintf(stderr, "  layer 5 tiles of stream wave 0 (kind: start x-ready done, us after the layer's start):");
-                        for (int i = 0; i < nt; ++i)
-                            fprintf(stderr, " [%d: %.2f %.2f %.2f]", (int)((unsigned long long)tx[3 + 3 * i] >> 60),
-                                    (tx[1 + 3 * i] - t0) * 0.01, (tx[2 + 3 * i] - t0) * 0.01,
-                                    ((tx[3 + 3 * i] & 0x0FFFFFFFFFFFFFFFll) - t0) * 0.01);
-                        fprintf(stderr, "\n  layer 5 barriers (us after the layer's start):");
-                        for (int j = 1; j <= 10; ++j) fprintf(stderr, " %.2f", (t[10 * 5 + j] - t0) * 0.01);
-                        fprintf(stderr, "\n");
-                    }
                     fprintf(stderr, "  work/ack/barrier:");
                     for (int j = 0; j < 10; ++j)
                         fprintf(stderr, " %s %.1f/%.1f/%.1f", names[j], wk[j] / s.n_layers, ak[j] / s.n_layers, br[j] / s.n_layers);
@@ -508,6 +504,8 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
                 return KOALA_E_DEVICE;
             }
             c->pl_gen += (unsigned long long)kp::BARRIERS_PER_LAYER * s.n_layers;
+            // per layer, five barriers where all workgroups arrive and five where only the first nclean do
+            c->pl_shard += (unsigned long long)s.n_layers * 5ull * (unsigned long long)(c->n_cu / 8 + q.nclean / 8);
         } else {
             for (int l = 0; l < s.n_layers; ++l)
                 decoder_layer_bf16(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,

@@ -60,6 +60,9 @@ struct Params {
     RowMeta meta;
     unsigned long long *bar;                // grid barrier counters (9 x 128 B), monotonic across launches
     unsigned long long bar_base;            // barrier generations used by earlier launches
+    unsigned long long shard_base;          // arrivals per shard counter in earlier launches
+    int nclean;                             // workgroups that run the small steps (multiple of 8)
+    int pf_from;                            // workgroups >= pf_from fetch the next projection's first tiles early
     int *abort_flag;                        // device: set when a wait timed out
     int *abort_host;                        // pinned host memory: set by the kernel on abort
     long long *trace;                       // optional [1 + 10 * L + 1] wall-clock ticks: start, after every barrier, end
@@ -106,6 +109,7 @@ struct koala_ctx {
     int *pl_abort;                 // device abort flag
     int *pl_abort_host;            // pinned host abort flag
     unsigned long long pl_gen;     // barrier generations consumed so far
+    unsigned long long pl_shard;   // arrivals per shard counter so far
     int n_cu;                      // compute units of the device the context is bound on
     float *med_logits;                                   // [D * max_batch][V] per-depth logits of Medusa-style heads (sampled drafting)
     float *acc_q, *acc_d;                                // [max_batch][V] distributions of the stochastic acceptance walk
