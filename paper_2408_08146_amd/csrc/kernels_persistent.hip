@@ -133,6 +133,9 @@ struct Shared {
     // here, because a global load in their instruction stream would have to wait for the whole weight queue
     unsigned wtab[MAX_LAYERS * 4][2];
     unsigned ltab[MAX_LAYERS * 4][2];   // per layer: input norm gain, post-attention norm gain, key cache, value cache
+#ifdef KOALA_PL_TW
+    long long tl[64][4];
+#endif
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -805,15 +808,26 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
             ++nflush;                                                                                    \
             if (l == 0) LDS_ST(&ctl->p_ready[wave], nflush);                                             \
         }
+#ifdef KOALA_PL_TW
+#define TT(I) if (ttile) sh.tl[tli][I] = wall_clock64();
+#define TT_DECL const bool ttile = p.trace && w == KOALA_PL_TW && wave == 0 && l == 0 && (gcur >> 2) == 5 && tli < 64;
+#define TT_NEXT if (ttile) ++tli;
+#else
+#define TT(I)
+#define TT_DECL
+#define TT_NEXT
+#endif
 #define STEP(S)                                                                                          \
         if (ci < n && !dead) {                                                                           \
             const int xs = seq % XR;                                                                     \
             const long long tb = wall_clock64();                                                         \
+            TT_DECL TT(0)                                                                                \
             while (LDS_LD(&ctl->xflag[xs]) != seq + 1) {                                                 \
                 __builtin_amdgcn_s_sleep(1);                                                             \
                 if (LDS_LD(&ctl->abort_l) || wall_clock64() - tb > TIMEOUT_TICKS) { dead = 1; LDS_ST(&ctl->abort_l, 1); break; } \
             }                                                                                            \
             LDS_ACQUIRE();                                                                               \
+            TT(1)                                                                                        \
             if (!dead) {                                                                                 \
                 const u32x4 *xt = xring + xs * XT;                                                       \
                 if (c_rg * 4 + wave < nrb) {                                                             \
@@ -835,12 +849,20 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
                 LDS_RELEASE();                                                                           \
                 if (l == 0) LDS_ST(&ctl->done[wave], seq);                                               \
                 ++ci; ++c_k;                                                                             \
+                TT(2)                                                                                    \
                 if (c_k == KT || ci == n) { FLUSH() c_k = 0; ++c_rg; }                                   \
+                TT(3) TT_NEXT                                                                            \
             }                                                                                            \
         }                                                                                                \
         ISSUE(S)
+#ifdef KOALA_PL_TW
+        int tli = 0, gcur = 0;
+#endif
         for (int g = 0; g < ng && !dead; ++g) {
             const int kx = g & 3;
+#ifdef KOALA_PL_TW
+            gcur = g;
+#endif
             n = LDS_LD(&ctl->kind[kx].n);
             if (n == 0) continue;
             const int t0 = LDS_LD(&ctl->kind[kx].t0);
@@ -891,6 +913,14 @@ __global__ __launch_bounds__(512) void k_layers_persistent(kp::Params p) {
 #endif
             }
         }
+#ifdef KOALA_PL_TW
+        if (p.trace && w == KOALA_PL_TW && wave == 0 && l == 0) {
+            long long *tx = p.trace + 3 * (2 + 10 * p.L);
+            tx[0] = tli;
+            for (int i = 0; i < tli; ++i)
+                for (int j = 0; j < 4; ++j) tx[1 + 4 * i + j] = sh.tl[i][j];
+        }
+#endif
     } else {
         // ============================================================== chain wave
         Chain k{p};

@@ -468,15 +468,15 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
             const char *tr = getenv("KOALA_PERSISTENT_TRACE");
             const size_t n_tr = 2 + (size_t)kp::BARRIERS_PER_LAYER * s.n_layers;
             if (tr && atoi(tr) != 0) {
-                if (!trace_dev && hipMalloc((void **)&trace_dev, 3 * (2 + kp::BARRIERS_PER_LAYER * 1024) * sizeof(long long)) != hipSuccess)
+                if (!trace_dev && hipMalloc((void **)&trace_dev, (3 * (2 + kp::BARRIERS_PER_LAYER * 1024) + 1 + 256) * sizeof(long long)) != hipSuccess)
                     trace_dev = nullptr;
                 if (s.n_layers <= 1024) q.trace = trace_dev;
             }
             const hipError_t le = kp::launch(st, q, MT, c->n_cu);
             if (q.trace && le == hipSuccess) {
-                std::vector<long long> t(3 * n_tr);
+                std::vector<long long> t(3 * n_tr + 1 + 256);
                 if (hipStreamSynchronize(st) == hipSuccess &&
-                    hipMemcpy(t.data(), trace_dev, 3 * n_tr * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess) {
+                    hipMemcpy(t.data(), trace_dev, (3 * n_tr + 1 + 256) * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess) {
                     static const char *names[10] = {"fold_in", "qkv", "rope", "attn", "combine", "o", "fold_post", "gu", "silu", "down"};
                     double acc[10] = {0};
                     for (int l = 0; l < s.n_layers; ++l)
@@ -493,6 +493,20 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
                             ak[j] += (double)(t[2 * n_tr + b] - t[n_tr + b]) * 0.01;
                             br[j] += (double)(t[b] - t[2 * n_tr + b]) * 0.01;
                         }
+#ifdef KOALA_PL_TW
+                    {
+                        const long long *tx = t.data() + 3 * n_tr;
+                        const int nt = (int)std::min<long long>(tx[0], 64);
+                        const long long t0 = t[10 * 5];
+                        fprintf(stderr, "  layer 5 tiles of stream wave 0 of workgroup %d (start x-ready done flushed, us after the layer began):\n   ", KOALA_PL_TW);
+                        for (int i = 0; i < nt; ++i)
+                            fprintf(stderr, " [%.2f %.2f %.2f %.2f]", (tx[1 + 4 * i] - t0) * 0.01, (tx[2 + 4 * i] - t0) * 0.01,
+                                    (tx[3 + 4 * i] - t0) * 0.01, (tx[4 + 4 * i] - t0) * 0.01);
+                        fprintf(stderr, "\n   barriers of layer 5:");
+                        for (int j = 1; j <= 10; ++j) fprintf(stderr, " %.2f", (t[10 * 5 + j] - t0) * 0.01);
+                        fprintf(stderr, "\n");
+                    }
+#endif
                     fprintf(stderr, "  work/ack/barrier:");
                     for (int j = 0; j < 10; ++j)
                         fprintf(stderr, " %s %.1f/%.1f/%.1f", names[j], wk[j] / s.n_layers, ak[j] / s.n_layers, br[j] / s.n_layers);
