@@ -173,7 +173,12 @@ koala_status koala_draft_expand(koala_ctx *ctx, void *hip_stream, int batch,
  *   feat_out    device fp32 [batch, n_nodes, hidden] (out): features after the final RMSNorm;
  *   logits_out  device fp32 [batch, n_nodes, vocab] (out, may be NULL);
  *   greedy_out  device int32 [batch, n_nodes] (out): argmax of each row's logits,
- *               lowest id among equal maxima. */
+ *               lowest id among equal maxima.
+ * Environment: KOALA_PERSISTENT=1 runs the decoder layers of a bf16 context with one sequence of at
+ * most 32 rows and head_dim 128 in a single cooperative kernel instead of one kernel per step (same
+ * results up to the order of the partial sums; not used while the stream is being captured).  If a
+ * wait inside that kernel times out, the outputs of that call are invalid and the next
+ * koala_tree_verify returns KOALA_E_DEVICE once, after which the context is usable again. */
 koala_status koala_tree_verify(koala_ctx *ctx, void *hip_stream, int batch,
                                const int32_t *tree_tokens, float *feat_out, float *logits_out,
                                int32_t *greedy_out);

@@ -424,8 +424,11 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
     if (bf) {
         const int MT = kb::mt_of(rows), Mp = MT * 16;
         c->pend_S = 0;
-        if (persistent_enabled() && kp::supported(rows, batch, s.head_dim, s.n_layers) && c->n_cu >= 8 && c->n_cu % 8 == 0 &&
-            c->n_cu <= 256) {
+        // a cooperative launch cannot be captured into a graph: a capturing stream takes the per-layer kernels
+        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &capture) != hipSuccess) capture = hipStreamCaptureStatusActive;
+        if (persistent_enabled() && capture == hipStreamCaptureStatusNone &&
+            kp::supported(rows, batch, s.head_dim, s.n_layers) && c->n_cu >= 8 && c->n_cu % 8 == 0 && c->n_cu <= 256) {
             if (*c->pl_abort_host != 0) {
                 // an earlier pass timed out inside the kernel: its results were wrong; start from clean counters
                 *c->pl_abort_host = 0;

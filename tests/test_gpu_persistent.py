@@ -100,3 +100,38 @@ def test_persistent_full_width_matches_layer_kernels(monkeypatch):
     for a, b in zip(kv_pers, kv_base):
         a, b = np.asarray(a, np.float32), np.asarray(b, np.float32)
         assert np.abs(a - b).max() <= 2.0 ** -6 * max(1.0, float(np.abs(b).max()))
+
+
+def test_persistent_switch_is_ignored_under_stream_capture(monkeypatch):
+    """A cooperative launch cannot be recorded into a graph: with the switch on, a capturing stream must
+    take the per-layer kernels, and the replayed graph must give what they give (bit for bit)."""
+    import torch
+    case = Case("cfg2_small")
+    case.fill_kv_normal()
+    case.upload_kv()
+    B, T, H, dev = case.B, case.T, case.H, case.device
+    tt = case.t(case.random_tree_tokens().astype(np.int32))
+    feat = torch.zeros(B, T, H, dtype=torch.float32, device=dev)
+    greedy = torch.zeros(B, T, dtype=torch.int32, device=dev)
+    monkeypatch.setenv("KOALA_PERSISTENT", "0")
+    case.gpu.tree_verify(B, tt, feat, None, greedy)
+    torch.cuda.synchronize()
+    want_feat, want_greedy = feat.clone(), greedy.clone()
+    monkeypatch.setenv("KOALA_PERSISTENT", "1")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        case.gpu.tree_verify(B, tt, feat, None, greedy)      # eager, cooperative kernel
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        case.gpu.tree_verify(B, tt, feat, None, greedy)      # captured: per-layer kernels
+    monkeypatch.setenv("KOALA_PERSISTENT", "0")
+    for _ in range(2):
+        feat.fill_(-1)
+        greedy.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(feat, want_feat) and torch.equal(greedy, want_greedy)
