@@ -56,9 +56,10 @@ __global__ void k_embed(const int32_t *tok, const WT *E, float *x, int H) {
 
 template <typename WT>
 __global__ void k_fc_input(const int32_t *tok, const WT *E, const float *feat, float *act, int H) {
+    // grid (rows, chunks of the hidden dimension): few rows, so the columns supply the parallelism
     const int r = blockIdx.x;
     const size_t t = (size_t)tok[r];
-    for (int j = threadIdx.x; j < H; j += blockDim.x) {
+    for (int j = blockIdx.y * blockDim.x + threadIdx.x; j < H; j += gridDim.y * blockDim.x) {
         act[(size_t)r * 2 * H + j] = ldf(E, t * H + j);
         act[(size_t)r * 2 * H + H + j] = feat[(size_t)r * H + j];
     }
@@ -72,7 +73,7 @@ __global__ void k_level_inputs(const int32_t *tree_tokens, const WT *E, const fl
     const int b = r / n_level, u = level_nodes[r % n_level];
     const size_t t = (size_t)tree_tokens[b * T + u];
     const float *f = fhat + ((size_t)b * T + parent[u]) * H;
-    for (int j = threadIdx.x; j < H; j += blockDim.x) {
+    for (int j = blockIdx.y * blockDim.x + threadIdx.x; j < H; j += gridDim.y * blockDim.x) {
         act[(size_t)r * 2 * H + j] = ldf(E, t * H + j);
         act[(size_t)r * 2 * H + H + j] = f[j];
     }
@@ -484,19 +485,21 @@ void embed_rows(hipStream_t s, bool bf16, const int32_t *tok, const void *E, flo
 
 void fc_input(hipStream_t s, bool bf16, const int32_t *tok, const void *E, const float *feat, float *act,
               int rows, int H) {
-    if (bf16) k_fc_input<bf16_t><<<rows, 256, 0, s>>>(tok, (const bf16_t *)E, feat, act, H);
-    else k_fc_input<float><<<rows, 256, 0, s>>>(tok, (const float *)E, feat, act, H);
+    const dim3 grid(rows, std::max(1, std::min(16, H / 256)));
+    if (bf16) k_fc_input<bf16_t><<<grid, 256, 0, s>>>(tok, (const bf16_t *)E, feat, act, H);
+    else k_fc_input<float><<<grid, 256, 0, s>>>(tok, (const float *)E, feat, act, H);
 }
 
 void level_inputs(hipStream_t s, bool bf16, const int32_t *tree_tokens, const void *E, const float *fhat,
                   const int32_t *level_nodes, const int32_t *parent, float *act, int batch, int n_level,
                   int T, int H) {
+    const dim3 grid(batch * n_level, std::max(1, std::min(16, H / 256)));
     if (bf16)
-        k_level_inputs<bf16_t><<<batch * n_level, 256, 0, s>>>(tree_tokens, (const bf16_t *)E, fhat, level_nodes,
-                                                                parent, act, n_level, T, H);
+        k_level_inputs<bf16_t><<<grid, 256, 0, s>>>(tree_tokens, (const bf16_t *)E, fhat, level_nodes, parent, act,
+                                                    n_level, T, H);
     else
-        k_level_inputs<float><<<batch * n_level, 256, 0, s>>>(tree_tokens, (const float *)E, fhat, level_nodes,
-                                                               parent, act, n_level, T, H);
+        k_level_inputs<float><<<grid, 256, 0, s>>>(tree_tokens, (const float *)E, fhat, level_nodes, parent, act,
+                                                   n_level, T, H);
 }
 
 void rmsnorm(hipStream_t s, bool bf16, const float *x, const void *g, float *out, int rows, int H, float eps) {
