@@ -65,7 +65,9 @@ struct Params {
     int pf_from;                            // workgroups >= pf_from fetch the next projection's first tiles early
     int *abort_flag;                        // device: set when a wait timed out
     int *abort_host;                        // pinned host memory: set by the kernel on abort
-    long long *trace;                       // optional [1 + 10 * L + 1] wall-clock ticks: start, after every barrier, end
+    long long *trace;                       // optional diagnostics, n = 2 + 10 * L wall-clock ticks per block:
+                                            // [0, n) start, every barrier passed, end; [n, 2n) step's work issued;
+                                            // [2n, 3n) its stores acknowledged; then 1 + 256 words of per-tile stamps
 };
 
 enum { BARRIERS_PER_LAYER = 10 };
