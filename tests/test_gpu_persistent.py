@@ -135,3 +135,19 @@ def test_persistent_switch_is_ignored_under_stream_capture(monkeypatch):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(feat, want_feat) and torch.equal(greedy, want_greedy)
+
+
+@pytest.mark.parametrize("cfgname", ["cfg3_small", "cfg5_small"])
+def test_persistent_switch_leaves_unsupported_shapes_alone(cfgname, monkeypatch):
+    """More than 32 rows (64-node tree) or more than one sequence: the switch must not change anything,
+    the per-layer kernels run and give the same bits."""
+    case = Case(cfgname)
+    assert case.T > 32 or case.B > 1
+    case.fill_kv_normal()
+    tt = case.random_tree_tokens()
+    (bfeat, blogits, bgreedy), kv_base, (feat, logits, greedy), kv_pers = _verify_both(case, tt, monkeypatch)
+    np.testing.assert_array_equal(logits, blogits)
+    np.testing.assert_array_equal(greedy, bgreedy)
+    np.testing.assert_array_equal(feat, bfeat)
+    for a, b in zip(kv_pers, kv_base):
+        np.testing.assert_array_equal(a, b)
