@@ -34,24 +34,30 @@ __device__ __forceinline__ uint32_t f2bf(float v) {  // round to nearest even
 // P:  [S][MTT*16][Npad] fp32 partial sums; split sp covers 128-k chunks [sp*nch/S, (sp+1)*nch/S).
 // Workgroup = 4 waves; wave w owns row block wb*4 + w (64 rows); the X chunk is shared in LDS.
 // ---------------------------------------------------------------------------------------------
-template <int MT>
-__global__ __launch_bounds__(256, MT == 4 ? 2 : 3) void k_gemm_packed(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
-                                                     float *__restrict__ P, int Npad, int K, int S, int nwb,
-                                                     int MTT, int mt0) {
+template <int MT, int RS>
+__global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm_packed(
+    const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf, float *__restrict__ P, int Npad, int K, int S, int nwb,
+    int MTT, int mt0) {
+    // RS waves share each 64-row weight block and split the activation tiles between them (wave w of 4 * RS:
+    // row block w % 4, tiles (w / 4) * MT ..): one pass over the weights then serves MT * RS tiles.  The waves
+    // that share a block load the same fragments at about the same time, so HBM sees them once.
     extern __shared__ u32x4 xs[];            // [2][XCH]
-    constexpr int XCH = 4 * MT * 2 * 64;     // 16-byte units of X per 128-k chunk
-    constexpr int XPT = XCH / 256;           // per thread
+    constexpr int MTW = MT * RS;             // activation tiles of the workgroup
+    constexpr int NT = 256 * RS;
+    constexpr int XCH = 4 * MTW * 2 * 64;    // 16-byte units of X per 128-k chunk
+    constexpr int XPT = XCH / NT;            // per thread
     const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
+    const int wv = wave & 3, rs = wave >> 2;
     const int wb = blockIdx.x % nwb, sp = blockIdx.x / nwb;
     const int nch = K / 128;
     const int c_begin = (int)((long long)sp * nch / S), c_end = (int)((long long)(sp + 1) * nch / S);
     const int nchunks = c_end - c_begin;
-    const int rb = wb * 4 + wave;
+    const int rb = wb * 4 + wv;
     const bool active = rb < Npad / 64;
     const u32x4 *wsrc = Wp + ((size_t)(active ? rb : 0) * (K / 64) + (size_t)c_begin * 2) * 512 + l;
-    // 16-byte unit u of chunk c lives at xsrc + (c*4 + u / (MT*128)) * MTT*128 + u % (MT*128)
+    // 16-byte unit u of chunk c lives at xsrc + (c*4 + u / (MTW*128)) * MTT*128 + u % (MTW*128)
     const u32x4 *xsrc = Xf + (size_t)c_begin * 4 * MTT * 128 + (size_t)mt0 * 128;
-    auto xaddr = [&](int c, int u) { return xsrc + ((size_t)c * 4 + u / (MT * 128)) * (MTT * 128) + u % (MT * 128); };
+    auto xaddr = [&](int c, int u) { return xsrc + ((size_t)c * 4 + u / (MTW * 128)) * (MTT * 128) + u % (MTW * 128); };
     f32x4 acc[4][MT];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
@@ -62,25 +68,26 @@ __global__ __launch_bounds__(256, MT == 4 ? 2 : 3) void k_gemm_packed(const u32x
     const int nb = nchunks * 2;
     auto wload = [&](int b, int slot) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) wr[slot][j] = __builtin_nontemporal_load(wsrc + (size_t)b * 512 + j * 64);
+        for (int j = 0; j < 8; ++j)   // RS > 1: cacheable, so that the second wave of a row block finds the tile in L2
+            wr[slot][j] = RS > 1 ? wsrc[(size_t)b * 512 + j * 64] : __builtin_nontemporal_load(wsrc + (size_t)b * 512 + j * 64);
     };
     if (nchunks > 0) {
         // X loads first, weight loads right behind them: the wait for X then leaves the weight loads in flight
 #pragma unroll
-        for (int i = 0; i < XPT; ++i) xr[i] = *xaddr(0, threadIdx.x + 256 * i);
+        for (int i = 0; i < XPT; ++i) xr[i] = *xaddr(0, threadIdx.x + NT * i);
         if (active) {
             wload(0, 0);
             wload(1, 1);
         }
 #pragma unroll
-        for (int i = 0; i < XPT; ++i) xs[threadIdx.x + 256 * i] = xr[i];
+        for (int i = 0; i < XPT; ++i) xs[threadIdx.x + NT * i] = xr[i];
     }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
         const bool more = c + 1 < nchunks;
         if (more) {
 #pragma unroll
-            for (int i = 0; i < XPT; ++i) xr[i] = *xaddr(c + 1, threadIdx.x + 256 * i);
+            for (int i = 0; i < XPT; ++i) xr[i] = *xaddr(c + 1, threadIdx.x + NT * i);
         }
         const u32x4 *xc = xs + (c & 1) * XCH;
         if (active) {
@@ -91,7 +98,7 @@ __global__ __launch_bounds__(256, MT == 4 ? 2 : 3) void k_gemm_packed(const u32x
                 for (int j = 0; j < 8; ++j) a[j] = __builtin_bit_cast(bf16x8, wr[bb][j]);
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
-                    const u32x4 *xk = xc + (bb * 2 + s) * (MT * 2 * 64);
+                    const u32x4 *xk = xc + (bb * 2 + s) * (MTW * 2 * 64) + rs * (MT * 2 * 64);
                     bf16x8 xh[MT], xl[MT];
 #pragma unroll
                     for (int m = 0; m < MT; ++m) {
@@ -117,7 +124,7 @@ __global__ __launch_bounds__(256, MT == 4 ? 2 : 3) void k_gemm_packed(const u32x
         if (more) {
             u32x4 *xn = xs + ((c + 1) & 1) * XCH;
 #pragma unroll
-            for (int i = 0; i < XPT; ++i) xn[threadIdx.x + 256 * i] = xr[i];
+            for (int i = 0; i < XPT; ++i) xn[threadIdx.x + NT * i] = xr[i];
         }
         __syncthreads();
     }
@@ -126,7 +133,7 @@ __global__ __launch_bounds__(256, MT == 4 ? 2 : 3) void k_gemm_packed(const u32x
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
-                const int row = (mt0 + m) * 16 + li, n = rb * 64 + 16 * t + 4 * lg;
+                const int row = (mt0 + rs * MT + m) * 16 + li, n = rb * 64 + 16 * t + 4 * lg;
                 *(f32x4 *)(P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = acc[t][m];
             }
     }
@@ -484,20 +491,34 @@ inline int cdiv(size_t a, size_t b) { return (int)((a + b - 1) / b); }
 // =====================================================================================================
 namespace kb {
 
-int gemm_splits(int Npad, int K) {
+int gemm_splits(int Npad, int K, int MTT) {
     const int nwb = (Npad / 64 + 3) / 4, nch = K / 128;
+    int smax = 16;
+    if (const char *e = getenv("KOALA_GEMM_SMAX")) smax = atoi(e) > 0 && atoi(e) <= 16 ? atoi(e) : smax;
+    smax = smax > nch ? nch : smax;
+    if (MTT >= 8 && !(getenv("KOALA_GEMM_WIDE") && atoi(getenv("KOALA_GEMM_WIDE")) == 0)) {
+        // passes of eight tiles: one 512-thread workgroup per CU is resident, so the grid runs in rounds of 256
+        // (a chip of another size would want its CU count here); take the smallest split whose last round is
+        // at least 90 % full, else the fullest
+        int best = 1;
+        double best_eff = 0.0;
+        for (int S = 1; S <= smax; ++S) {
+            const int wgs = nwb * S, rounds = (wgs + 255) / 256;
+            const double eff = (double)wgs / (rounds * 256.0);
+            if (eff >= 0.9) return S;
+            if (eff > best_eff) { best_eff = eff; best = S; }
+        }
+        return best;
+    }
     int target = 384;
     if (const char *e = getenv("KOALA_GEMM_WGS")) target = atoi(e) > 0 ? atoi(e) : target;
     int S = (target + nwb / 2) / nwb;
-    int smax = 16;
-    if (const char *e = getenv("KOALA_GEMM_SMAX")) smax = atoi(e) > 0 && atoi(e) <= 16 ? atoi(e) : smax;
     S = S < 1 ? 1 : S;
     S = S > smax ? smax : S;
-    S = S > nch ? nch : S;
     return S;
 }
 
-static bool g_attr_done[3] = {false, false, false};
+static bool g_attr_done[4] = {false, false, false, false};
 
 static RowScale mk_scale(const NormScale &n) { return RowScale{n.sums, n.nparts, n.srows, n.K, n.eps}; }
 
@@ -505,28 +526,33 @@ void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int N
                  hipEvent_t ev_start, hipEvent_t ev_stop) {
     const int nwb = (Npad / 64 + 3) / 4;
     const dim3 grid(nwb * S);
-#define KOALA_GEMM(MTV, IDX)                                                                                     \
+#define KOALA_GEMM(MTV, RSV, IDX)                                                                                \
     {                                                                                                            \
-        const size_t sm = (size_t)2 * 4 * MTV * 2 * 64 * 16;                                                     \
+        const size_t sm = (size_t)2 * 4 * MTV * RSV * 2 * 64 * 16;                                               \
         if (!g_attr_done[IDX]) {                                                                                 \
-            (void)hipFuncSetAttribute((const void *)k_gemm_packed<MTV>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                      (int)sm);                                                                  \
+            (void)hipFuncSetAttribute((const void *)k_gemm_packed<MTV, RSV>,                                     \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);                      \
             g_attr_done[IDX] = true;                                                                             \
         }                                                                                                        \
         if (ev_start || ev_stop) /* events bound to the dispatch itself: they read the kernel's own begin and end */ \
-            hipExtLaunchKernelGGL(k_gemm_packed<MTV>, grid, dim3(256), sm, st, mt0 == 0 ? ev_start : nullptr,    \
-                                  mt0 + 4 >= MTT ? ev_stop : nullptr, 0, (const u32x4 *)Wp, (const u32x4 *)Xf, P, \
-                                  Npad, K, S, nwb, MTT, mt0);                                                    \
+            hipExtLaunchKernelGGL((k_gemm_packed<MTV, RSV>), grid, dim3(256 * RSV), sm, st,                      \
+                                  mt0 == 0 ? ev_start : nullptr, mt0 + g >= MTT ? ev_stop : nullptr, 0,          \
+                                  (const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, S, nwb, MTT, mt0);           \
         else                                                                                                     \
-            k_gemm_packed<MTV><<<grid, 256, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, S, nwb,  \
-                                                      MTT, mt0);                                                 \
+            k_gemm_packed<MTV, RSV><<<grid, 256 * RSV, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, \
+                                                                 S, nwb, MTT, mt0);                              \
     }
-    // MTT is 1, 2 or a multiple of 4: groups of at most four activation tiles per launch
-    for (int mt0 = 0; mt0 < MTT; mt0 += 4) {
-        const int g = MTT - mt0 >= 4 ? 4 : MTT - mt0;
-        if (g == 1) KOALA_GEMM(1, 0)
-        else if (g == 2) KOALA_GEMM(2, 1)
-        else KOALA_GEMM(4, 2)
+    // MTT is 1, 2 or a multiple of 4: up to eight activation tiles per pass over the weights (eight: two waves
+    // per weight row block, four tiles each)
+    static const bool wide = !(getenv("KOALA_GEMM_WIDE") && atoi(getenv("KOALA_GEMM_WIDE")) == 0);
+    for (int mt0 = 0; mt0 < MTT;) {
+        const int left = MTT - mt0;
+        const int g = left >= 8 && wide ? 8 : left >= 4 ? 4 : left;
+        if (g == 1) KOALA_GEMM(1, 1, 0)
+        else if (g == 2) KOALA_GEMM(2, 1, 1)
+        else if (g == 4) KOALA_GEMM(4, 1, 2)
+        else KOALA_GEMM(4, 2, 3)
+        mt0 += g;
     }
 #undef KOALA_GEMM
 }

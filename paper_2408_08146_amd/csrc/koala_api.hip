@@ -101,7 +101,8 @@ size_t carve(koala_ctx *c, char *base) {
         const int shapes[6][2] = {{3 * H, H}, {H, H}, {2 * F, H}, {H, F}, {kb::pad64(V), H}, {H, 2 * H}};
         size_t worst = 0;
         for (auto &sh : shapes)
-            worst = std::max(worst, (size_t)kb::gemm_splits(kb::pad64(sh[0]), sh[1]) * kb::pad64(sh[0]));
+            worst = std::max(worst, (size_t)std::max(kb::gemm_splits(kb::pad64(sh[0]), sh[1]),
+                                                     kb::gemm_splits(kb::pad64(sh[0]), sh[1], MTmax)) * kb::pad64(sh[0]));
         // the persistent verification cuts its GEMMs stream-K over the CUs (sized for 256 of them)
         worst = std::max(worst, kp::part_floats_per_row(H, F, 256));
         c->part_bytes = worst * MTmax * 16 * sizeof(float);
@@ -144,7 +145,7 @@ void decoder_layer(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, co
 
 // Split-K GEMM on the fragments in c->xf: partial sums of X * W^T into c->part; returns the split count.
 int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) {
-    const int Npad = kb::pad64(N), S = kb::gemm_splits(Npad, K);
+    const int Npad = kb::pad64(N), S = kb::gemm_splits(Npad, K, MT);
     const bool timed = c->prof_on && (size_t)(c->prof_used + 2) <= c->prof_ev.size();
     kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S, timed ? c->prof_ev[c->prof_used] : nullptr,
                     timed ? c->prof_ev[c->prof_used + 1] : nullptr);

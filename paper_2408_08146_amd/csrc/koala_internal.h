@@ -236,7 +236,7 @@ struct NormScale {
     float eps;
 };
 
-int gemm_splits(int Npad, int K);
+int gemm_splits(int Npad, int K, int MTT = 0);   // MTT: activation tiles of the call (0: at most four)
 // P[S][MTT*16][Npad] = partial sums of X * W^T, X given as hi/lo fragments [K/32][MTT][2][64] x 16 B
 // ev_start/ev_stop (either may be null) are attached to the dispatch: they take the kernel's own begin and end times
 void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S,
