@@ -499,10 +499,11 @@ int gemm_splits(int Npad, int K, int MTT) {
     if (MTT >= 8 && !(getenv("KOALA_GEMM_WIDE") && atoi(getenv("KOALA_GEMM_WIDE")) == 0)) {
         // passes of eight tiles: one 512-thread workgroup per CU is resident, so the grid runs in rounds of 256
         // (a chip of another size would want its CU count here); take the smallest split whose last round is
-        // at least 90 % full, else the fullest
+        // at least 90 % full, else the fullest; at most 8 splits (more splits mean more
+        // partial-sum traffic, which at hundreds of rows costs more than a part-empty round: measured)
         int best = 1;
         double best_eff = 0.0;
-        for (int S = 1; S <= smax; ++S) {
+        for (int S = 1; S <= std::min(smax, 8); ++S) {
             const int wgs = nwb * S, rounds = (wgs + 255) / 256;
             const double eff = (double)wgs / (rounds * 256.0);
             if (eff >= 0.9) return S;
