@@ -491,12 +491,22 @@ inline int cdiv(size_t a, size_t b) { return (int)((a + b - 1) / b); }
 // =====================================================================================================
 namespace kb {
 
+// tuning knobs from the environment, read once
+static int env_int(const char *name, int fallback) {
+    const char *e = getenv(name);
+    return e && atoi(e) > 0 ? atoi(e) : fallback;
+}
+static bool wide_passes() {
+    static const bool on = !(getenv("KOALA_GEMM_WIDE") && atoi(getenv("KOALA_GEMM_WIDE")) == 0);
+    return on;
+}
+
 int gemm_splits(int Npad, int K, int MTT) {
+    static const int target = env_int("KOALA_GEMM_WGS", 384);
+    static const int smax_env = std::min(16, env_int("KOALA_GEMM_SMAX", 16));
     const int nwb = (Npad / 64 + 3) / 4, nch = K / 128;
-    int smax = 16;
-    if (const char *e = getenv("KOALA_GEMM_SMAX")) smax = atoi(e) > 0 && atoi(e) <= 16 ? atoi(e) : smax;
-    smax = smax > nch ? nch : smax;
-    if (MTT >= 8 && !(getenv("KOALA_GEMM_WIDE") && atoi(getenv("KOALA_GEMM_WIDE")) == 0)) {
+    const int smax = std::min(smax_env, nch);
+    if (MTT >= 8 && wide_passes()) {
         // passes of eight tiles: one 512-thread workgroup per CU is resident, so the grid runs in rounds of 256
         // (a chip of another size would want its CU count here); take the smallest split whose last round is
         // at least 90 % full, else the fullest; at most 8 splits (more splits mean more
@@ -511,8 +521,6 @@ int gemm_splits(int Npad, int K, int MTT) {
         }
         return best;
     }
-    int target = 384;
-    if (const char *e = getenv("KOALA_GEMM_WGS")) target = atoi(e) > 0 ? atoi(e) : target;
     int S = (target + nwb / 2) / nwb;
     S = S < 1 ? 1 : S;
     S = S > smax ? smax : S;
@@ -545,7 +553,7 @@ void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int N
     }
     // MTT is 1, 2 or a multiple of 4: up to eight activation tiles per pass over the weights (eight: two waves
     // per weight row block, four tiles each)
-    static const bool wide = !(getenv("KOALA_GEMM_WIDE") && atoi(getenv("KOALA_GEMM_WIDE")) == 0);
+    const bool wide = wide_passes();
     for (int mt0 = 0; mt0 < MTT;) {
         const int left = MTT - mt0;
         const int g = left >= 8 && wide ? 8 : left >= 4 ? 4 : left;
