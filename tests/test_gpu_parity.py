@@ -258,3 +258,20 @@ def test_bf16_draft_expand_matches_oracle(cfgname, K):
     assert n_skip <= max(1, n_cmp // 10), f"{n_skip} of {n_cmp} drafted tokens skipped by the margin rule"
     for b in range(case.B):
         assert len(set(tokens[b, 1:1 + case.tree.topk_per_depth[0]])) == case.tree.topk_per_depth[0]
+
+
+# --------------------------------------------------------------------------- bf16, many rows
+@pytest.mark.parametrize("batch", [2, 4, 5])
+def test_bf16_batched_verify_many_rows_matches_oracle(batch):
+    """Batches whose row count needs the GEMM's passes of eight activation tiles: 2 x 60 rows = 8 tiles (one
+    pass of eight), 4 x 60 = 16 tiles (two passes of eight), 5 x 60 = 20 tiles (two of eight and one of four).
+    Ragged contexts; every logit of every row is compared."""
+    case = Case("cfg5_small", batch=batch, n_layers=2)
+    case.fill_kv_normal()
+    case.upload_kv()
+    tt = case.random_tree_tokens()
+    feat, logits, greedy = case.gpu_verify(tt)
+    rfeat, rlogits, rgreedy = case.oracle_verify(tt)
+    skipped, err = compare_logits_and_greedy(case, logits, greedy, rlogits, rgreedy)
+    assert skipped <= max(1, case.B * case.T // 10)
+    assert rel_err_rows(feat, rfeat).max() < case.tol
