@@ -162,6 +162,58 @@ bool persistent_enabled() {
     return v && atoi(v) != 0;
 }
 
+// KOALA_PERSISTENT_TRACE=1 (diagnostic): the single-kernel verification stamps the wall clock at every step as
+// workgroup 0 sees it; the times are printed to stderr after every call (which then waits for the stream).
+constexpr size_t kTraceMaxLayers = 1024;
+size_t persistent_trace_words(size_t layers) { return 3 * (2 + (size_t)kp::BARRIERS_PER_LAYER * layers) + 1 + 256; }
+
+long long *persistent_trace_buffer(int n_layers) {
+    static long long *dev = nullptr;   // one buffer per process, kept until it ends
+    const char *tr = getenv("KOALA_PERSISTENT_TRACE");
+    if (!tr || atoi(tr) == 0 || (size_t)n_layers > kTraceMaxLayers) return nullptr;
+    if (!dev && hipMalloc((void **)&dev, persistent_trace_words(kTraceMaxLayers) * sizeof(long long)) != hipSuccess) dev = nullptr;
+    return dev;
+}
+
+void persistent_trace_print(hipStream_t st, const long long *dev, int n_layers) {
+    const size_t n_tr = 2 + (size_t)kp::BARRIERS_PER_LAYER * n_layers;
+    std::vector<long long> t(persistent_trace_words(n_layers));
+    if (hipStreamSynchronize(st) != hipSuccess ||
+        hipMemcpy(t.data(), dev, t.size() * sizeof(long long), hipMemcpyDeviceToHost) != hipSuccess)
+        return;
+    static const char *names[10] = {"fold_in", "qkv", "rope", "attn", "combine", "o", "fold_post", "gu", "silu", "down"};
+    // per step: whole duration, and its split into work issued | stores acknowledged | barrier passed
+    double acc[10] = {0}, wk[10] = {0}, ak[10] = {0}, br[10] = {0};
+    for (int l = 0; l < n_layers; ++l)
+        for (int j = 0; j < 10; ++j) {
+            const size_t b = 1 + 10 * l + j;
+            acc[j] += (double)(t[b] - t[b - 1]) * 0.01;
+            wk[j] += (double)(t[n_tr + b] - t[b - 1]) * 0.01;
+            ak[j] += (double)(t[2 * n_tr + b] - t[n_tr + b]) * 0.01;
+            br[j] += (double)(t[b] - t[2 * n_tr + b]) * 0.01;
+        }
+    fprintf(stderr, "persistent trace (us per layer):");
+    for (int j = 0; j < 10; ++j) fprintf(stderr, " %s %.2f", names[j], acc[j] / n_layers);
+    fprintf(stderr, " | total %.1f us\n", (double)(t[n_tr - 1] - t[0]) * 0.01);
+#ifdef KOALA_PL_TW
+    if (n_layers > 5) {
+        const long long *tx = t.data() + 3 * n_tr;
+        const int nt = (int)std::min<long long>(tx[0], 64);
+        const long long t0 = t[10 * 5];
+        fprintf(stderr, "  layer 5 tiles of stream wave 0 of workgroup %d (start x-ready done flushed, us after the layer began):\n   ", KOALA_PL_TW);
+        for (int i = 0; i < nt; ++i)
+            fprintf(stderr, " [%.2f %.2f %.2f %.2f]", (tx[1 + 4 * i] - t0) * 0.01, (tx[2 + 4 * i] - t0) * 0.01,
+                    (tx[3 + 4 * i] - t0) * 0.01, (tx[4 + 4 * i] - t0) * 0.01);
+        fprintf(stderr, "\n   barriers of layer 5:");
+        for (int j = 1; j <= 10; ++j) fprintf(stderr, " %.2f", (t[10 * 5 + j] - t0) * 0.01);
+        fprintf(stderr, "\n");
+    }
+#endif
+    fprintf(stderr, "  work/ack/barrier:");
+    for (int j = 0; j < 10; ++j) fprintf(stderr, " %s %.1f/%.1f/%.1f", names[j], wk[j] / n_layers, ak[j] / n_layers, br[j] / n_layers);
+    fprintf(stderr, "\n");
+}
+
 kb::NormScale no_scale() { return kb::NormScale{nullptr, 0, 0, 1, 0.f}; }
 
 // row scale of an RMSNorm over the hidden dimension whose chunk sums are in c->row_sums
@@ -467,56 +519,9 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
             q.abort_flag = c->pl_abort; q.abort_host = c->pl_abort_host;
             if (ls > 0xFFFFFF00ull || c->part_bytes > 0xFFFFFF00ull)
                 return fail(c, KOALA_E_UNSUPPORTED, "buffers too large for the persistent verification kernel");
-            // KOALA_PERSISTENT_TRACE=1 (diagnostic): time of every step as workgroup 0 sees it, printed per call
-            static long long *trace_dev = nullptr;
-            const char *tr = getenv("KOALA_PERSISTENT_TRACE");
-            const size_t n_tr = 2 + (size_t)kp::BARRIERS_PER_LAYER * s.n_layers;
-            if (tr && atoi(tr) != 0) {
-                if (!trace_dev && hipMalloc((void **)&trace_dev, (3 * (2 + kp::BARRIERS_PER_LAYER * 1024) + 1 + 256) * sizeof(long long)) != hipSuccess)
-                    trace_dev = nullptr;
-                if (s.n_layers <= 1024) q.trace = trace_dev;
-            }
+            q.trace = persistent_trace_buffer(s.n_layers);
             const hipError_t le = kp::launch(st, q, MT, c->n_cu);
-            if (q.trace && le == hipSuccess) {
-                std::vector<long long> t(3 * n_tr + 1 + 256);
-                if (hipStreamSynchronize(st) == hipSuccess &&
-                    hipMemcpy(t.data(), trace_dev, (3 * n_tr + 1 + 256) * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess) {
-                    static const char *names[10] = {"fold_in", "qkv", "rope", "attn", "combine", "o", "fold_post", "gu", "silu", "down"};
-                    double acc[10] = {0};
-                    for (int l = 0; l < s.n_layers; ++l)
-                        for (int j = 0; j < 10; ++j) acc[j] += (double)(t[1 + 10 * l + j + 0] - t[10 * l + j]) * 0.01;
-                    fprintf(stderr, "persistent trace (us per layer):");
-                    for (int j = 0; j < 10; ++j) fprintf(stderr, " %s %.2f", names[j], acc[j] / s.n_layers);
-                    fprintf(stderr, " | total %.1f us\n", (double)(t[n_tr - 1] - t[0]) * 0.01);
-                    // the same steps split into: work issued | stores acknowledged | barrier passed (workgroup 0)
-                    double wk[10] = {0}, ak[10] = {0}, br[10] = {0};
-                    for (int l = 0; l < s.n_layers; ++l)
-                        for (int j = 0; j < 10; ++j) {
-                            const size_t b = 1 + 10 * l + j;
-                            wk[j] += (double)(t[n_tr + b] - t[b - 1]) * 0.01;
-                            ak[j] += (double)(t[2 * n_tr + b] - t[n_tr + b]) * 0.01;
-                            br[j] += (double)(t[b] - t[2 * n_tr + b]) * 0.01;
-                        }
-#ifdef KOALA_PL_TW
-                    {
-                        const long long *tx = t.data() + 3 * n_tr;
-                        const int nt = (int)std::min<long long>(tx[0], 64);
-                        const long long t0 = t[10 * 5];
-                        fprintf(stderr, "  layer 5 tiles of stream wave 0 of workgroup %d (start x-ready done flushed, us after the layer began):\n   ", KOALA_PL_TW);
-                        for (int i = 0; i < nt; ++i)
-                            fprintf(stderr, " [%.2f %.2f %.2f %.2f]", (tx[1 + 4 * i] - t0) * 0.01, (tx[2 + 4 * i] - t0) * 0.01,
-                                    (tx[3 + 4 * i] - t0) * 0.01, (tx[4 + 4 * i] - t0) * 0.01);
-                        fprintf(stderr, "\n   barriers of layer 5:");
-                        for (int j = 1; j <= 10; ++j) fprintf(stderr, " %.2f", (t[10 * 5 + j] - t0) * 0.01);
-                        fprintf(stderr, "\n");
-                    }
-#endif
-                    fprintf(stderr, "  work/ack/barrier:");
-                    for (int j = 0; j < 10; ++j)
-                        fprintf(stderr, " %s %.1f/%.1f/%.1f", names[j], wk[j] / s.n_layers, ak[j] / s.n_layers, br[j] / s.n_layers);
-                    fprintf(stderr, "\n");
-                }
-            }
+            if (q.trace && le == hipSuccess) persistent_trace_print(st, q.trace, s.n_layers);
             if (le != hipSuccess) {
                 c->err = std::string("cooperative launch failed: ") + hipGetErrorString(le);
                 return KOALA_E_DEVICE;
