@@ -53,7 +53,10 @@ class Case:
             self.Wt = target_weights(cfg, SEED_WEIGHTS, norm_gain=norm_gain, cache=True)
             self.Wd = (eagle_weights if self.eagle else medusa_weights)(
                 cfg, SEED_WEIGHTS, **({"norm_gain": norm_gain} if self.eagle else {}), cache=True)
-        if isinstance(cfg["ctx"], tuple):
+        if isinstance(cfg["ctx"], list):          # explicit length per sequence
+            assert len(cfg["ctx"]) == self.B
+            self.ctx_lens = [int(v) for v in cfg["ctx"]]
+        elif isinstance(cfg["ctx"], tuple):
             lo, hi = cfg["ctx"]
             self.ctx_lens = [int(v) for v in tensor_uniform_int(SEED_LENGTHS, "ctx_lens", (self.B,), lo, hi + 1)]
         else:

@@ -1,7 +1,10 @@
-"""Parity at the benchmark's full width (7B shape: hidden 4096, 32 heads x 128, ffn 11008, vocab 32000,
-26-node tree, 1024-token context) - the launch configuration bench.py times - with the layer count reduced
-so that the fp64 oracle and the CPU weight generator finish in about a minute.  Every logit of every tree
-row is compared.  Set KOALA_FULL_DEPTH=1 to run all 32 layers (several minutes)."""
+"""Parity at the benchmarked full widths - the launch configurations bench.py times - with the layer count
+reduced to two so that the fp64 oracle and the CPU weight generator finish in a minute or two per shape:
+  7B shape, EAGLE-style head, 26-node tree, 1024-token context (KOALA_FULL_DEPTH=1 runs all 32 layers);
+  7B shape, Medusa-style heads, 64-node tree, 2048-token context;
+  13B shape, 60-node tree, 4096-token context;
+  33B shape, two sequences of 60 nodes with ragged contexts of 8100 and 777 tokens.
+Every logit of every tree row is compared with the oracle."""
 import os
 
 import numpy as np
@@ -53,3 +56,57 @@ def test_cfg2_full_width_draft_expand(case):
     n_cmp, n_skip = compare_draft_tokens(case, tokens, scores, ref)
     print(f"full-width draft: {n_cmp} tokens compared, {n_skip} skipped by the margin rule")
     assert n_cmp >= 1 and n_skip <= max(1, n_cmp // 10)
+
+
+# --------------------------------------------------------------------------- the other benchmarked shapes
+def _verify_full_width(case, max_skipped):
+    case.upload_kv()
+    tt = case.random_tree_tokens()
+    feat, logits, greedy = case.gpu_verify(tt)
+    rfeat, rlogits, rgreedy = case.oracle_verify(tt)
+    skipped, err = compare_logits_and_greedy(case, logits, greedy, rlogits, rgreedy)
+    print(f"{case.cfg['name']} full-width verify: max logit error {err:.2e}, rows skipped by the margin rule {skipped}")
+    assert skipped <= max_skipped
+    assert rel_err_rows(feat, rfeat).max() < case.tol
+    # the tree rows' keys/values of the last layer, as stored (bf16) against the oracle's exact rows
+    k, v = case.download_kv()
+    for b in range(case.B):
+        C = case.ctx_lens[b]
+        for got, ref in ((k, case.tc[b].k), (v, case.tc[b].v)):
+            r = ref[-1][:, C:C + case.T]
+            assert np.abs(got[-1, b][:, C:C + case.T] - r).max() < 1e-2 * np.abs(r).max()
+
+
+def test_cfg3_full_width_verify_and_medusa_draft():
+    """64 rows (four activation tiles), 2048-token context: 9 key steps per attention split."""
+    case = Case("cfg3", n_layers=2, norm_gain="ones")
+    case.fill_kv_normal()
+    _verify_full_width(case, 4)
+    feat_in, tok_in = case.normal_draft_inputs()
+    tokens, scores = case.gpu_draft(feat_in, tok_in)
+    ref = case.oracle_draft(feat_in.astype(np.float64), tok_in)
+    n_cmp, n_skip = compare_draft_tokens(case, tokens, scores, ref)
+    print(f"cfg3 full-width draft: {n_cmp} tokens compared, {n_skip} skipped by the margin rule")
+    assert n_cmp >= case.T // 2 and n_skip <= max(1, n_cmp // 10)
+
+
+def test_cfg4_full_width_verify_and_draft():
+    """13B shape: hidden 5120 (40 heads), ffn 13824, 60 rows, 4096-token context (17 key steps per split)."""
+    case = Case("cfg4", n_layers=2, K=1, norm_gain="ones")
+    case.fill_kv_normal()
+    _verify_full_width(case, 4)
+    case.upload_kv()
+    feat_in, tok_in = case.normal_draft_inputs()
+    tokens, scores = case.gpu_draft(feat_in, tok_in)
+    ref = case.oracle_draft(feat_in.astype(np.float64), tok_in)
+    n_cmp, n_skip = compare_draft_tokens(case, tokens, scores, ref)
+    print(f"cfg4 full-width draft: {n_cmp} tokens compared, {n_skip} skipped by the margin rule")
+    assert n_cmp >= 1 and n_skip <= max(1, n_cmp // 10)
+
+
+def test_cfg5_full_width_ragged_batch_verify():
+    """33B shape: hidden 6656 (52 heads), ffn 17920; two sequences x 60 rows = 120 rows (one pass of eight
+    activation tiles), contexts of 8100 and 777 tokens in a cache of capacity 8320."""
+    case = Case("cfg5", n_layers=2, K=1, batch=2, ctx=[8100, 777], norm_gain="ones")
+    case.fill_kv_normal()
+    _verify_full_width(case, 6)

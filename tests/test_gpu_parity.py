@@ -260,6 +260,39 @@ def test_bf16_draft_expand_matches_oracle(cfgname, K):
         assert len(set(tokens[b, 1:1 + case.tree.topk_per_depth[0]])) == case.tree.topk_per_depth[0]
 
 
+# --------------------------------------------------------------------------- bf16, long contexts
+@pytest.mark.parametrize("cfgname,ctx", [("cfg2_small", 4096), ("cfg4_small", 2500), ("cfg3_small", 1777)])
+def test_bf16_verify_long_context_matches_oracle(cfgname, ctx):
+    """Contexts long enough that every attention wave runs several 32-key steps (the running maximum and
+    sum of the softmax are rescaled between steps), with a ragged last step."""
+    case = Case(cfgname, n_layers=2, ctx=ctx, capacity=ctx + 128)
+    case.fill_kv_normal()
+    case.upload_kv()
+    tt = case.random_tree_tokens()
+    feat, logits, greedy = case.gpu_verify(tt)
+    rfeat, rlogits, rgreedy = case.oracle_verify(tt)
+    skipped, err = compare_logits_and_greedy(case, logits, greedy, rlogits, rgreedy)
+    assert skipped <= max(1, case.B * case.T // 10)
+    assert rel_err_rows(feat, rfeat).max() < case.tol
+
+
+def test_bf16_long_context_softmax_with_a_dominant_late_key():
+    """The last 40 context rows get keys 8 x larger than the rest (a power of two: still exact in the
+    cache's storage type), so that the row maxima of the scores sit at the end of the context: every
+    earlier step's running maximum is replaced there and its partial sums are scaled down."""
+    case = Case("cfg2_small", n_layers=1, ctx=3000, capacity=3128)
+    case.fill_kv_normal()
+    C = case.ctx_lens[0]
+    for c in case.tc:
+        c.k[0][:, C - 40:C] *= 8.0
+    case.upload_kv()
+    tt = case.random_tree_tokens()
+    feat, logits, greedy = case.gpu_verify(tt)
+    rfeat, rlogits, rgreedy = case.oracle_verify(tt)
+    compare_logits_and_greedy(case, logits, greedy, rlogits, rgreedy)
+    assert rel_err_rows(feat, rfeat).max() < case.tol
+
+
 # --------------------------------------------------------------------------- bf16, many rows
 @pytest.mark.parametrize("batch", [2, 4, 5])
 def test_bf16_batched_verify_many_rows_matches_oracle(batch):

@@ -205,6 +205,7 @@ def test_bf16_sampled_draft_matches_oracle():
         n_cmp, n_all = _compare_sampled_tree(tree, draft([ud[0]]), tokens[0], ud[0], TEMP, 5e-5)
         compared += n_cmp
         total += n_all
+    print(f"bf16 sampled draft: {compared} of {total} draws decidable and compared")
     assert compared >= 0.5 * total
 
 
@@ -229,6 +230,7 @@ def test_medusa_sampled_draft_matches_oracle(K):
         dl = dl_dev.cpu().numpy()
         for u, row in ref["logits"].items():
             assert rel_err_rows(dl[0, u][None], row[None]).max() < case.tol
+    print(f"Medusa sampled draft K={K}: {compared} of {total} draws decidable and compared")
     assert compared >= 0.5 * total
 
 

@@ -460,3 +460,44 @@ def test_iterations_emit_plain_greedy_decoding(mode):
     assert got[:10] == want[:10]
     if mode == "planted":
         assert max(accepted) == tree.depth         # full-depth acceptance was exercised
+
+
+# ----------------------------------------------------------------------------- cache storage hook
+def test_cache_store_hook_touches_new_keys_and_values_only():
+    """KVCache.store models the cache's storage format.  Pins: no hook and the identity hook give the same
+    bits; the hook a -> a/2 (exact in binary) gives exactly what halving W_k and W_v gives without a hook
+    (keys and values are linear in those matrices and the rotation is linear), which fails if the hook also
+    reached the queries, missed the keys or the values, was applied twice, or touched context rows."""
+    Wt, _, _, toks, cache, _, _ = _nano_state()
+    C = 9
+    tree = nano_tree()
+    tt = tensor_uniform_int(7, "tree_tokens", (tree.n_nodes,), 0, NANO["vocab"])
+    plain, ident, halved_store, halved_w = cache.copy(), cache.copy(), cache.copy(), cache.copy()
+    ident.store = lambda a: a
+    halved_store.store = lambda a: 0.5 * a
+    ref = verify_tree(NANO, Wt, plain, C, tt, tree.parent)
+    got = verify_tree(NANO, Wt, ident, C, tt, tree.parent)
+    for r, g in zip(ref[:2], got[:2]):
+        np.testing.assert_array_equal(r, g)
+    for l in range(NANO["n_layers"]):
+        np.testing.assert_array_equal(plain.k[l], ident.k[l])
+        np.testing.assert_array_equal(plain.v[l], ident.v[l])
+
+    class HalvedKV:
+        """The same weights with every W_k and W_v multiplied by 1/2."""
+        def f32(self, name):
+            w = Wt.f32(name)
+            return 0.5 * w if name.endswith(".wk") or name.endswith(".wv") else w
+    a = verify_tree(NANO, Wt, halved_store, C, tt, tree.parent)
+    b = verify_tree(NANO, HalvedKV(), halved_w, C, tt, tree.parent)
+    assert np.abs(a[1] - ref[1]).max() > 1e-6              # the hook changed the result at all
+    np.testing.assert_allclose(a[0], b[0], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(a[1], b[1], rtol=1e-12, atol=1e-14)
+    for l in range(NANO["n_layers"]):
+        np.testing.assert_allclose(halved_store.k[l], halved_w.k[l], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(halved_store.v[l], halved_w.v[l], rtol=1e-12, atol=1e-14)
+        np.testing.assert_array_equal(halved_store.k[l][:, :C], cache.k[l][:, :C])   # context rows as given
+        np.testing.assert_array_equal(halved_store.v[l][:, :C], cache.v[l][:, :C])
+    # layer 0 sees the same input in both runs, so its stored tree rows are exactly half the exact ones
+    np.testing.assert_array_equal(halved_store.k[0][:, C:C + tree.n_nodes], 0.5 * plain.k[0][:, C:C + tree.n_nodes])
+    np.testing.assert_array_equal(halved_store.v[0][:, C:C + tree.n_nodes], 0.5 * plain.v[0][:, C:C + tree.n_nodes])

@@ -249,3 +249,30 @@ def test_medusa_sampled_draft_special_cases():
     np.testing.assert_allclose(s["logits"][0], g["logits"][0])
     np.testing.assert_allclose(s["logits"][a], g["logits"][1])
     assert len(set(int(s["tokens"][c]) for c in kids[a])) == len(kids[a])     # without replacement
+
+
+def test_inverse_cdf_definition_and_degenerate_cases():
+    """Inverse CDF over ascending id against a plain loop; a distribution with no positive weight has no
+    index whose running sum exceeds u * 0, and the reading for that case is the lowest id (the same
+    preference as in every tie rule of this build: lower id first).  It arises when more children are
+    drawn without replacement than the distribution has positive entries."""
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        V = int(rng.integers(1, 12))
+        p = rng.random(V) * (rng.random(V) < 0.7)
+        u = rng.random()
+        if p.sum() == 0:
+            assert oracle.inverse_cdf(p, u) == 0
+            continue
+        run, want = 0.0, None
+        for i in range(V):
+            run += p[i]
+            if run > u * p.sum():
+                want = i
+                break
+        if want is not None:
+            assert oracle.inverse_cdf(p, u) == want
+    assert oracle.inverse_cdf(np.zeros(7), 0.3) == 0
+    assert oracle.inverse_cdf(np.array([0.0, 0.0, 1.0, 0.0]), 0.999999) == 2
+    # a one-hot distribution drawn three times: the one positive id, then the degenerate reading twice
+    assert oracle.draw_without_replacement([0.0, 0.0, 0.0, 1.0, 0.0], [0.5, 0.5, 0.9]) == [3, 0, 0]
