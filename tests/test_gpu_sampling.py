@@ -206,7 +206,7 @@ def test_bf16_sampled_draft_matches_oracle():
         compared += n_cmp
         total += n_all
     print(f"bf16 sampled draft: {compared} of {total} draws decidable and compared")
-    assert compared >= 0.5 * total
+    assert compared >= 0.8 * total
 
 
 @pytest.mark.parametrize("K", [1, 2])
@@ -231,7 +231,7 @@ def test_medusa_sampled_draft_matches_oracle(K):
         for u, row in ref["logits"].items():
             assert rel_err_rows(dl[0, u][None], row[None]).max() < case.tol
     print(f"Medusa sampled draft K={K}: {compared} of {total} draws decidable and compared")
-    assert compared >= 0.5 * total
+    assert compared >= 0.8 * total
 
 
 def test_sampling_argument_errors():
