@@ -233,6 +233,23 @@ koala_status koala_accept_sample(koala_ctx *ctx, void *hip_stream, int batch,
                                  const float *u_resample, float temperature, int32_t *accept_len,
                                  int32_t *accept_path, int32_t *next_token, int commit);
 
+/* koala_accept_sample for callers that cannot allocate device memory or size a workspace for it: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Identical to
+ * koala_accept_sample (same kernels, same results bit for bit) except that the two vocabulary-sized
+ * distributions per sequence that the walk keeps are held in a fixed array inside the library
+ * (2 MiB of device memory per GPU, present from the moment the library is loaded until the process
+ * ends) instead of the workspace.  The call allocates nothing.
+ *   Limit: batch * vocab <= 262144, else KOALA_E_CAPACITY (nothing is launched).
+ *   The array is shared by every context and every call on the same GPU: two calls that overlap on
+ *   one GPU (different streams or threads) race; calls on one stream are ordered.  Nothing in the
+ *   array has to be cleared between calls (every element a call reads, it has written before). */
+koala_status koala_accept_sample_static(koala_ctx *ctx, void *hip_stream, int batch,
+                                        const int32_t *tree_tokens, const float *target_logits,
+                                        const float *draft_logits, const float *u_accept,
+                                        const float *u_resample, float temperature,
+                                        int32_t *accept_len, int32_t *accept_path,
+                                        int32_t *next_token, int commit);
+
 /* Statistics of a generation run.  accept_hist[a] counts the iterations that accepted exactly a
  * drafted tokens; from it follow the average number of tokens per iteration (section 4.1:
  * sum_a (a+1) accept_hist[a] / iterations) and, for a chain template, the n-alpha acceptance rates

@@ -9,7 +9,7 @@ KOALA_DRAFT_EAGLE, KOALA_DRAFT_MEDUSA = 0, 1
 
 EXPORTS = ("koala_create", "koala_workspace_bytes", "koala_bind", "koala_draft_expand",
            "koala_tree_verify", "koala_accept_prefix", "koala_generate", "koala_draft_expand_sample",
-           "koala_accept_sample", "koala_generate_sample", "koala_measure_stream_read", "koala_profile_begin",
+           "koala_accept_sample", "koala_accept_sample_static", "koala_generate_sample", "koala_measure_stream_read", "koala_profile_begin",
            "koala_profile_end", "koala_last_error", "koala_destroy")
 
 _STATUS = {0: "KOALA_OK", -1: "KOALA_E_NULL", -2: "KOALA_E_SHAPE", -3: "KOALA_E_ALIGN",
@@ -83,6 +83,7 @@ def load_library():
     lib.koala_generate.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp, C.POINTER(_GenStats)]
     lib.koala_draft_expand_sample.argtypes = [vp, vp, ip, vp, vp, ip, vp, C.c_float, vp, vp]
     lib.koala_accept_sample.argtypes = [vp, vp, ip, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, ip]
+    lib.koala_accept_sample_static.argtypes = lib.koala_accept_sample.argtypes
     lib.koala_generate_sample.argtypes = [vp, vp, vp, vp, ip, ip, ip, vp, ip, C.c_float, vp, C.POINTER(_GenStats)]
     lib.koala_measure_stream_read.argtypes = [vp, vp, C.c_size_t, ip, C.POINTER(C.c_double)]
     lib.koala_profile_begin.argtypes = [vp, ip]
@@ -91,7 +92,7 @@ def load_library():
     lib.koala_last_error.restype = C.c_char_p
     lib.koala_destroy.argtypes = [vp]
     lib.koala_destroy.restype = None
-    for n in EXPORTS[:13]:
+    for n in EXPORTS[:14]:
         getattr(lib, n).restype = C.c_int
     _LIB = lib
     return lib
@@ -213,6 +214,13 @@ class KoalaContext:
                                                  _ptr(target_logits), _ptr(draft_logits), _ptr(u_accept),
                                                  _ptr(u_resample), float(temperature), _ptr(accept_len),
                                                  _ptr(accept_path), _ptr(next_token), 1 if commit else 0))
+
+    def accept_sample_static(self, batch, tree_tokens, target_logits, draft_logits, u_accept, u_resample,
+                             temperature, accept_len, accept_path, next_token, commit, stream=None):
+        self._check(self.lib.koala_accept_sample_static(self._h, _stream(stream), batch, _ptr(tree_tokens),
+                                                        _ptr(target_logits), _ptr(draft_logits), _ptr(u_accept),
+                                                        _ptr(u_resample), float(temperature), _ptr(accept_len),
+                                                        _ptr(accept_path), _ptr(next_token), 1 if commit else 0))
 
     def profile_begin(self, max_launches=4096):
         self._check(self.lib.koala_profile_begin(self._h, max_launches))

@@ -6,7 +6,16 @@
 
 #include <algorithm>
 
+#include <mutex>
+
 #include "koala_internal.h"
+
+// Scratch of koala_accept_sample_static: the two distributions of the stochastic acceptance walk,
+// [2][KOALA_STATIC_SCRATCH_FLOATS / 2] floats.  Every device the library runs on holds its own copy of
+// the array until the process ends.  In host code the array's name is only a handle: the device
+// address is looked up once per device (static_scratch) and that pointer is what kernels receive.
+enum { KOALA_STATIC_SCRATCH_FLOATS = 2 * 262144 };
+static __device__ __align__(256) float scratch[KOALA_STATIC_SCRATCH_FLOATS];
 
 namespace {
 
@@ -31,6 +40,27 @@ struct Carver {
         return p;
     }
 };
+
+// Device address of `scratch` on the current device, looked up on first use per device.
+hipError_t static_scratch(float **out) {
+    enum { MAX_DEVICES = 64 };
+    static float *ptr[MAX_DEVICES] = {nullptr};
+    static std::mutex mu;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = (float *)p;
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
 
 int attn_nsplit(const koala_ctx *c) {
     // enough (split, head, sequence) workgroups to cover the chip a few times over
@@ -427,6 +457,10 @@ koala_status koala_bind(koala_ctx *c, const koala_weights *w, const koala_kv *kv
     if (e == hipSuccess) e = upload(c->tt.exp_index, c->exp_index);
     if (e == hipSuccess) e = upload(c->tt.draft_mask, c->draft_mask);
     if (e == hipSuccess) e = upload(c->tt.level_nodes, levels);
+    if (e == hipSuccess) {
+        float *unused = nullptr;   // looks up this device's copy of the static scratch array
+        e = static_scratch(&unused);
+    }
     if (e == hipSuccess && c->shape.dtype == KOALA_BF16) {
         // persistent verification: device table of the layers' pointers, zeroed barrier counters, abort flags
         const size_t ls = layer_stride_bytes(c);
@@ -710,10 +744,11 @@ koala_status koala_draft_expand_sample(koala_ctx *c, void *hip_stream, int batch
                              draft_logits);
 }
 
-koala_status koala_accept_sample(koala_ctx *c, void *hip_stream, int batch, const int32_t *tree_tokens,
-                                 const float *target_logits, const float *draft_logits, const float *u_accept,
-                                 const float *u_resample, float temperature, int32_t *accept_len,
-                                 int32_t *accept_path, int32_t *next_token, int commit) {
+static koala_status accept_sample_impl(koala_ctx *c, void *hip_stream, int batch, const int32_t *tree_tokens,
+                                       const float *target_logits, const float *draft_logits,
+                                       const float *u_accept, const float *u_resample, float temperature,
+                                       int32_t *accept_len, int32_t *accept_path, int32_t *next_token, int commit,
+                                       bool use_static) {
     koala_status st0 = check_call(c, batch);
     if (st0 != KOALA_OK) return st0;
     if (!tree_tokens || !target_logits || !u_accept || !u_resample || !accept_len || !accept_path || !next_token ||
@@ -722,10 +757,23 @@ koala_status koala_accept_sample(koala_ctx *c, void *hip_stream, int batch, cons
     if (!(temperature > 0.f)) return fail(c, KOALA_E_SHAPE, "temperature must be positive");
     if (c->shape.vocab > ks::max_vocab())
         return fail(c, KOALA_E_UNSUPPORTED, "vocabulary too large for the sampling kernels");
-    hipStream_t st = (hipStream_t)hip_stream;
     const koala_shape &s = c->shape;
+    float *qv = c->acc_q, *dv = c->acc_d;
+    if (use_static) {
+        if ((size_t)batch * (size_t)s.vocab > KOALA_STATIC_SCRATCH_FLOATS / 2)
+            return fail(c, KOALA_E_CAPACITY, "koala_accept_sample_static: batch * vocab exceeds 262144");
+        float *base = nullptr;
+        const hipError_t e = static_scratch(&base);
+        if (e != hipSuccess) {
+            c->err = std::string("static scratch look-up failed: ") + hipGetErrorString(e);
+            return KOALA_E_DEVICE;
+        }
+        qv = base;
+        dv = base + KOALA_STATIC_SCRATCH_FLOATS / 2;
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
     ks::accept_sample(st, c->tt, c->T, c->D, s.vocab, temperature, tree_tokens, target_logits, draft_logits,
-                      u_accept, u_resample, c->acc_q, c->acc_d, accept_len, accept_path, next_token, batch);
+                      u_accept, u_resample, qv, dv, accept_len, accept_path, next_token, batch);
     if (commit) {
         kg::kv_commit(st, s.dtype == KOALA_BF16, c->kv.target_k, c->kv.target_v, c->kv.ctx_len, accept_len,
                       accept_path, c->D, s.n_layers, c->max_batch, batch, s.n_heads, c->kv.capacity, s.head_dim);
@@ -733,6 +781,23 @@ koala_status koala_accept_sample(koala_ctx *c, void *hip_stream, int batch, cons
     }
     KOALA_CHECK_LAUNCH(c);
     return KOALA_OK;
+}
+
+koala_status koala_accept_sample(koala_ctx *c, void *hip_stream, int batch, const int32_t *tree_tokens,
+                                 const float *target_logits, const float *draft_logits, const float *u_accept,
+                                 const float *u_resample, float temperature, int32_t *accept_len,
+                                 int32_t *accept_path, int32_t *next_token, int commit) {
+    return accept_sample_impl(c, hip_stream, batch, tree_tokens, target_logits, draft_logits, u_accept, u_resample,
+                              temperature, accept_len, accept_path, next_token, commit, false);
+}
+
+koala_status koala_accept_sample_static(koala_ctx *c, void *hip_stream, int batch, const int32_t *tree_tokens,
+                                        const float *target_logits, const float *draft_logits,
+                                        const float *u_accept, const float *u_resample, float temperature,
+                                        int32_t *accept_len, int32_t *accept_path, int32_t *next_token,
+                                        int commit) {
+    return accept_sample_impl(c, hip_stream, batch, tree_tokens, target_logits, draft_logits, u_accept, u_resample,
+                              temperature, accept_len, accept_path, next_token, commit, true);
 }
 
 koala_status koala_accept_prefix(koala_ctx *c, void *hip_stream, int batch, const int32_t *tree_tokens,
