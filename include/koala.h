@@ -103,7 +103,9 @@ typedef struct {
 /* Device weight pointers, borrowed until koala_destroy or the next koala_bind.
  *   embed, lm_head  [vocab, hidden];  final_norm [hidden]
  *   layer_w: host array of 6 * n_layers device pointers, per layer
- *       in_norm [hidden], wqkv [3*hidden, hidden] (rows: all of W_q, then W_k, then W_v),
+ *       in_norm [hidden], wqkv [3*hidden, hidden] (rows: all of W_q, then W_k, then W_v; for KOALA_BF16
+ *           the rows of W_q and W_k are reordered inside every head so that the two members of a rotary
+ *           pair are neighbours: row 2i of a head is dimension i, row 2i+1 is dimension i + head_dim/2),
  *       wo [hidden, hidden], post_norm [hidden],
  *       wgu [2*ffn, hidden] with rows interleaved (row 2f = gate_f, row 2f+1 = up_f),
  *       wdown [hidden, ffn]
@@ -173,12 +175,7 @@ koala_status koala_draft_expand(koala_ctx *ctx, void *hip_stream, int batch,
  *   feat_out    device fp32 [batch, n_nodes, hidden] (out): features after the final RMSNorm;
  *   logits_out  device fp32 [batch, n_nodes, vocab] (out, may be NULL);
  *   greedy_out  device int32 [batch, n_nodes] (out): argmax of each row's logits,
- *               lowest id among equal maxima.
- * Environment: KOALA_PERSISTENT=1 runs the decoder layers of a bf16 context with one sequence of at
- * most 32 rows and head_dim 128 in a single cooperative kernel instead of one kernel per step (same
- * results up to the order of the partial sums; not used while the stream is being captured).  If a
- * wait inside that kernel times out, the outputs of that call are invalid and the next
- * koala_tree_verify returns KOALA_E_DEVICE once, after which the context is usable again. */
+ *               lowest id among equal maxima. */
 koala_status koala_tree_verify(koala_ctx *ctx, void *hip_stream, int batch,
                                const int32_t *tree_tokens, float *feat_out, float *logits_out,
                                int32_t *greedy_out);

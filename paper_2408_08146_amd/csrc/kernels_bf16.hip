@@ -18,6 +18,8 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+struct __attribute__((may_alias, aligned(8))) u64_pair { uint32_t x, y; };
+struct __attribute__((may_alias, aligned(8))) f32_pair { float x, y; };
 
 __device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
 __device__ __forceinline__ uint32_t f2bf(float v) {  // round to nearest even
@@ -136,6 +138,200 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
                 const int row = (mt0 + rs * MT + m) * 16 + li, n = rb * 64 + 16 * t + 4 * lg;
                 *(f32x4 *)(P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = acc[t][m];
             }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row-group GEMM with a fused epilogue.  One workgroup owns U consecutive 16-row groups of the weights
+// (16 U output columns) over a K range; its waves take the 64-k tiles of that range in turn (wave w:
+// tiles w, w + KW, ...) and every wave loads both operands of its tiles straight into MFMA registers -
+// the U 2 KiB weight pieces and the matching hi/lo activation fragments - so the streaming loop has no
+// barrier and no LDS traffic.  The waves' accumulators meet once, in LDS, and are added in wave order
+// (deterministic).  With S = 1 the workgroup then holds finished outputs and applies the consumer's
+// element-wise step itself:
+//   EPI_PARTIAL  store fp32 partial sums P[sp][row][n] (split-K, S >= 1), folded by a later kernel;
+//   EPI_QKV      row scale of the pending RMSNorm, rotary embedding, queries to qrot (fp32), rotated keys
+//                and values to their cache slots (bf16).  W_q / W_k rows are stored pair-interleaved
+//                (koala.h), so the two halves of a rotary pair are neighbours in one lane;
+//   EPI_SWIGLU   row scale, SiLU(gate) * up (rows interleaved gate, up), written as hi/lo fragments of the
+//                down projection's input.
+// Every compute unit can take in only so many bytes per second (about 53 GB/s measured, weights and
+// activations together), and with S = 1 every workgroup reads all activation fragments; U is therefore
+// chosen so that one launch is one workgroup per compute unit with equal shares of the weights.
+// RS > 1: RS waves share a tile position and split the MT * RS activation tiles between them.
+// ---------------------------------------------------------------------------------------------
+enum { EPI_PARTIAL = 0, EPI_QKV = 1, EPI_SWIGLU = 2 };
+
+struct GemmEpi {
+    float *P;           // EPI_PARTIAL
+    const float *sums;  // EPI_QKV, EPI_SWIGLU: per-chunk sums of squares of the input rows (nullptr: scale 1)
+    int nparts, srows, Kn;
+    float eps;
+    int rows;           // valid activation rows
+    RowMeta meta;       // EPI_QKV
+    float *qrot;
+    bf16_t *kc, *vc;
+    int H, n_heads, DH, cap;
+    uint32_t *Xo;       // EPI_SWIGLU: output fragments, F = out features / 2
+    int F;
+};
+
+template <int U, int MT, int RS, int NW, int PF, int EPI>
+__global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
+                                                       int Npad, int K, int S, GemmEpi e) {
+    constexpr int MTT = MT * RS, KW = NW / RS;
+    extern __shared__ __attribute__((aligned(16))) unsigned char gsm[];
+    f32x4 *red = (f32x4 *)gsm;                                     // [NW][U][MT][64]
+    float *cs = (float *)(gsm + (size_t)NW * U * MT * 64 * 16);    // EPI_QKV: [MTT*16][U][8][cos, sin]
+    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
+    const int kw = wave / RS, mh = wave % RS;
+    const int nunits = Npad / 16, nwg = (nunits + U - 1) / U;
+    const int g = blockIdx.x % nwg, sp = blockIdx.x / nwg, ug0 = g * U;
+    const int nkt = K / 64;
+    const int kt0 = (int)((long long)sp * nkt / S), kt1 = (int)((long long)(sp + 1) * nkt / S);
+    const u32x4 *w[U];   // unit j, tile kt, half s: w[j] + kt * 512 + s * 64 (a ragged last group re-reads its last unit)
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        const int ug = min(ug0 + j, nunits - 1);
+        w[j] = Wp + ((size_t)(ug >> 2) * nkt * 8 + (ug & 3) * 2) * 64 + l;
+    }
+    const u32x4 *x = Xf + (size_t)mh * MT * 128 + l;
+
+    u32x4 wr[PF][U][2], xr[PF][2][MT][2];
+    auto load = [&](int kt, int slot) {
+#pragma unroll
+        for (int j = 0; j < U; ++j)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) wr[slot][j][s] = __builtin_nontemporal_load(w[j] + (size_t)kt * 512 + s * 64);
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    xr[slot][s][m][h] = x[(size_t)(2 * kt + s) * (MTT * 128) + (m * 2 + h) * 64];
+    };
+    int kt = kt0 + kw;
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+        if (kt + p * KW < kt1) load(kt + p * KW, p);
+
+    // per-lane row data of the epilogue, fetched while the first tiles are in flight
+    float rsc[MTT];
+    int rslot[MTT], rbat[MTT];
+    if (EPI != EPI_PARTIAL) {
+#pragma unroll
+        for (int m = 0; m < MTT; ++m) {
+            const int row = m * 16 + li;
+            const bool ok = row < e.rows;
+            float tot = 0.f;
+            if (e.sums && ok)
+                for (int c = 0; c < e.nparts; ++c) tot += e.sums[(size_t)c * e.srows + row];
+            rsc[m] = e.sums ? 1.0f / sqrtf(tot / (float)e.Kn + e.eps) : 1.f;
+            if (EPI == EPI_QKV) {
+                rslot[m] = ok ? e.meta.row_slot[row] : 0;
+                rbat[m] = ok ? e.meta.row_b[row] : 0;
+            }
+        }
+    }
+    if (EPI == EPI_QKV) {
+        const int half = e.DH / 2;
+        for (int u = threadIdx.x; u < MTT * 16 * U * 8; u += 64 * NW) {
+            const int dd = u & 7, j = (u >> 3) % U, row = (u >> 3) / U;
+            const int n = min(ug0 + j, nunits - 1) * 16;
+            const bool ok = row < e.rows && n < 2 * e.H;
+            const int ddg = ((n % e.H) % e.DH) / 2 + dd;
+            cs[2 * u] = ok ? e.meta.rope_cos[(size_t)row * half + ddg] : 1.f;
+            cs[2 * u + 1] = ok ? e.meta.rope_sin[(size_t)row * half + ddg] : 0.f;
+        }
+    }
+
+    f32x4 acc[U][MT];
+#pragma unroll
+    for (int j = 0; j < U; ++j)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[j][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (; kt < kt1; kt += PF * KW) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            if (kt + p * KW < kt1) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+#pragma unroll
+                    for (int j = 0; j < U; ++j) {
+                        const bf16x8 a = __builtin_bit_cast(bf16x8, wr[p][j][s]);
+#pragma unroll
+                        for (int m = 0; m < MT; ++m) {
+                            acc[j][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                a, __builtin_bit_cast(bf16x8, xr[p][s][m][0]), acc[j][m], 0, 0, 0);
+                            acc[j][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                a, __builtin_bit_cast(bf16x8, xr[p][s][m][1]), acc[j][m], 0, 0, 0);
+                        }
+                    }
+                }
+                if (kt + (p + PF) * KW < kt1) load(kt + (p + PF) * KW, p);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) red[((size_t)(wave * U + j) * MT + m) * 64 + l] = acc[j][m];
+    __syncthreads();
+
+    // output piece (j, mtt): weight rows of unit j x activation tile mtt; lane (li, lg) holds columns
+    // n .. n + 3 of activation row mtt * 16 + li
+    for (int u = wave; u < U * MTT; u += NW) {
+        const int j = u / MTT, mtt = u % MTT, umh = mtt / MT, um = mtt % MT;
+        if (ug0 + j >= nunits) continue;
+        f32x4 v = red[((size_t)(umh * U + j) * MT + um) * 64 + l];
+#pragma unroll
+        for (int q = 1; q < KW; ++q) v += red[((size_t)((q * RS + umh) * U + j) * MT + um) * 64 + l];
+        const int row = mtt * 16 + li, n = (ug0 + j) * 16 + 4 * lg;
+        if (EPI == EPI_PARTIAL) {
+            *(f32x4 *)(e.P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = v;
+            continue;
+        }
+        if (row >= e.rows) continue;
+        float sc = 1.f;
+        int slot = 0, bat = 0;
+#pragma unroll
+        for (int m = 0; m < MTT; ++m)   // static indexing keeps the per-row data in registers
+            if (m == mtt) { sc = rsc[m]; if (EPI == EPI_QKV) { slot = rslot[m]; bat = rbat[m]; } }
+        v *= sc;
+        if (EPI == EPI_QKV) {
+            const int which = n / e.H, nn = n % e.H, h = nn / e.DH, r = nn % e.DH, half = e.DH / 2;
+            const size_t o = (((size_t)bat * e.n_heads + h) * e.cap + slot) * e.DH;
+            if (which == 2) {
+                const uint32_t lo = f2bf(v[0]) | (f2bf(v[1]) << 16), hi = f2bf(v[2]) | (f2bf(v[3]) << 16);
+                *(u64_pair *)(e.vc + o + r) = u64_pair{lo, hi};
+            } else {
+                const int dd = r >> 1;
+                const float *t = cs + 2 * (((size_t)row * U + j) * 8 + 2 * lg);
+                const float c0 = t[0], s0 = t[1], c1 = t[2], s1 = t[3];
+                const float a0 = v[0] * c0 - v[1] * s0, b0 = v[1] * c0 + v[0] * s0;
+                const float a1 = v[2] * c1 - v[3] * s1, b1 = v[3] * c1 + v[2] * s1;
+                if (which == 0) {
+                    float *q = e.qrot + (size_t)row * e.H + h * e.DH + dd;
+                    *(f32_pair *)q = f32_pair{a0, a1};
+                    *(f32_pair *)(q + half) = f32_pair{b0, b1};
+                } else {
+                    *(uint32_t *)(e.kc + o + dd) = f2bf(a0) | (f2bf(a1) << 16);
+                    *(uint32_t *)(e.kc + o + half + dd) = f2bf(b0) | (f2bf(b1) << 16);
+                }
+            }
+        } else {   // EPI_SWIGLU
+            const int f0 = n >> 1;
+            if (f0 >= e.F) continue;
+            const float g0 = v[0], g1 = v[2];
+            const float y0 = g0 / (1.0f + __expf(-g0)) * v[1], y1 = g1 / (1.0f + __expf(-g1)) * v[3];
+            const uint32_t h0 = f2bf(y0), h1 = f2bf(y1);
+            const uint32_t l0 = f2bf(y0 - bf2f(h0)), l1 = f2bf(y1 - bf2f(h1));
+            const int ks = f0 >> 5, lane = li + 16 * ((f0 & 31) >> 3);
+            uint32_t *dst = e.Xo + ((((size_t)ks * MTT + mtt) * 2) * 64 + lane) * 4 + ((f0 & 7) >> 1);
+            dst[0] = h0 | (h1 << 16);
+            dst[64 * 4] = l0 | (l1 << 16);
+        }
     }
 }
 
@@ -296,8 +492,9 @@ __global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowScale
     const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x, half = DH / 2;
     const int b = meta.row_b[r], slot = meta.row_slot[r];
     const float c = meta.rope_cos[(size_t)r * half + i], s = meta.rope_sin[(size_t)r * half + i];
-    const int cols[6] = {h * DH + i, h * DH + half + i, H + h * DH + i, H + h * DH + half + i, 2 * H + h * DH + i,
-                         2 * H + h * DH + half + i};
+    // W_q and W_k rows are stored pair-interleaved: output 2i of a head is dimension i, 2i + 1 is i + half
+    const int cols[6] = {h * DH + 2 * i, h * DH + 2 * i + 1, H + h * DH + 2 * i, H + h * DH + 2 * i + 1,
+                         2 * H + h * DH + i, 2 * H + h * DH + half + i};
     float t[6];
     psum_n<6>(P, S, Mp, ldp, r, cols, t);
     const float sc = row_scale(rs, r);
@@ -486,6 +683,59 @@ __global__ __launch_bounds__(256) void k_topk_stage2(const float *cand_val, cons
 
 inline int cdiv(size_t a, size_t b) { return (int)((a + b - 1) / b); }
 
+template <int U, int MT, int RS, int NW, int PF, int EPI>
+void launch_gemm_rows(hipStream_t st, const void *Wp, const void *Xf, int Npad, int K, int S, const GemmEpi &e,
+                      hipEvent_t ev_start, hipEvent_t ev_stop) {
+    const size_t sm = (size_t)NW * U * MT * 64 * 16 + (EPI == EPI_QKV ? (size_t)MT * RS * 16 * U * 8 * 2 * 4 : 0);
+    static bool done = false;
+    if (!done) {
+        (void)hipFuncSetAttribute((const void *)k_gemm_rows<U, MT, RS, NW, PF, EPI>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+        done = true;
+    }
+    const dim3 grid(((Npad / 16 + U - 1) / U) * S);
+    if (ev_start || ev_stop)
+        hipExtLaunchKernelGGL((k_gemm_rows<U, MT, RS, NW, PF, EPI>), grid, dim3(64 * NW), sm, st, ev_start, ev_stop, 0,
+                              (const u32x4 *)Wp, (const u32x4 *)Xf, Npad, K, S, e);
+    else
+        k_gemm_rows<U, MT, RS, NW, PF, EPI><<<grid, 64 * NW, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, Npad, K, S,
+                                                                      e);
+}
+
+// MTT = 1, 2 or 4 activation tiles (four: two waves per tile position, two tiles each)
+template <int U, int EPI>
+void dispatch_gemm_rows_u(hipStream_t st, const void *Wp, const void *Xf, int Npad, int K, int MTT, int S,
+                          const GemmEpi &e, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    constexpr int PF = U >= 7 ? 1 : 2;   // tiles in flight per wave; seven groups with two leave no registers for a second
+    if (MTT == 1) launch_gemm_rows<U, 1, 1, 8, 2, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
+    else if (MTT == 2) launch_gemm_rows<U, 2, 1, 8, PF, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
+    else launch_gemm_rows<U, 2, 2, 8, PF, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
+}
+
+// 16-row groups per workgroup for an S = 1 launch over Npad rows: the smallest supported count that covers the
+// rows with at most one workgroup per compute unit (KOALA_GEMM_U forces a count, for tests and tuning)
+int rows_units(int Npad, int n_cu) {
+    static const int forced = getenv("KOALA_GEMM_U") ? atoi(getenv("KOALA_GEMM_U")) : 0;
+    static const int sup[4] = {3, 4, 6, 7};
+    for (int u : sup)
+        if (forced == u) return u;
+    const int units = Npad / 16;
+    for (int u : sup)
+        if ((units + u - 1) / u <= n_cu) return u;
+    return sup[3];
+}
+
+template <int EPI>
+void dispatch_gemm_rows(hipStream_t st, const void *Wp, const void *Xf, int Npad, int K, int MTT, int U,
+                        const GemmEpi &e, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    switch (U) {
+    case 3: dispatch_gemm_rows_u<3, EPI>(st, Wp, Xf, Npad, K, MTT, 1, e, ev_start, ev_stop); break;
+    case 4: dispatch_gemm_rows_u<4, EPI>(st, Wp, Xf, Npad, K, MTT, 1, e, ev_start, ev_stop); break;
+    case 6: dispatch_gemm_rows_u<6, EPI>(st, Wp, Xf, Npad, K, MTT, 1, e, ev_start, ev_stop); break;
+    default: dispatch_gemm_rows_u<7, EPI>(st, Wp, Xf, Npad, K, MTT, 1, e, ev_start, ev_stop); break;
+    }
+}
+
 }  // namespace
 
 // =====================================================================================================
@@ -527,6 +777,15 @@ int gemm_splits(int Npad, int K, int MTT) {
     return S;
 }
 
+// K splits of gemm_rows_partial: about 256 workgroups of 64 weight rows each
+int rows_splits(int Npad, int K) {
+    static const int target = env_int("KOALA_ROWS_WGS", 256);
+    const int nb = Npad / 64, nkt = K / 64;
+    int S = (target + nb / 2) / nb;
+    S = S < 1 ? 1 : S > 8 ? 8 : S;
+    return S > nkt ? nkt : S;
+}
+
 static bool g_attr_done[4] = {false, false, false, false};
 
 static RowScale mk_scale(const NormScale &n) { return RowScale{n.sums, n.nparts, n.srows, n.K, n.eps}; }
@@ -564,6 +823,32 @@ void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int N
         mt0 += g;
     }
 #undef KOALA_GEMM
+}
+
+void gemm_rows_partial(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S,
+                       hipEvent_t ev_start, hipEvent_t ev_stop) {
+    GemmEpi e{};
+    e.P = P;
+    dispatch_gemm_rows_u<4, EPI_PARTIAL>(st, Wp, Xf, Npad, K, MTT, S, e, ev_start, ev_stop);
+}
+
+void gemm_rows_qkv(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const NormScale &ns, int rows,
+                   const RowMeta &meta, float *qrot, void *kc, void *vc, int H, int n_heads, int head_dim, int cap, int n_cu,
+                   hipEvent_t ev_start, hipEvent_t ev_stop) {
+    GemmEpi e{};
+    e.sums = ns.sums; e.nparts = ns.nparts; e.srows = ns.srows; e.Kn = ns.K; e.eps = ns.eps;
+    e.rows = rows; e.meta = meta; e.qrot = qrot; e.kc = (bf16_t *)kc; e.vc = (bf16_t *)vc;
+    e.H = H; e.n_heads = n_heads; e.DH = head_dim; e.cap = cap;
+    dispatch_gemm_rows<EPI_QKV>(st, Wp, Xf, 3 * H, K, MTT, rows_units(3 * H, n_cu), e, ev_start, ev_stop);
+}
+
+void gemm_rows_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const NormScale &ns, int rows,
+                      void *Xo, int F, int n_cu, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    GemmEpi e{};
+    e.sums = ns.sums; e.nparts = ns.nparts; e.srows = ns.srows; e.Kn = ns.K; e.eps = ns.eps;
+    e.rows = rows; e.Xo = (uint32_t *)Xo; e.F = F;
+    dispatch_gemm_rows<EPI_SWIGLU>(st, Wp, Xf, pad64(2 * F), K, MTT, rows_units(pad64(2 * F), n_cu), e, ev_start,
+                                   ev_stop);
 }
 
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,

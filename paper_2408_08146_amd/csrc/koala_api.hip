@@ -62,11 +62,12 @@ hipError_t static_scratch(float **out) {
     return hipSuccess;
 }
 
-int attn_nsplit(const koala_ctx *c) {
-    // enough (split, head, sequence) workgroups to cover the chip a few times over
+// Key splits per (head, sequence) of the attention kernels: enough workgroups to cover the chip.  Read once,
+// at koala_create (KOALA_ATTN_WGS overrides the target); the workspace is carved for this count.
+int attn_nsplit(const koala_shape &s) {
     int target = 256;
     if (const char *e = getenv("KOALA_ATTN_WGS")) target = atoi(e) > 0 ? atoi(e) : target;
-    int ns = target / std::max(1, c->shape.n_heads * 1);
+    const int ns = target / std::max(1, s.n_heads);
     return std::max(1, std::min((int)KOALA_NSPLIT_MAX, ns));
 }
 
@@ -74,7 +75,7 @@ size_t carve(koala_ctx *c, char *base) {
     Carver w{base, 0};
     const koala_shape &s = c->shape;
     const int T = c->T, D = c->D, R = c->max_rows, H = s.hidden, F = s.ffn, V = s.vocab;
-    const int half = s.head_dim / 2, ns = attn_nsplit(c);
+    const int half = s.head_dim / 2, ns = c->attn_ns;
     (void)w.take<double>(half);  // inv_freq, first in the workspace
     c->tt.parent = w.take<int32_t>(T);
     c->tt.depth = w.take<int32_t>(T);
@@ -123,28 +124,27 @@ size_t carve(koala_ctx *c, char *base) {
     c->med_logits = c->draft.kind == KOALA_DRAFT_MEDUSA ? w.take<float>((size_t)D * c->max_batch * V) : nullptr;
     c->acc_q = w.take<float>((size_t)c->max_batch * V);
     c->acc_d = w.take<float>((size_t)c->max_batch * V);
-    c->xf = nullptr;
+    c->xf = c->xf2 = nullptr;
     c->part = nullptr;
     c->xf_bytes = c->part_bytes = 0;
     if (s.dtype == KOALA_BF16) {
         const int MTmax = kb::mt_of(R);
         const int shapes[6][2] = {{3 * H, H}, {H, H}, {2 * F, H}, {H, F}, {kb::pad64(V), H}, {H, 2 * H}};
         size_t worst = 0;
-        for (auto &sh : shapes)
-            worst = std::max(worst, (size_t)std::max(kb::gemm_splits(kb::pad64(sh[0]), sh[1]),
-                                                     kb::gemm_splits(kb::pad64(sh[0]), sh[1], MTmax)) * kb::pad64(sh[0]));
-        // the persistent verification cuts its GEMMs stream-K over the CUs (sized for 256 of them)
-        worst = std::max(worst, kp::part_floats_per_row(H, F, 256));
+        for (auto &sh : shapes) {
+            const int Np = kb::pad64(sh[0]);
+            const int S = std::max(std::max(kb::gemm_splits(Np, sh[1]), kb::gemm_splits(Np, sh[1], MTmax)),
+                                   kb::rows_splits(Np, sh[1]));
+            worst = std::max(worst, (size_t)S * Np);
+        }
         c->part_bytes = worst * MTmax * 16 * sizeof(float);
         c->xf_bytes = kb::xf_bytes(std::max(2 * H, F), MTmax);
         c->xf = w.take<char>(c->xf_bytes);
+        c->xf2 = w.take<char>(kb::xf_bytes(F, MTmax));
         c->part = w.take<float>(c->part_bytes / sizeof(float));
         c->row_sums = w.take<float>((size_t)R * 64);
         c->cand_val = w.take<float>((size_t)R * ((V + 1023) / 1024) * KOALA_TOPK_MAX);
         c->cand_idx = w.take<int>((size_t)R * ((V + 1023) / 1024) * KOALA_TOPK_MAX);
-        c->pl_layers = w.take<kp::Layer>(s.n_layers);
-        c->pl_bar = w.take<unsigned long long>(9 * 16);
-        c->pl_abort = w.take<int>(4);
     }
     return w.off;
 }
@@ -165,7 +165,7 @@ void decoder_layer(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, co
     kg::gemm(st, bf, c->act, H, lw[1], c->qkv, 3 * H, rows, 3 * H, H, false);
     kg::rope_append(st, bf, c->qkv, c->meta, c->qrot, kc, vc, rows, H, s.n_heads, s.head_dim, c->kv.capacity, 0);
     kg::attention(st, bf, c->qrot, c->meta, kc, vc, c->o_part, c->ml, c->attn_out, batch, rows_per_seq, s.n_heads,
-                  s.head_dim, c->kv.capacity, attn_nsplit(c));
+                  s.head_dim, c->kv.capacity, c->attn_ns);
     kg::gemm(st, bf, c->attn_out, H, lw[2], c->x, H, rows, H, H, true);
     kg::rmsnorm(st, bf, c->x, lw[3], c->act, rows, H, s.rms_eps);
     kg::gemm(st, bf, c->act, H, lw[4], c->gu, 2 * F, rows, 2 * F, H, false);
@@ -173,75 +173,31 @@ void decoder_layer(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, co
     kg::gemm(st, bf, c->act, F, lw[5], c->x, H, rows, H, F, true);
 }
 
+// Event pair for the next weight-streaming launch while profiling is on (else nulls); counts its weight bytes.
+struct LaunchEvents { hipEvent_t start, stop; };
+LaunchEvents timed_launch(koala_ctx *c, double weight_bytes) {
+    if (!c->prof_on || (size_t)(c->prof_used + 2) > c->prof_ev.size()) return LaunchEvents{nullptr, nullptr};
+    const LaunchEvents ev{c->prof_ev[c->prof_used], c->prof_ev[c->prof_used + 1]};
+    c->prof_used += 2;
+    c->prof_bytes += weight_bytes;
+    return ev;
+}
+
 // Split-K GEMM on the fragments in c->xf: partial sums of X * W^T into c->part; returns the split count.
 int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) {
     const int Npad = kb::pad64(N), S = kb::gemm_splits(Npad, K, MT);
-    const bool timed = c->prof_on && (size_t)(c->prof_used + 2) <= c->prof_ev.size();
-    kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S, timed ? c->prof_ev[c->prof_used] : nullptr,
-                    timed ? c->prof_ev[c->prof_used + 1] : nullptr);
-    if (timed) {
-        c->prof_used += 2;
-        c->prof_bytes += (double)Npad * K * 2.0;
-    }
+    const LaunchEvents ev = timed_launch(c, (double)Npad * K * 2.0);
+    kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S, ev.start, ev.stop);
     return S;
 }
 
-// KOALA_PERSISTENT=1: verification of one sequence of at most 32 rows runs all layers in one cooperative kernel
-bool persistent_enabled() {
-    const char *v = getenv("KOALA_PERSISTENT");   // read per call, so that a process can compare both paths
-    return v && atoi(v) != 0;
-}
-
-// KOALA_PERSISTENT_TRACE=1 (diagnostic): the single-kernel verification stamps the wall clock at every step as
-// workgroup 0 sees it; the times are printed to stderr after every call (which then waits for the stream).
-constexpr size_t kTraceMaxLayers = 1024;
-size_t persistent_trace_words(size_t layers) { return 3 * (2 + (size_t)kp::BARRIERS_PER_LAYER * layers) + 1 + 256; }
-
-long long *persistent_trace_buffer(int n_layers) {
-    static long long *dev = nullptr;   // one buffer per process, kept until it ends
-    const char *tr = getenv("KOALA_PERSISTENT_TRACE");
-    if (!tr || atoi(tr) == 0 || (size_t)n_layers > kTraceMaxLayers) return nullptr;
-    if (!dev && hipMalloc((void **)&dev, persistent_trace_words(kTraceMaxLayers) * sizeof(long long)) != hipSuccess) dev = nullptr;
-    return dev;
-}
-
-void persistent_trace_print(hipStream_t st, const long long *dev, int n_layers) {
-    const size_t n_tr = 2 + (size_t)kp::BARRIERS_PER_LAYER * n_layers;
-    std::vector<long long> t(persistent_trace_words(n_layers));
-    if (hipStreamSynchronize(st) != hipSuccess ||
-        hipMemcpy(t.data(), dev, t.size() * sizeof(long long), hipMemcpyDeviceToHost) != hipSuccess)
-        return;
-    static const char *names[10] = {"fold_in", "qkv", "rope", "attn", "combine", "o", "fold_post", "gu", "silu", "down"};
-    // per step: whole duration, and its split into work issued | stores acknowledged | barrier passed
-    double acc[10] = {0}, wk[10] = {0}, ak[10] = {0}, br[10] = {0};
-    for (int l = 0; l < n_layers; ++l)
-        for (int j = 0; j < 10; ++j) {
-            const size_t b = 1 + 10 * l + j;
-            acc[j] += (double)(t[b] - t[b - 1]) * 0.01;
-            wk[j] += (double)(t[n_tr + b] - t[b - 1]) * 0.01;
-            ak[j] += (double)(t[2 * n_tr + b] - t[n_tr + b]) * 0.01;
-            br[j] += (double)(t[b] - t[2 * n_tr + b]) * 0.01;
-        }
-    fprintf(stderr, "persistent trace (us per layer):");
-    for (int j = 0; j < 10; ++j) fprintf(stderr, " %s %.2f", names[j], acc[j] / n_layers);
-    fprintf(stderr, " | total %.1f us\n", (double)(t[n_tr - 1] - t[0]) * 0.01);
-#ifdef KOALA_PL_TW
-    if (n_layers > 5) {
-        const long long *tx = t.data() + 3 * n_tr;
-        const int nt = (int)std::min<long long>(tx[0], 64);
-        const long long t0 = t[10 * 5];
-        fprintf(stderr, "  layer 5 tiles of stream wave 0 of workgroup %d (start x-ready done flushed, us after the layer began):\n   ", KOALA_PL_TW);
-        for (int i = 0; i < nt; ++i)
-            fprintf(stderr, " [%.2f %.2f %.2f %.2f]", (tx[1 + 4 * i] - t0) * 0.01, (tx[2 + 4 * i] - t0) * 0.01,
-                    (tx[3 + 4 * i] - t0) * 0.01, (tx[4 + 4 * i] - t0) * 0.01);
-        fprintf(stderr, "\n   barriers of layer 5:");
-        for (int j = 1; j <= 10; ++j) fprintf(stderr, " %.2f", (t[10 * 5 + j] - t0) * 0.01);
-        fprintf(stderr, "\n");
-    }
-#endif
-    fprintf(stderr, "  work/ack/barrier:");
-    for (int j = 0; j < 10; ++j) fprintf(stderr, " %s %.1f/%.1f/%.1f", names[j], wk[j] / n_layers, ak[j] / n_layers, br[j] / n_layers);
-    fprintf(stderr, "\n");
+// Split-K GEMM for at most four activation tiles with the row-group kernel (64 weight rows per workgroup, the
+// K range cut so that the launch is about one workgroup per compute unit); fragments from Xf
+int bf_gemm_rows(koala_ctx *c, hipStream_t st, const void *Wp, const void *Xf, int N, int K, int MT) {
+    const int Npad = kb::pad64(N), S = kb::rows_splits(Npad, K);
+    const LaunchEvents ev = timed_launch(c, (double)Npad * K * 2.0);
+    kb::gemm_rows_partial(st, Wp, Xf, c->part, Npad, K, MT, S, ev.start, ev.stop);
+    return S;
 }
 
 kb::NormScale no_scale() { return kb::NormScale{nullptr, 0, 0, 1, 0.f}; }
@@ -267,24 +223,41 @@ void rows_to_frags(koala_ctx *c, hipStream_t st, const float *a, int lda, int ro
 }
 
 // bf16 decoder layer.  On entry c->pend_* may describe partial sums still to be folded into x; on exit
-// the down projection's are pending.
+// the down projection's are pending.  Up to 64 rows: seven launches (fold, QKV projection with rotary embedding
+// and cache append, attention, merge of its key splits, O projection, fold, gate/up projection with SwiGLU,
+// down projection).  More rows: the projections run in passes with their element-wise steps as kernels of
+// their own.
 void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_seq, const void *const *lw,
                         void *kc, void *vc) {
     const koala_shape &s = c->shape;
     const int rows = batch * rows_per_seq, H = s.hidden, F = s.ffn, MT = kb::mt_of(rows), Mp = MT * 16;
-    const int ns = attn_nsplit(c);
+    const int ns = c->attn_ns;
+    const bool fused = MT <= 4;
     fold_pending(c, st, rows, MT, lw[0]);
-    int S = bf_gemm(c, st, lw[1], 3 * H, H, MT);
-    kb::rope_append(st, c->part, S, Mp, 3 * H, hidden_scale(c), c->meta, c->qrot, kc, vc, rows, H, s.n_heads,
-                    s.head_dim, c->kv.capacity);
+    int S;
+    if (fused) {
+        const LaunchEvents ev = timed_launch(c, 3.0 * H * H * 2.0);
+        kb::gemm_rows_qkv(st, lw[1], c->xf, H, MT, hidden_scale(c), rows, c->meta, c->qrot, kc, vc, H, s.n_heads,
+                          s.head_dim, c->kv.capacity, c->n_cu, ev.start, ev.stop);
+    } else {
+        S = bf_gemm(c, st, lw[1], 3 * H, H, MT);
+        kb::rope_append(st, c->part, S, Mp, 3 * H, hidden_scale(c), c->meta, c->qrot, kc, vc, rows, H, s.n_heads,
+                        s.head_dim, c->kv.capacity);
+    }
     kb::attention_mfma(st, c->qrot, c->meta, kc, vc, c->o_part, c->ml, batch, rows_per_seq, s.n_heads, s.head_dim,
                        c->kv.capacity, ns);
     kb::attn_combine_frag(st, c->o_part, c->ml, c->xf, MT, rows, s.n_heads, ns, s.head_dim);
-    S = bf_gemm(c, st, lw[2], H, H, MT);
+    S = fused ? bf_gemm_rows(c, st, lw[2], c->xf, H, H, MT) : bf_gemm(c, st, lw[2], H, H, MT);
     kb::fold(st, c->x, H, c->part, S, Mp, H, 1, rows, H, lw[3], c->xf, MT, c->row_sums, c->max_rows);
-    S = bf_gemm(c, st, lw[4], 2 * F, H, MT);
-    kb::silu_frag(st, c->part, S, Mp, 2 * F, hidden_scale(c), c->xf, MT, rows, F);
-    S = bf_gemm(c, st, lw[5], H, F, MT);
+    if (fused) {
+        const LaunchEvents ev = timed_launch(c, (double)kb::pad64(2 * F) * H * 2.0);
+        kb::gemm_rows_swiglu(st, lw[4], c->xf, H, MT, hidden_scale(c), rows, c->xf2, F, c->n_cu, ev.start, ev.stop);
+        S = bf_gemm_rows(c, st, lw[5], c->xf2, H, F, MT);
+    } else {
+        S = bf_gemm(c, st, lw[4], 2 * F, H, MT);
+        kb::silu_frag(st, c->part, S, Mp, 2 * F, hidden_scale(c), c->xf, MT, rows, F);
+        S = bf_gemm(c, st, lw[5], H, F, MT);
+    }
     c->pend_S = S;
     c->pend_ld = H;
     c->pend_mode = 1;
@@ -351,6 +324,8 @@ koala_status koala_create(const koala_shape *shape, const koala_draft_shape *dra
     c->prof_used = 0;
     c->prof_bytes = 0.0;
     c->pend_S = 0;
+    c->attn_ns = attn_nsplit(s);
+    c->n_cu = 256;
     c->parent.assign(tree->parent, tree->parent + T);
     c->rank.assign(tree->rank, tree->rank + T);
     c->topk.assign(tree->topk_per_depth, tree->topk_per_depth + D);
@@ -461,25 +436,10 @@ koala_status koala_bind(koala_ctx *c, const koala_weights *w, const koala_kv *kv
         float *unused = nullptr;   // looks up this device's copy of the static scratch array
         e = static_scratch(&unused);
     }
-    if (e == hipSuccess && c->shape.dtype == KOALA_BF16) {
-        // persistent verification: device table of the layers' pointers, zeroed barrier counters, abort flags
-        const size_t ls = layer_stride_bytes(c);
-        std::vector<kp::Layer> lt(c->shape.n_layers);
-        for (int l = 0; l < c->shape.n_layers; ++l) {
-            const void *const *lw = c->w.layer_w + 6 * l;
-            lt[l] = kp::Layer{lw[1], lw[2], lw[4], lw[5], lw[0], lw[3], (char *)c->kv.target_k + ls * l,
-                              (char *)c->kv.target_v + ls * l};
-        }
-        e = upload(c->pl_layers, lt);
-        if (e == hipSuccess) e = hipMemset(c->pl_bar, 0, 9 * 16 * sizeof(unsigned long long));
-        if (e == hipSuccess) e = hipMemset(c->pl_abort, 0, 4 * sizeof(int));
-        c->pl_gen = 0;
-        c->pl_shard = 0;
-        if (e == hipSuccess && !c->pl_abort_host) e = hipHostMalloc((void **)&c->pl_abort_host, 64, hipHostMallocDefault);
-        if (e == hipSuccess) *c->pl_abort_host = 0;
+    if (e == hipSuccess) {
         int dev = 0;
         hipDeviceProp_t prop;
-        if (e == hipSuccess) e = hipGetDevice(&dev);
+        e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
         if (e == hipSuccess) c->n_cu = prop.multiProcessorCount;
     }
@@ -511,63 +471,9 @@ koala_status koala_tree_verify(koala_ctx *c, void *hip_stream, int batch, const 
     if (bf) {
         const int MT = kb::mt_of(rows), Mp = MT * 16;
         c->pend_S = 0;
-        // a cooperative launch cannot be captured into a graph: a capturing stream takes the per-layer kernels
-        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(st, &capture) != hipSuccess) capture = hipStreamCaptureStatusActive;
-        if (persistent_enabled() && capture == hipStreamCaptureStatusNone &&
-            kp::supported(rows, batch, s.head_dim, s.n_layers) && c->n_cu >= 8 && c->n_cu % 8 == 0 && c->n_cu <= 256) {
-            if (*c->pl_abort_host != 0) {
-                // an earlier pass timed out inside the kernel: its results were wrong; start from clean counters
-                *c->pl_abort_host = 0;
-                (void)hipMemsetAsync(c->pl_bar, 0, 9 * 16 * sizeof(unsigned long long), st);
-                (void)hipMemsetAsync(c->pl_abort, 0, 4 * sizeof(int), st);
-                c->pl_gen = 0;
-                c->pl_shard = 0;
-                return fail(c, KOALA_E_DEVICE, "an earlier persistent verification pass timed out; its outputs are invalid");
-            }
-            kp::Params q{};
-            const int ns = attn_nsplit(c);
-            q.layers = c->pl_layers;
-            q.L = s.n_layers; q.H = H; q.F = s.ffn; q.n_heads = s.n_heads; q.rows = rows; q.cap = c->kv.capacity;
-            q.nsplit = ns; q.srows = c->max_rows; q.eps = s.rms_eps;
-            q.x = c->x; q.x_bytes = (unsigned)((size_t)c->max_rows * H * 4);
-            q.Xf = c->xf; q.xf_bytes = (unsigned)c->xf_bytes;
-            q.part = c->part; q.part_bytes = (unsigned)c->part_bytes;
-            q.sums = c->row_sums; q.sums_bytes = (unsigned)((size_t)c->max_rows * 64 * 4);
-            q.qrot = c->qrot; q.qrot_bytes = (unsigned)((size_t)c->max_rows * H * 4);
-            q.o_part = c->o_part; q.opart_bytes = (unsigned)((size_t)c->max_rows * H * ns * 4);
-            q.ml = c->ml; q.ml_bytes = (unsigned)((size_t)c->max_rows * s.n_heads * ns * 2 * 4);
-            q.kv_layer_bytes = (unsigned)ls;
-            q.meta = c->meta;
-            q.bar = c->pl_bar; q.bar_base = c->pl_gen; q.shard_base = c->pl_shard;
-            {
-                // tuning knobs (measured best: every workgroup runs the small steps and every workgroup fetches the
-                // next projection's first tiles right after it arrived at the barrier that ends a projection)
-                int nc = c->n_cu;
-                if (const char *e = getenv("KOALA_PL_NCLEAN")) nc = atoi(e);
-                nc = std::max(8, std::min(c->n_cu, nc / 8 * 8));
-                q.nclean = nc;
-                q.pf_from = 0;
-                if (const char *e = getenv("KOALA_PL_PFFROM")) q.pf_from = std::max(0, atoi(e));
-            }
-            q.abort_flag = c->pl_abort; q.abort_host = c->pl_abort_host;
-            if (ls > 0xFFFFFF00ull || c->part_bytes > 0xFFFFFF00ull)
-                return fail(c, KOALA_E_UNSUPPORTED, "buffers too large for the persistent verification kernel");
-            q.trace = persistent_trace_buffer(s.n_layers);
-            const hipError_t le = kp::launch(st, q, MT, c->n_cu);
-            if (q.trace && le == hipSuccess) persistent_trace_print(st, q.trace, s.n_layers);
-            if (le != hipSuccess) {
-                c->err = std::string("cooperative launch failed: ") + hipGetErrorString(le);
-                return KOALA_E_DEVICE;
-            }
-            c->pl_gen += (unsigned long long)kp::BARRIERS_PER_LAYER * s.n_layers;
-            // per layer, five barriers where all workgroups arrive and five where only the first nclean do
-            c->pl_shard += (unsigned long long)s.n_layers * 5ull * (unsigned long long)(c->n_cu / 8 + q.nclean / 8);
-        } else {
-            for (int l = 0; l < s.n_layers; ++l)
-                decoder_layer_bf16(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,
-                                   (char *)c->kv.target_v + ls * l);
-        }
+        for (int l = 0; l < s.n_layers; ++l)
+            decoder_layer_bf16(c, st, batch, T, c->w.layer_w + 6 * l, (char *)c->kv.target_k + ls * l,
+                               (char *)c->kv.target_v + ls * l);
         // last down projection folded in; the LM head runs on gain * x and its logits take the row scale;
         // the features (an output) are normalised separately
         fold_pending(c, st, rows, MT, c->w.final_norm);
@@ -990,7 +896,6 @@ const char *koala_last_error(const koala_ctx *ctx) { return ctx ? ctx->err.c_str
 void koala_destroy(koala_ctx *ctx) {
     if (!ctx) return;
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
-    if (ctx->pl_abort_host) (void)hipHostFree(ctx->pl_abort_host);
     delete ctx;
 }
 

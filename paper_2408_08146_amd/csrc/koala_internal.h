@@ -35,50 +35,6 @@ struct TreeTables {
     int32_t *child_first, *child_count;  // unused by kernels that scan; kept for clarity
 };
 
-// ---------------------------------------------------------------------------------------------
-// kernels_persistent.hip: all decoder layers of a verification pass in one cooperative kernel
-// ---------------------------------------------------------------------------------------------
-namespace kp {
-
-struct Layer {   // device pointers of one decoder layer (array in the workspace)
-    const void *wqkv, *wo, *wgu, *wdown, *in_norm, *post_norm;
-    void *kc, *vc;
-};
-
-struct Params {
-    const Layer *layers;
-    int L, H, F, n_heads, rows, cap, nsplit, srows;
-    float eps;
-    float *x;       unsigned x_bytes;       // residual stream [rows][H]
-    void *Xf;       unsigned xf_bytes;      // GEMM input fragments
-    float *part;    unsigned part_bytes;    // partial sums [slot][MT*16][Npad]
-    float *sums;    unsigned sums_bytes;    // per-chunk sums of squares [chunk][srows]
-    float *qrot;    unsigned qrot_bytes;    // rotated queries [rows][H]
-    float *o_part;  unsigned opart_bytes;   // attention partial outputs
-    float *ml;      unsigned ml_bytes;      // their running max / sum
-    unsigned kv_layer_bytes;                // bytes of one layer of a KV cache
-    RowMeta meta;
-    unsigned long long *bar;                // grid barrier counters (9 x 128 B), monotonic across launches
-    unsigned long long bar_base;            // barrier generations used by earlier launches
-    unsigned long long shard_base;          // arrivals per shard counter in earlier launches
-    int nclean;                             // workgroups that run the small steps (multiple of 8)
-    int pf_from;                            // workgroups >= pf_from fetch the next projection's first tiles early
-    int *abort_flag;                        // device: set when a wait timed out
-    int *abort_host;                        // pinned host memory: set by the kernel on abort
-    long long *trace;                       // optional diagnostics, n = 2 + 10 * L wall-clock ticks per block:
-                                            // [0, n) start, every barrier passed, end; [n, 2n) step's work issued;
-                                            // [2n, 3n) its stores acknowledged; then 1 + 256 words of per-tile stamps
-};
-
-enum { BARRIERS_PER_LAYER = 10 };
-
-bool supported(int rows, int batch, int head_dim, int n_layers);
-// floats the partial-sum buffer needs per activation row for the stream-K cut over G workgroups
-size_t part_floats_per_row(int H, int F, int G);
-hipError_t launch(hipStream_t st, const Params &p, int MT, int G);
-
-}  // namespace kp
-
 struct koala_ctx {
     koala_shape shape;
     koala_draft_shape draft;
@@ -105,18 +61,12 @@ struct koala_ctx {
     float *gen_dlogits, *gen_tlogits;                    // [T][V] draft / target logits of the non-greedy loop
     float *gen_feat, *gen_feat_in;                       // [T][H] verify features; [max(D+1, max_m)][H] next draft inputs
     int32_t *gen_tree, *gen_greedy, *gen_acc, *gen_path, *gen_next, *gen_tok_in;
-    // persistent verification (kernels_persistent.hip)
-    kp::Layer *pl_layers;          // [n_layers] device copy of the layer pointers
-    unsigned long long *pl_bar;    // grid barrier counters
-    int *pl_abort;                 // device abort flag
-    int *pl_abort_host;            // pinned host abort flag
-    unsigned long long pl_gen;     // barrier generations consumed so far
-    unsigned long long pl_shard;   // arrivals per shard counter so far
     int n_cu;                      // compute units of the device the context is bound on
+    int attn_ns;                   // key splits of the attention kernels (fixed at create)
     float *med_logits;                                   // [D * max_batch][V] per-depth logits of Medusa-style heads (sampled drafting)
     float *acc_q, *acc_d;                                // [max_batch][V] distributions of the stochastic acceptance walk
     // bf16 path: GEMM input as hi/lo bf16 MFMA fragments, and the split-K partial sums
-    void *xf;
+    void *xf, *xf2;   // xf2: input of the down projection (written by the gate/up projection's epilogue)
     float *part;
     size_t xf_bytes, part_bytes;
     float *cand_val;   // [rows][ceil(V/1024)][16] top-k candidates of the LM-head epilogue
@@ -236,11 +186,24 @@ struct NormScale {
     float eps;
 };
 
-int gemm_splits(int Npad, int K, int MTT = 0);   // MTT: activation tiles of the call (0: at most four)
+int gemm_splits(int Npad, int K, int MTT = 0);
+int rows_splits(int Npad, int K);              // split count of gemm_rows_partial   // MTT: activation tiles of the call (0: at most four)
 // P[S][MTT*16][Npad] = partial sums of X * W^T, X given as hi/lo fragments [K/32][MTT][2][64] x 16 B
 // ev_start/ev_stop (either may be null) are attached to the dispatch: they take the kernel's own begin and end times
 void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S,
                  hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+// Row-group GEMM (one workgroup per few 16-row groups of the weights and K range, waves take 64-k tiles in
+// turn; n_cu = compute units of the device, which sets the groups per workgroup), MTT = 1, 2 or 4:
+// _partial: P[S][MTT*16][Npad] partial sums, like gemm_packed;  _qkv (S = 1): row scale, rotary embedding,
+// queries to qrot, keys/values into their cache slots (W_q, W_k rows pair-interleaved);  _swiglu (S = 1): row
+// scale, SiLU(gate) * up as hi/lo fragments Xo of the down projection's input
+void gemm_rows_partial(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S,
+                       hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+void gemm_rows_qkv(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const NormScale &ns, int rows,
+                   const RowMeta &meta, float *qrot, void *kc, void *vc, int H, int n_heads, int head_dim, int cap, int n_cu,
+                   hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+void gemm_rows_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const NormScale &ns, int rows,
+                      void *Xo, int F, int n_cu, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 // v = (mode 1: x +) sum of partials (mode 0: x as is); x <- v for modes 1, 2; Xf (may be NULL) receives the
 // fragments of gain * v (gain NULL: v); sums (may be NULL) the sums of squares of v per 512-column chunk
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,

@@ -31,10 +31,22 @@ def _mat(w, dtype):
     return fragment_major(w) if dtype == "bf16" else w.contiguous()
 
 
-def _layer(provider, prefix, l, device, dtype):
+def rotary_pair_interleave(w, head_dim):
+    """Reorder the rows of W_q or W_k [n_heads * head_dim, K] inside every head so that the two members of a
+    rotary pair are neighbours: new row 2i holds dimension i, new row 2i + 1 dimension i + head_dim / 2."""
+    n, k = w.shape
+    half = head_dim // 2
+    return w.reshape(n // head_dim, 2, half, k).transpose(1, 2).reshape(n, k)
+
+
+def _layer(provider, prefix, l, device, dtype, head_dim):
     import torch
     g = lambda n: _dev(provider, f"{prefix}layers.{l}.{n}", device, dtype)
-    wqkv = torch.cat([g("wq"), g("wk"), g("wv")], dim=0)
+    if dtype == "bf16":
+        wqkv = torch.cat([rotary_pair_interleave(g("wq"), head_dim), rotary_pair_interleave(g("wk"), head_dim),
+                          g("wv")], dim=0)
+    else:
+        wqkv = torch.cat([g("wq"), g("wk"), g("wv")], dim=0)
     gate, up = g("wgate"), g("wup")
     wgu = torch.stack([gate, up], dim=1).reshape(2 * gate.shape[0], gate.shape[1])
     return (g("in_norm"), _mat(wqkv, dtype), _mat(g("wo"), dtype), g("post_norm"), _mat(wgu, dtype),
@@ -45,12 +57,12 @@ def pack_target_weights(provider, cfg, device="cuda"):
     dt = cfg["dtype"]
     return dict(embed=_dev(provider, "embed", device, dt), lm_head=_mat(_dev(provider, "lm_head", device, dt), dt),
                 final_norm=_dev(provider, "final_norm", device, dt),
-                layers=[_layer(provider, "", l, device, dt) for l in range(cfg["n_layers"])])
+                layers=[_layer(provider, "", l, device, dt, cfg["head_dim"]) for l in range(cfg["n_layers"])])
 
 
 def pack_eagle_weights(provider, cfg, device="cuda"):
     dt = cfg["dtype"]
-    layers = [_layer(provider, "draft.", k, device, dt) for k in range(cfg["K"])]
+    layers = [_layer(provider, "draft.", k, device, dt, cfg["head_dim"]) for k in range(cfg["K"])]
     return dict(fc=_mat(_dev(provider, "draft.fc", device, dt), dt), draft=[t for layer in layers for t in layer])
 
 

@@ -12,11 +12,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("cfgname", ["cfg1", "cfg2_small"])
-def test_captured_iteration_replays_like_eager(cfgname, monkeypatch):
+def test_captured_iteration_replays_like_eager(cfgname):
     import torch
-    # eager and captured calls must run the same kernels for a bit-for-bit comparison: a capturing stream never
-    # takes the single-kernel verification, so the eager call must not either
-    monkeypatch.setenv("KOALA_PERSISTENT", "0")
     case = Case(cfgname, ctx=48 if cfgname == "cfg1" else None)
     case.fill_kv_normal()
     case.upload_kv()
