@@ -150,8 +150,8 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
 // (deterministic).  With S = 1 the workgroup then holds finished outputs and applies the consumer's
 // element-wise step itself:
 //   EPI_PARTIAL  store fp32 partial sums P[sp][row][n] (split-K, S >= 1), folded by a later kernel;
-//   EPI_QKV      row scale of the pending RMSNorm, rotary embedding, queries to qrot (fp32), rotated keys
-//                and values to their cache slots (bf16).  W_q / W_k rows are stored pair-interleaved
+//   EPI_QKV      row scale of the pending RMSNorm, rotary embedding, queries (times 1/sqrt(head_dim)) as hi/lo
+//                MFMA fragments for the attention kernel, rotated keys and values to their cache slots (bf16).  W_q / W_k rows are stored pair-interleaved
 //                (koala.h), so the two halves of a rotary pair are neighbours in one lane;
 //   EPI_SWIGLU   row scale, SiLU(gate) * up (rows interleaved gate, up), written as hi/lo fragments of the
 //                down projection's input.
@@ -169,9 +169,10 @@ struct GemmEpi {
     float eps;
     int rows;           // valid activation rows
     RowMeta meta;       // EPI_QKV
-    float *qrot;
+    uint32_t *qf;       // query fragments [batch][n_heads][MTQ][DH/32][hi, lo][64 lanes][4], scaled by qscale
     bf16_t *kc, *vc;
-    int H, n_heads, DH, cap;
+    int H, n_heads, DH, cap, rows_per_seq, MTQ;
+    float qscale;
     uint32_t *Xo;       // EPI_SWIGLU: output fragments, F = out features / 2
     int F;
 };
@@ -312,9 +313,19 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
                 const float a0 = v[0] * c0 - v[1] * s0, b0 = v[1] * c0 + v[0] * s0;
                 const float a1 = v[2] * c1 - v[3] * s1, b1 = v[3] * c1 + v[2] * s1;
                 if (which == 0) {
-                    float *q = e.qrot + (size_t)row * e.H + h * e.DH + dd;
-                    *(f32_pair *)q = f32_pair{a0, a1};
-                    *(f32_pair *)(q + half) = f32_pair{b0, b1};
+                    // dimensions dd, dd + 1 and dd + half, dd + half + 1 of row i of its sequence
+                    const int i = row - bat * e.rows_per_seq;
+                    uint32_t *qt = e.qf + ((((size_t)bat * e.n_heads + h) * e.MTQ + (i >> 4)) * (e.DH / 32)) * 2 * 64 * 4;
+                    const float y[4] = {a0 * e.qscale, a1 * e.qscale, b0 * e.qscale, b1 * e.qscale};
+#pragma unroll
+                    for (int z = 0; z < 2; ++z) {
+                        const int d = dd + z * half;
+                        const uint32_t h0 = f2bf(y[2 * z]), h1 = f2bf(y[2 * z + 1]);
+                        const uint32_t l0 = f2bf(y[2 * z] - bf2f(h0)), l1 = f2bf(y[2 * z + 1] - bf2f(h1));
+                        uint32_t *dst = qt + (((size_t)(d >> 5) * 2) * 64 + (i & 15) + 16 * ((d & 31) >> 3)) * 4 + ((d & 7) >> 1);
+                        dst[0] = h0 | (h1 << 16);
+                        dst[64 * 4] = l0 | (l1 << 16);
+                    }
                 } else {
                     *(uint32_t *)(e.kc + o + dd) = f2bf(a0) | (f2bf(a1) << 16);
                     *(uint32_t *)(e.kc + o + half + dd) = f2bf(b0) | (f2bf(b1) << 16);
@@ -487,8 +498,9 @@ __global__ __launch_bounds__(64) void k_fold(float *x, int ldx, const float *P, 
 // ---------------------------------------------------------------------------------------------
 // RoPE + KV append from the QKV partials.  grid (rows, n_heads), block head_dim/2.
 // ---------------------------------------------------------------------------------------------
-__global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowScale rs, RowMeta meta, float *qrot,
-                                bf16_t *kc, bf16_t *vc, int H, int n_heads, int DH, int cap) {
+__global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowScale rs, RowMeta meta, bf16_t *qf,
+                                bf16_t *kc, bf16_t *vc, int H, int n_heads, int DH, int cap, int rows_per_seq, int MTQ,
+                                float qscale) {
     const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x, half = DH / 2;
     const int b = meta.row_b[r], slot = meta.row_slot[r];
     const float c = meta.rope_cos[(size_t)r * half + i], s = meta.rope_sin[(size_t)r * half + i];
@@ -499,57 +511,23 @@ __global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowScale
     psum_n<6>(P, S, Mp, ldp, r, cols, t);
     const float sc = row_scale(rs, r);
     const float q0 = sc * t[0], q1 = sc * t[1], k0 = sc * t[2], k1 = sc * t[3], v0 = sc * t[4], v1 = sc * t[5];
-    qrot[(size_t)r * H + h * DH + i] = q0 * c - q1 * s;
-    qrot[(size_t)r * H + h * DH + half + i] = q1 * c + q0 * s;
+    // query fragments [b][h][MTQ][DH/32][hi, lo][64 lanes][8]: row ri of the sequence, dimensions i and i + half
+    const int ri = r - b * rows_per_seq;
+    bf16_t *qt = qf + ((((size_t)b * n_heads + h) * MTQ + (ri >> 4)) * (DH / 32)) * 2 * 64 * 8;
+    const float y[2] = {(q0 * c - q1 * s) * qscale, (q1 * c + q0 * s) * qscale};
+#pragma unroll
+    for (int z = 0; z < 2; ++z) {
+        const int d = i + z * half;
+        const uint32_t hi = f2bf(y[z]), lo = f2bf(y[z] - bf2f(hi));
+        bf16_t *dst = qt + (((size_t)(d >> 5) * 2) * 64 + (ri & 15) + 16 * ((d & 31) >> 3)) * 8 + (d & 7);
+        dst[0] = (bf16_t)hi;
+        dst[64 * 8] = (bf16_t)lo;
+    }
     const size_t o = (((size_t)b * n_heads + h) * cap + slot) * DH;
     kc[o + i] = (bf16_t)f2bf(k0 * c - k1 * s);
     kc[o + half + i] = (bf16_t)f2bf(k1 * c + k0 * s);
     vc[o + i] = (bf16_t)f2bf(v0);
     vc[o + half + i] = (bf16_t)f2bf(v1);
-}
-
-// merge the attention splits and write the result as hi/lo fragments (K = H). grid (H/512, M), 64 threads.
-// All loads are issued before anything is combined (one memory round trip).
-__global__ __launch_bounds__(64) void k_attn_combine_frag(const float *o_part, const float *ml, u32x4 *Xf, int MT,
-                                                          int n_heads, int nsplit, int DH, int H) {
-    const int r = blockIdx.y, g = blockIdx.x * 64 + threadIdx.x;
-    if (g >= H / 8) return;
-    const int h = (g * 8) / DH, d0 = (g * 8) % DH;
-    const float *p = ml + ((size_t)r * n_heads + h) * nsplit * 2;
-    const float *ob = o_part + ((size_t)r * n_heads + h) * nsplit * DH + d0;
-    f32x4 oa[KOALA_NSPLIT_MAX], oc[KOALA_NSPLIT_MAX];
-    float ms[KOALA_NSPLIT_MAX], ls[KOALA_NSPLIT_MAX];
-#pragma unroll
-    for (int s = 0; s < KOALA_NSPLIT_MAX; ++s) {
-        if (s < nsplit) {
-            const f32x4 *o = (const f32x4 *)(ob + (size_t)s * DH);
-            oa[s] = o[0];
-            oc[s] = o[1];
-            ms[s] = p[2 * s];
-            ls[s] = p[2 * s + 1];
-        } else {
-            oa[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            oc[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            ms[s] = -INFINITY;
-            ls[s] = 0.f;
-        }
-    }
-    float Mx = -INFINITY;
-#pragma unroll
-    for (int s = 0; s < KOALA_NSPLIT_MAX; ++s) Mx = fmaxf(Mx, ms[s]);
-    f32x4 ya = {0.f, 0.f, 0.f, 0.f}, yc = {0.f, 0.f, 0.f, 0.f};
-    float den = 0.f;
-#pragma unroll
-    for (int s = 0; s < KOALA_NSPLIT_MAX; ++s) {
-        const float w = (ms[s] == -INFINITY) ? 0.f : __expf(ms[s] - Mx);
-        den += w * ls[s];
-        ya += w * oa[s];
-        yc += w * oc[s];
-    }
-    const float inv = 1.0f / den;
-    const float y[8] = {ya[0] * inv, ya[1] * inv, ya[2] * inv, ya[3] * inv, yc[0] * inv, yc[1] * inv, yc[2] * inv,
-                        yc[3] * inv};
-    store_frag8(Xf, MT, r, g * 8, y);
 }
 
 // SiLU(gate) * up from the gate/up partials (col 2f = gate, 2f+1 = up), scaled by the pending RMSNorm
@@ -833,12 +811,13 @@ void gemm_rows_partial(hipStream_t st, const void *Wp, const void *Xf, float *P,
 }
 
 void gemm_rows_qkv(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const NormScale &ns, int rows,
-                   const RowMeta &meta, float *qrot, void *kc, void *vc, int H, int n_heads, int head_dim, int cap, int n_cu,
-                   hipEvent_t ev_start, hipEvent_t ev_stop) {
+                   int rows_per_seq, const RowMeta &meta, void *qf, void *kc, void *vc, int H, int n_heads, int head_dim,
+                   int cap, int n_cu, hipEvent_t ev_start, hipEvent_t ev_stop) {
     GemmEpi e{};
     e.sums = ns.sums; e.nparts = ns.nparts; e.srows = ns.srows; e.Kn = ns.K; e.eps = ns.eps;
-    e.rows = rows; e.meta = meta; e.qrot = qrot; e.kc = (bf16_t *)kc; e.vc = (bf16_t *)vc;
+    e.rows = rows; e.meta = meta; e.qf = (uint32_t *)qf; e.kc = (bf16_t *)kc; e.vc = (bf16_t *)vc;
     e.H = H; e.n_heads = n_heads; e.DH = head_dim; e.cap = cap;
+    e.rows_per_seq = rows_per_seq; e.MTQ = (rows_per_seq + 15) / 16; e.qscale = 1.0f / sqrtf((float)head_dim);
     dispatch_gemm_rows<EPI_QKV>(st, Wp, Xf, 3 * H, K, MTT, rows_units(3 * H, n_cu), e, ev_start, ev_stop);
 }
 
@@ -858,17 +837,11 @@ void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int 
 }
 
 void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, const RowMeta &meta,
-                 float *qrot, void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap) {
-    k_rope_append_p<<<dim3(rows, n_heads), head_dim / 2, 0, st>>>(P, S, Mp, ldp, mk_scale(ns), meta, qrot,
-                                                                  (bf16_t *)kc, (bf16_t *)vc, H, n_heads, head_dim,
-                                                                  cap);
-}
-
-void attn_combine_frag(hipStream_t st, const float *o_part, const float *ml, void *Xf, int MT, int M, int n_heads,
-                       int nsplit, int head_dim) {
-    const int H = n_heads * head_dim;
-    k_attn_combine_frag<<<dim3((H / 8 + 63) / 64, M), 64, 0, st>>>(o_part, ml, (u32x4 *)Xf, MT, n_heads, nsplit,
-                                                                   head_dim, H);
+                 void *qf, void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap, int rows_per_seq) {
+    k_rope_append_p<<<dim3(rows, n_heads), head_dim / 2, 0, st>>>(P, S, Mp, ldp, mk_scale(ns), meta, (bf16_t *)qf,
+                                                                  (bf16_t *)kc, (bf16_t *)vc, H, n_heads, head_dim, cap,
+                                                                  rows_per_seq, (rows_per_seq + 15) / 16,
+                                                                  1.0f / sqrtf((float)head_dim));
 }
 
 void silu_frag(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, void *Xf, int MT, int M,
@@ -896,11 +869,12 @@ void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *o
 }  // namespace kb
 
 // =====================================================================================================
-// Tree-masked attention on MFMA (bf16 KV cache, fp32 queries split into bf16 hi + lo).
+// Tree-masked attention on MFMA (bf16 KV cache; queries arrive as bf16 hi + lo MFMA fragments, already
+// multiplied by 1/sqrt(head_dim), written by the QKV projection's epilogue).
 //
-// grid (nsplit, n_heads, batch), 4 waves.  The sequence's visible key range [0, kv_end) is cut into
-// nsplit chunks; inside a chunk the waves take 32-key steps round-robin, each wave keeping an
-// online-softmax state (running max, sum, output) for all MT row tiles, merged through LDS at the end.
+// grid (nsplit * row groups, n_heads, batch), NWV waves.  The 32-key steps of the sequence's visible key range
+// [0, kv_end) are dealt out round-robin over the nsplit workgroups and their waves, each wave keeping an
+// online-softmax state (running max, sum, output) for its MT row tiles, merged through LDS at the end.
 // Per step and wave:
 //   S^T[key][row] = K[key][:] . Q[row][:]   A = K rows straight from the cache (16 B per lane),
 //                                            B = Q fragments (hi, lo) from LDS;
@@ -909,6 +883,12 @@ void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *o
 //                                            (hi + lo), A = V transposed through a per-wave LDS tile.
 // The contraction order of the second product is chosen so that no probability moves between lanes:
 // slot (lane group g, element e) stands for key 16*(e/4) + 4*g + e%4 of the step.
+//
+// The key splits of one (sequence, head, row group) are merged inside the kernel: every workgroup writes
+// its partial result (output, running max, sum) through to memory, then adds one to a counter; the
+// workgroup that finds the counter at nsplit - 1 reads all partial results back, merges them in split
+// order (deterministic) and writes the rows as hi/lo fragments of the O projection's input.  Nobody waits
+// for anybody.  The counter is reset by that last workgroup, so it is zero again at the next launch.
 // =====================================================================================================
 namespace {
 
@@ -917,38 +897,93 @@ namespace {
 typedef unsigned short __attribute__((may_alias)) u16_alias;
 struct __attribute__((may_alias)) u64_alias { unsigned int x, y; };
 
-template <int DH, int MT>
-__global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float *__restrict__ qrot, RowMeta meta,
-                                                   const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc,
-                                                   float *__restrict__ o_part, float *__restrict__ ml,
-                                                   int rows_per_seq, int n_heads, int cap, int nsplit, int H) {
+// Partial results cross workgroups (and so, possibly, L2 caches that are not coherent with each other) inside
+// one kernel: they are stored and loaded with the sc1 cache policy (agent scope: written through to, and read
+// from, memory that every compute unit sees), through buffer instructions bounded by the allocation size.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr int AUX_SC1 = 16;
+__device__ __forceinline__ rsrc_t make_rsrc(const void *p, size_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes > 0xFFFFFFF0ull ? (int)0xFFFFFFF0u : (int)bytes,
+                                             0x00020000);
+}
+__device__ __forceinline__ void st_sc1(rsrc_t r, size_t off, f32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, AUX_SC1);
+}
+__device__ __forceinline__ void st_sc1(rsrc_t r, size_t off, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)off, 0, AUX_SC1);
+}
+__device__ __forceinline__ f32x4 ld4_sc1(rsrc_t r, size_t off) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, AUX_SC1));
+}
+__device__ __forceinline__ float ld1_sc1(rsrc_t r, size_t off) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, AUX_SC1));
+}
+
+struct AttnArgs {
+    const u32x4 *qf;      // [batch][n_heads][MTQ][KS][hi, lo][64] query fragments
+    RowMeta meta;
+    const bf16_t *kc, *vc;
+    float *o_part, *ml;   // [row][head][split][DH], [row][head][split][max, sum]
+    unsigned opart_bytes, ml_bytes;
+    int *counters;        // [batch][n_heads][row groups], zero between launches
+    u32x4 *Xf;            // merged output: hi/lo fragments, K = n_heads * DH, MT_out activation tiles
+    int MT_out;
+    int rows_per_seq, MTQ, n_heads, cap, nsplit;
+};
+
+template <int DH, int MT, int NWV>
+__global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     constexpr int KS = DH / 32;            // contraction steps over the head dimension
     constexpr int DT = DH / 16;            // 16-wide output tiles over the head dimension
     constexpr int VS = DH * 2 + 8;         // bytes per key row of the transposed-read V tile (padded)
     constexpr int LPR = DH / 8;            // lanes that cover one cache row with 16 B each
     constexpr int VI = DH / 16;            // load instructions per 32-key V tile
+    constexpr int NTH = 64 * NWV;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ int s_last;
     u32x4 *qf = (u32x4 *)smem;                                   // [MT][KS][2][64]
-    unsigned char *vt_all = smem + (size_t)MT * KS * 2 * 64 * 16;  // [4 waves][32][VS]
+    unsigned char *vt_all = smem + (size_t)MT * KS * 2 * 64 * 16;  // [NWV waves][32][VS]
+    const int nsplit = a.nsplit, rows_per_seq = a.rows_per_seq, n_heads = a.n_heads, cap = a.cap;
     // blockIdx.x = key split + nsplit * (group of MT row tiles): sequences of more than MT*16 rows are
     // covered by several workgroups per (split, head), each with its own MT tiles of rows
-    const int s = blockIdx.x % nsplit, mt0 = (blockIdx.x / nsplit) * MT, h = blockIdx.y, b = blockIdx.z;
+    const int s = blockIdx.x % nsplit, grp = blockIdx.x / nsplit, mt0 = grp * MT, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, li = l & 15, lg = l >> 4;
     unsigned char *vt = vt_all + (size_t)wave * 32 * VS;
-    const float scale = rsqrtf((float)DH);
 
-    // key range of this workgroup, and the first step's K fragments (A operand) / V tile rows; the loads
-    // are in flight while the Q fragments are built
-    const int kv_end = meta.kv_end[b];
-    int chunk = (kv_end + nsplit - 1) / nsplit;
-    chunk = (chunk + 31) / 32 * 32;
-    const int j0 = s * chunk, j1 = min(kv_end, j0 + chunk);
-    const int nsteps = j1 > j0 ? (j1 - j0 + 31) / 32 : 0;
-    const bf16_t *kb = kc + ((size_t)b * n_heads + h) * cap * DH;
-    const bf16_t *vb = vc + ((size_t)b * n_heads + h) * cap * DH;
+    // everything that does not depend on the key range is requested first: the query fragments and the rows'
+    // visibility data travel while the sequence's length is fetched
+    const int kv_end = a.meta.kv_end[b];
+    u32x4 qreg[(MT * KS * 2 * 64 + NTH - 1) / NTH];
+#pragma unroll
+    for (int i = 0; i < (MT * KS * 2 * 64 + NTH - 1) / NTH; ++i) {
+        const int u = tid + i * NTH, mt = u / (KS * 2 * 64);
+        qreg[i] = (u < MT * KS * 2 * 64 && mt0 + mt < a.MTQ)
+                      ? a.qf[(((size_t)b * n_heads + h) * a.MTQ + mt0) * (KS * 2 * 64) + u]
+                      : (u32x4){0u, 0u, 0u, 0u};
+    }
+    int nvis[MT], base[MT];
+    uint64_t mask[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int row = (mt0 + mt) * 16 + li;
+        const bool ok = row < rows_per_seq;
+        const int r = b * rows_per_seq + (ok ? row : 0);
+        nvis[mt] = ok ? a.meta.row_nvis[r] : 0;
+        base[mt] = ok ? a.meta.row_base[r] : 0;
+        mask[mt] = ok ? a.meta.row_mask[r] : 0ull;
+    }
+    // The 32-key steps of the sequence are dealt out round-robin, first over the key splits and then over the
+    // waves: workgroup s, wave w takes steps s + nsplit * (w + NWV * k).  Which keys a wave starts with therefore
+    // does not depend on the sequence's length, and its first K fragments (A operand) / V tile rows are
+    // requested before that length has arrived (a step past the end is loaded from clamped rows and unused).
+    const int j1 = kv_end;
+    const int nsteps = (kv_end + 31) / 32;
+    const int tstride = nsplit * NWV;
+    const bf16_t *kb = a.kc + ((size_t)b * n_heads + h) * cap * DH;
+    const bf16_t *vb = a.vc + ((size_t)b * n_heads + h) * cap * DH;
     u32x4 kf[2][KS], vr[VI];
     auto load_step = [&](int st) {
-        const int k0 = j0 + st * 32;
+        const int k0 = st * 32;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int key = min(k0 + 16 * j + li, cap - 1);
@@ -962,45 +997,11 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
             vr[i] = *(const u32x4 *)(vb + (size_t)key * DH + (l % LPR) * 8);
         }
     };
-    if (wave < nsteps) load_step(wave);
+    load_step(s + nsplit * wave);
+#pragma unroll
+    for (int i = 0; i < (MT * KS * 2 * 64 + NTH - 1) / NTH; ++i)
+        if (tid + i * NTH < MT * KS * 2 * 64) qf[tid + i * NTH] = qreg[i];
 
-    // Q fragments (B operand): lane (row%16, g) holds Q[row][32*ks + 8*g .. +8], scaled, as hi and lo
-    for (int u = tid; u < MT * KS * 64; u += 256) {
-        const int lane = u & 63, ks = (u >> 6) % KS, mt = (u >> 6) / KS;
-        const int row = (mt0 + mt) * 16 + (lane & 15);
-        float y[8];
-        if (row < rows_per_seq) {
-            const float *q = qrot + (size_t)(b * rows_per_seq + row) * H + h * DH + ks * 32 + 8 * (lane >> 4);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] = q[e] * scale;
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] = 0.f;
-        }
-        uint32_t hi[8], lo[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            hi[e] = f2bf(y[e]);
-            lo[e] = f2bf(y[e] - bf2f(hi[e]));
-        }
-        u32x4 a, c;
-        a.x = hi[0] | (hi[1] << 16); a.y = hi[2] | (hi[3] << 16); a.z = hi[4] | (hi[5] << 16); a.w = hi[6] | (hi[7] << 16);
-        c.x = lo[0] | (lo[1] << 16); c.y = lo[2] | (lo[3] << 16); c.z = lo[4] | (lo[5] << 16); c.w = lo[6] | (lo[7] << 16);
-        qf[((mt * KS + ks) * 2 + 0) * 64 + lane] = a;
-        qf[((mt * KS + ks) * 2 + 1) * 64 + lane] = c;
-    }
-    // per-lane row metadata (lane's row in tile mt is mt*16 + li)
-    int nvis[MT], base[MT];
-    uint64_t mask[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int row = (mt0 + mt) * 16 + li;
-        const bool ok = row < rows_per_seq;
-        const int r = b * rows_per_seq + (ok ? row : 0);
-        nvis[mt] = ok ? meta.row_nvis[r] : 0;
-        base[mt] = ok ? meta.row_base[r] : 0;
-        mask[mt] = ok ? meta.row_mask[r] : 0ull;
-    }
     f32x4 acc_o[MT][DT];
     float m_run[MT], l_run[MT];
 #pragma unroll
@@ -1012,8 +1013,8 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
     }
     __syncthreads();
 
-    for (int st = wave; st < nsteps; st += 4) {
-        const int k0 = j0 + st * 32;
+    for (int st = s + nsplit * wave; st < nsteps; st += tstride) {
+        const int k0 = st * 32;
         // ---- S^T = K Q^T
         f32x4 sc[2][MT];
 #pragma unroll
@@ -1028,9 +1029,9 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
                 const bf16x8 ql = __builtin_bit_cast(bf16x8, qf[((mt * KS + ks) * 2 + 1) * 64 + l]);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, kf[j][ks]);
-                    sc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qh, sc[j][mt], 0, 0, 0);
-                    sc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ql, sc[j][mt], 0, 0, 0);
+                    const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[j][ks]);
+                    sc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qh, sc[j][mt], 0, 0, 0);
+                    sc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql, sc[j][mt], 0, 0, 0);
                 }
             }
         // ---- V tile -> LDS (row-major, padded), written as 8-byte halves
@@ -1038,11 +1039,11 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
         for (int i = 0; i < VI; ++i) {
             const int kl = i * (64 / LPR) + l / LPR;
             u64_alias *dst = (u64_alias *)(vt + (size_t)kl * VS + (l % LPR) * 16);
-            const bool in = k0 + kl < j1;   // rows past the chunk contribute exact zeros (0 * garbage could be NaN)
+            const bool in = k0 + kl < j1;   // rows past the end contribute exact zeros (0 * garbage could be NaN)
             dst[0] = in ? u64_alias{vr[i].x, vr[i].y} : u64_alias{0u, 0u};
             dst[1] = in ? u64_alias{vr[i].z, vr[i].w} : u64_alias{0u, 0u};
         }
-        if (st + 4 < nsteps) load_step(st + 4);   // kf / vr are free again: next step's loads overlap the rest
+        if (st + tstride < nsteps) load_step(st + tstride);   // kf / vr are free again: next step's loads overlap the rest
         // ---- mask, online softmax; probabilities stay in place as the B operand (hi, lo)
         bf16x8 ph[MT], pl[MT];
 #pragma unroll
@@ -1079,10 +1080,10 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
                 acc_o[mt][dt][0] *= alpha; acc_o[mt][dt][1] *= alpha;
                 acc_o[mt][dt][2] *= alpha; acc_o[mt][dt][3] *= alpha;
             }
-            u32x4 a, c;
-            a.x = hi[0] | (hi[1] << 16); a.y = hi[2] | (hi[3] << 16); a.z = hi[4] | (hi[5] << 16); a.w = hi[6] | (hi[7] << 16);
+            u32x4 x, c;
+            x.x = hi[0] | (hi[1] << 16); x.y = hi[2] | (hi[3] << 16); x.z = hi[4] | (hi[5] << 16); x.w = hi[6] | (hi[7] << 16);
             c.x = lo[0] | (lo[1] << 16); c.y = lo[2] | (lo[3] << 16); c.z = lo[4] | (lo[5] << 16); c.w = lo[6] | (lo[7] << 16);
-            ph[mt] = __builtin_bit_cast(bf16x8, a);
+            ph[mt] = __builtin_bit_cast(bf16x8, x);
             pl[mt] = __builtin_bit_cast(bf16x8, c);
         }
         // ---- O^T += V^T P^T ; A operand gathered from the LDS tile: lane (d%16, g), slot e -> key 16*(e/4)+4g+e%4
@@ -1097,9 +1098,9 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
                 const uint32_t v1 = vt16[(size_t)(ka + 1) * (VS / 2) + dt * 16 + li];
                 w[e2] = v0 | (v1 << 16);
             }
-            u32x4 a;
-            a.x = w[0]; a.y = w[1]; a.z = w[2]; a.w = w[3];
-            const bf16x8 va = __builtin_bit_cast(bf16x8, a);
+            u32x4 x;
+            x.x = w[0]; x.y = w[1]; x.z = w[2]; x.w = w[3];
+            const bf16x8 va = __builtin_bit_cast(bf16x8, x);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 acc_o[mt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, ph[mt], acc_o[mt][dt], 0, 0, 0);
@@ -1113,101 +1114,158 @@ __global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void k_attn_mfma(const float 
         l_run[mt] += __shfl_xor(l_run[mt], 16);
         l_run[mt] += __shfl_xor(l_run[mt], 32);
     }
-    // ---- merge the four waves through LDS (the Q / V regions are free now)
-    __syncthreads();
-    float *mo = (float *)smem;                         // [3 waves][MT][DT][64][4]
-    float *mm = mo + (size_t)3 * MT * DT * 256;        // [3 waves][MT][64][2]
-    if (wave > 0) {
+    // ---- merge the waves through LDS (the Q / V regions are free now), halving the number of live states per
+    //      round: waves [n/2, n) hand theirs to waves [0, n/2)
+    float *mo = (float *)smem;                                  // [NWV/2 waves][MT][DT][64][4]
+    float *mm = mo + (size_t)(NWV / 2) * MT * DT * 256;         // [NWV/2 waves][MT][64][2]
+#pragma unroll
+    for (int n = NWV; n > 1; n >>= 1) {
+        const int hn = n >> 1;
+        __syncthreads();
+        if (wave >= hn && wave < n) {
+            const int w = wave - hn;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+                    *(f32x4 *)(mo + ((((size_t)w * MT + mt) * DT + dt) * 64 + l) * 4) = acc_o[mt][dt];
+                mm[((w * MT + mt) * 64 + l) * 2 + 0] = m_run[mt];
+                mm[((w * MT + mt) * 64 + l) * 2 + 1] = l_run[mt];
+            }
+        }
+        __syncthreads();
+        if (wave < hn) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const float mw = mm[((wave * MT + mt) * 64 + l) * 2], lw = mm[((wave * MT + mt) * 64 + l) * 2 + 1];
+                const float M = fmaxf(m_run[mt], mw);
+                const float a0 = (m_run[mt] == -INFINITY) ? 0.f : __expf(m_run[mt] - M);
+                const float aw = (mw == -INFINITY) ? 0.f : __expf(mw - M);
+                l_run[mt] = l_run[mt] * a0 + lw * aw;
+                m_run[mt] = M;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const f32x4 o = *(const f32x4 *)(mo + ((((size_t)wave * MT + mt) * DT + dt) * 64 + l) * 4);
+                    acc_o[mt][dt][0] = acc_o[mt][dt][0] * a0 + aw * o[0];
+                    acc_o[mt][dt][1] = acc_o[mt][dt][1] * a0 + aw * o[1];
+                    acc_o[mt][dt][2] = acc_o[mt][dt][2] * a0 + aw * o[2];
+                    acc_o[mt][dt][3] = acc_o[mt][dt][3] * a0 + aw * o[3];
+                }
+            }
+        }
+    }
+    // ---- wave 0 writes this split's partial result through to memory
+    const rsrc_t ro = make_rsrc(a.o_part, a.opart_bytes), rm = make_rsrc(a.ml, a.ml_bytes);
+    if (wave == 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
+            const int row = (mt0 + mt) * 16 + li;
+            if (row < rows_per_seq) {
+                const size_t r = (size_t)b * rows_per_seq + row;
+                const size_t o = (((r * n_heads + h) * nsplit + s) * DH) * 4;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-                *(f32x4 *)(mo + ((((size_t)(wave - 1) * MT + mt) * DT + dt) * 64 + l) * 4) = acc_o[mt][dt];
-            mm[(((wave - 1) * MT + mt) * 64 + l) * 2 + 0] = m_run[mt];
-            mm[(((wave - 1) * MT + mt) * 64 + l) * 2 + 1] = l_run[mt];
+                for (int dt = 0; dt < DT; ++dt) st_sc1(ro, o + (dt * 16 + 4 * lg) * 4, acc_o[mt][dt]);
+                if (lg == 0) {
+                    const size_t pm = (((r * n_heads + h) * nsplit + s) * 2) * 4;
+                    st_sc1(rm, pm, m_run[mt]);
+                    st_sc1(rm, pm + 4, l_run[mt]);
+                }
+            }
+        }
+        // the partial results were written through (sc1), so nothing of this wave's is left in a cache to be
+        // written back: it is enough that the stores have been acknowledged before the counter moves
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        if (l == 0) {
+            int *cnt = a.counters + ((size_t)b * n_heads + h) * gridDim.x / nsplit + grp;
+            const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = old == nsplit - 1;
+            if (old == nsplit - 1) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     __syncthreads();
-    if (wave > 0) return;
+    if (!s_last) return;
+    // ---- the last workgroup of this (sequence, head, row group) merges the splits: one thread per (row, 8 dims)
+    for (int u = tid; u < MT * 16 * (DH / 8); u += NTH) {
+        const int row = mt0 * 16 + u / (DH / 8), d0 = (u % (DH / 8)) * 8;
+        if (row >= rows_per_seq) continue;
+        const size_t r = (size_t)b * rows_per_seq + row;
+        const size_t ob = ((r * n_heads + h) * nsplit) * DH * 4 + d0 * 4, mb = ((r * n_heads + h) * nsplit) * 2 * 4;
+        f32x4 oa[KOALA_NSPLIT_MAX], oc[KOALA_NSPLIT_MAX];
+        float ms[KOALA_NSPLIT_MAX], ls[KOALA_NSPLIT_MAX];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        float M = m_run[mt];
-#pragma unroll
-        for (int w = 0; w < 3; ++w) M = fmaxf(M, mm[((w * MT + mt) * 64 + l) * 2]);
-        const float a0 = (m_run[mt] == -INFINITY) ? 0.f : __expf(m_run[mt] - M);
-        float lsum = l_run[mt] * a0;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            acc_o[mt][dt][0] *= a0; acc_o[mt][dt][1] *= a0; acc_o[mt][dt][2] *= a0; acc_o[mt][dt][3] *= a0;
-        }
-#pragma unroll
-        for (int w = 0; w < 3; ++w) {
-            const float mw = mm[((w * MT + mt) * 64 + l) * 2];
-            if (mw == -INFINITY) continue;
-            const float aw = __expf(mw - M);
-            lsum += aw * mm[((w * MT + mt) * 64 + l) * 2 + 1];
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                const f32x4 o = *(const f32x4 *)(mo + ((((size_t)w * MT + mt) * DT + dt) * 64 + l) * 4);
-                acc_o[mt][dt][0] += aw * o[0]; acc_o[mt][dt][1] += aw * o[1];
-                acc_o[mt][dt][2] += aw * o[2]; acc_o[mt][dt][3] += aw * o[3];
+        for (int q = 0; q < KOALA_NSPLIT_MAX; ++q) {
+            if (q < nsplit) {
+                oa[q] = ld4_sc1(ro, ob + (size_t)q * DH * 4);
+                oc[q] = ld4_sc1(ro, ob + (size_t)q * DH * 4 + 16);
+                ms[q] = ld1_sc1(rm, mb + q * 8);
+                ls[q] = ld1_sc1(rm, mb + q * 8 + 4);
+            } else {
+                oa[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                oc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                ms[q] = -INFINITY;
+                ls[q] = 0.f;
             }
         }
-        const int row = (mt0 + mt) * 16 + li;
-        if (row < rows_per_seq) {
-            const size_t r = (size_t)b * rows_per_seq + row;
-            float *o = o_part + ((r * n_heads + h) * nsplit + s) * DH;
+        float Mx = -INFINITY;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) *(f32x4 *)(o + dt * 16 + 4 * lg) = acc_o[mt][dt];
-            if (lg == 0) {
-                float *p = ml + ((r * n_heads + h) * nsplit + s) * 2;
-                p[0] = M;
-                p[1] = lsum;
-            }
+        for (int q = 0; q < KOALA_NSPLIT_MAX; ++q) Mx = fmaxf(Mx, ms[q]);
+        f32x4 ya = {0.f, 0.f, 0.f, 0.f}, yc = {0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
+#pragma unroll
+        for (int q = 0; q < KOALA_NSPLIT_MAX; ++q) {
+            const float w = (ms[q] == -INFINITY) ? 0.f : __expf(ms[q] - Mx);
+            den += w * ls[q];
+            ya += w * oa[q];
+            yc += w * oc[q];
         }
+        const float inv = 1.0f / den;
+        const float y[8] = {ya[0] * inv, ya[1] * inv, ya[2] * inv, ya[3] * inv, yc[0] * inv, yc[1] * inv, yc[2] * inv,
+                            yc[3] * inv};
+        store_frag8(a.Xf, a.MT_out, (int)r, h * DH + d0, y);
     }
 }
 
-template <int DH, int MT>
-void launch_attn(hipStream_t st, const float *qrot, const RowMeta &meta, const void *kc, const void *vc,
-                 float *o_part, float *ml, int batch, int rows_per_seq, int n_heads, int cap, int nsplit) {
+template <int DH, int MT, int NWV>
+void launch_attn(hipStream_t st, const AttnArgs &a, int batch) {
     constexpr int KS = DH / 32, DT = DH / 16, VS = DH * 2 + 8;
-    const size_t main_b = (size_t)MT * KS * 2 * 64 * 16 + (size_t)4 * 32 * VS;
-    const size_t merge_b = (size_t)3 * MT * DT * 256 * 4 + (size_t)3 * MT * 64 * 2 * 4;
+    const size_t main_b = (size_t)MT * KS * 2 * 64 * 16 + (size_t)NWV * 32 * VS;
+    const size_t merge_b = (size_t)(NWV / 2) * MT * DT * 256 * 4 + (size_t)(NWV / 2) * MT * 64 * 2 * 4;
     const size_t sm = main_b > merge_b ? main_b : merge_b;
     static bool done = false;
     if (!done) {
-        (void)hipFuncSetAttribute((const void *)k_attn_mfma<DH, MT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        (void)hipFuncSetAttribute((const void *)k_attn_tree<DH, MT, NWV>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)sm);
         done = true;
     }
-    const int groups = (rows_per_seq + MT * 16 - 1) / (MT * 16);   // row-tile groups per (split, head)
-    k_attn_mfma<DH, MT><<<dim3(nsplit * groups, n_heads, batch), 256, sm, st>>>(
-        qrot, meta, (const bf16_t *)kc, (const bf16_t *)vc, o_part, ml, rows_per_seq, n_heads, cap, nsplit,
-        n_heads * DH);
+    const int groups = (a.rows_per_seq + MT * 16 - 1) / (MT * 16);   // row-tile groups per (split, head)
+    k_attn_tree<DH, MT, NWV><<<dim3(a.nsplit * groups, a.n_heads, batch), 64 * NWV, sm, st>>>(a);
 }
 
 }  // namespace
 
 namespace kb {
 
-// rows_per_seq <= 64.  Writes per-split partial outputs (o_part, ml) like the generic kernel.
-void attention_mfma(hipStream_t st, const float *qrot, const RowMeta &meta, const void *kc, const void *vc,
-                    float *o_part, float *ml, int batch, int rows_per_seq, int n_heads, int head_dim, int cap,
-                    int nsplit) {
-    // more than 32 rows: two workgroups of two row tiles each per (split, head) (the four-tile kernel needs so
-    // many registers that only one workgroup fits a CU).  KOALA_ATTN_MT = 1, 2 or 4 forces the tiles per workgroup.
-    static const int forced = getenv("KOALA_ATTN_MT") ? atoi(getenv("KOALA_ATTN_MT")) : 0;
-    int MT = rows_per_seq <= 16 ? 1 : 2;
-    if (forced == 1 || (forced == 2 && rows_per_seq > 16) || (forced == 4 && rows_per_seq > 32)) MT = forced;
-#define KOALA_ATT(DHV, MTV) \
-    launch_attn<DHV, MTV>(st, qrot, meta, kc, vc, o_part, ml, batch, rows_per_seq, n_heads, cap, nsplit)
+// rows_per_seq <= 64.  counters: batch * n_heads * 4 ints, zero before the first launch (the kernel leaves them
+// zero).  The merged rows are written as fragments Xf (MT_out activation tiles) of the O projection's input.
+void attention_tree(hipStream_t st, const void *qf, const RowMeta &meta, const void *kc, const void *vc, float *o_part,
+                    size_t opart_bytes, float *ml, size_t ml_bytes, int *counters, void *Xf, int MT_out, int batch,
+                    int rows_per_seq, int n_heads, int head_dim, int cap, int nsplit) {
+    AttnArgs a{};
+    a.qf = (const u32x4 *)qf; a.meta = meta; a.kc = (const bf16_t *)kc; a.vc = (const bf16_t *)vc;
+    a.o_part = o_part; a.ml = ml;
+    a.opart_bytes = (unsigned)std::min<size_t>(opart_bytes, 0xFFFFFFF0u);
+    a.ml_bytes = (unsigned)std::min<size_t>(ml_bytes, 0xFFFFFFF0u);
+    a.counters = counters; a.Xf = (u32x4 *)Xf; a.MT_out = MT_out;
+    a.rows_per_seq = rows_per_seq; a.MTQ = (rows_per_seq + 15) / 16; a.n_heads = n_heads; a.cap = cap; a.nsplit = nsplit;
+    // up to 16 rows: one row tile per workgroup; more: two (sequences of more than 32 rows take two workgroups
+    // per split and head)
+    const int MT = rows_per_seq <= 16 ? 1 : 2;
     if (head_dim == 128) {
-        if (MT == 1) KOALA_ATT(128, 1); else if (MT == 2) KOALA_ATT(128, 2); else KOALA_ATT(128, 4);
+        if (MT == 1) launch_attn<128, 1, 8>(st, a, batch); else launch_attn<128, 2, 8>(st, a, batch);
     } else {
-        if (MT == 1) KOALA_ATT(64, 1); else if (MT == 2) KOALA_ATT(64, 2); else KOALA_ATT(64, 4);
+        if (MT == 1) launch_attn<64, 1, 8>(st, a, batch); else launch_attn<64, 2, 8>(st, a, batch);
     }
-#undef KOALA_ATT
 }
 
 }  // namespace kb

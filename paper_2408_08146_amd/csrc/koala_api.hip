@@ -98,11 +98,16 @@ size_t carve(koala_ctx *c, char *base) {
     c->x = w.take<float>((size_t)R * H);
     c->act = w.take<float>((size_t)R * std::max(2 * H, F));
     c->qkv = w.take<float>((size_t)R * 3 * H);
-    c->qrot = w.take<float>((size_t)R * H);
+    // also holds the bf16 path's query fragments, whose rows are padded to 16 per sequence
+    c->qrot = w.take<float>((size_t)c->max_batch * ((R / c->max_batch + 15) / 16 * 16) * H);
+    c->qf = c->qrot;
     c->attn_out = w.take<float>((size_t)R * H);
     c->gu = w.take<float>((size_t)R * 2 * F);
     c->o_part = w.take<float>((size_t)R * H * ns);
     c->ml = w.take<float>((size_t)R * s.n_heads * ns * 2);
+    c->opart_bytes = (size_t)R * H * ns * sizeof(float);
+    c->ml_bytes = (size_t)R * s.n_heads * ns * 2 * sizeof(float);
+    c->attn_cnt = w.take<int>((size_t)c->max_batch * s.n_heads * 4);
     c->logits = w.take<float>((size_t)R * V);
     c->fhat = w.take<float>((size_t)c->max_batch * T * H);
     c->topk_val = w.take<float>((size_t)R * KOALA_TOPK_MAX);
@@ -237,16 +242,15 @@ void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_se
     int S;
     if (fused) {
         const LaunchEvents ev = timed_launch(c, 3.0 * H * H * 2.0);
-        kb::gemm_rows_qkv(st, lw[1], c->xf, H, MT, hidden_scale(c), rows, c->meta, c->qrot, kc, vc, H, s.n_heads,
-                          s.head_dim, c->kv.capacity, c->n_cu, ev.start, ev.stop);
+        kb::gemm_rows_qkv(st, lw[1], c->xf, H, MT, hidden_scale(c), rows, rows_per_seq, c->meta, c->qf, kc, vc, H,
+                          s.n_heads, s.head_dim, c->kv.capacity, c->n_cu, ev.start, ev.stop);
     } else {
         S = bf_gemm(c, st, lw[1], 3 * H, H, MT);
-        kb::rope_append(st, c->part, S, Mp, 3 * H, hidden_scale(c), c->meta, c->qrot, kc, vc, rows, H, s.n_heads,
-                        s.head_dim, c->kv.capacity);
+        kb::rope_append(st, c->part, S, Mp, 3 * H, hidden_scale(c), c->meta, c->qf, kc, vc, rows, H, s.n_heads,
+                        s.head_dim, c->kv.capacity, rows_per_seq);
     }
-    kb::attention_mfma(st, c->qrot, c->meta, kc, vc, c->o_part, c->ml, batch, rows_per_seq, s.n_heads, s.head_dim,
-                       c->kv.capacity, ns);
-    kb::attn_combine_frag(st, c->o_part, c->ml, c->xf, MT, rows, s.n_heads, ns, s.head_dim);
+    kb::attention_tree(st, c->qf, c->meta, kc, vc, c->o_part, c->opart_bytes, c->ml, c->ml_bytes, c->attn_cnt, c->xf,
+                       MT, batch, rows_per_seq, s.n_heads, s.head_dim, c->kv.capacity, ns);
     S = fused ? bf_gemm_rows(c, st, lw[2], c->xf, H, H, MT) : bf_gemm(c, st, lw[2], H, H, MT);
     kb::fold(st, c->x, H, c->part, S, Mp, H, 1, rows, H, lw[3], c->xf, MT, c->row_sums, c->max_rows);
     if (fused) {
@@ -407,6 +411,10 @@ koala_status koala_bind(koala_ctx *c, const koala_weights *w, const koala_kv *kv
         if (c->bound) carve(c, c->ws);
         return fail(c, KOALA_E_WORKSPACE, "workspace too small");
     }
+    if (c->opart_bytes > 0xFFFFFFF0ull) {
+        c->bound = false;
+        return fail(c, KOALA_E_UNSUPPORTED, "attention partial results exceed 4 GiB: reduce max_batch");
+    }
     c->w = *w;
     c->layer_w.assign(w->layer_w, w->layer_w + n_lw);
     c->draft_w.assign(w->draft_w, w->draft_w + n_dw);
@@ -436,6 +444,7 @@ koala_status koala_bind(koala_ctx *c, const koala_weights *w, const koala_kv *kv
         float *unused = nullptr;   // looks up this device's copy of the static scratch array
         e = static_scratch(&unused);
     }
+    if (e == hipSuccess) e = hipMemset(c->attn_cnt, 0, (size_t)c->max_batch * c->shape.n_heads * 4 * sizeof(int));
     if (e == hipSuccess) {
         int dev = 0;
         hipDeviceProp_t prop;

@@ -69,6 +69,9 @@ struct koala_ctx {
     void *xf, *xf2;   // xf2: input of the down projection (written by the gate/up projection's epilogue)
     float *part;
     size_t xf_bytes, part_bytes;
+    void *qf;          // query fragments of the bf16 attention (in the buffer of qrot)
+    int *attn_cnt;     // arrival counters of the attention kernel's split merge
+    size_t opart_bytes, ml_bytes;
     float *cand_val;   // [rows][ceil(V/1024)][16] top-k candidates of the LM-head epilogue
     int *cand_idx;
     float *row_sums;   // [64 chunks][rows] sums of squares per 512-column chunk (RMSNorm row scale)
@@ -195,26 +198,28 @@ void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int N
 // Row-group GEMM (one workgroup per few 16-row groups of the weights and K range, waves take 64-k tiles in
 // turn; n_cu = compute units of the device, which sets the groups per workgroup), MTT = 1, 2 or 4:
 // _partial: P[S][MTT*16][Npad] partial sums, like gemm_packed;  _qkv (S = 1): row scale, rotary embedding,
-// queries to qrot, keys/values into their cache slots (W_q, W_k rows pair-interleaved);  _swiglu (S = 1): row
+// queries as attention fragments qf, keys/values into their cache slots (W_q, W_k rows pair-interleaved);  _swiglu (S = 1): row
 // scale, SiLU(gate) * up as hi/lo fragments Xo of the down projection's input
 void gemm_rows_partial(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S,
                        hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 void gemm_rows_qkv(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const NormScale &ns, int rows,
-                   const RowMeta &meta, float *qrot, void *kc, void *vc, int H, int n_heads, int head_dim, int cap, int n_cu,
-                   hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+                   int rows_per_seq, const RowMeta &meta, void *qf, void *kc, void *vc, int H, int n_heads, int head_dim,
+                   int cap, int n_cu, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 void gemm_rows_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const NormScale &ns, int rows,
                       void *Xo, int F, int n_cu, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 // v = (mode 1: x +) sum of partials (mode 0: x as is); x <- v for modes 1, 2; Xf (may be NULL) receives the
 // fragments of gain * v (gain NULL: v); sums (may be NULL) the sums of squares of v per 512-column chunk
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,
           const void *gain, void *Xf, int MT, float *sums, int srows);
+// qf: query fragments [batch][n_heads][ceil(rows_per_seq/16)][head_dim/32][hi, lo][64 lanes] x 16 B, times
+// 1/sqrt(head_dim)
 void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, const RowMeta &meta,
-                 float *qrot, void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap);
-void attention_mfma(hipStream_t st, const float *qrot, const RowMeta &meta, const void *kc, const void *vc,
-                    float *o_part, float *ml, int batch, int rows_per_seq, int n_heads, int head_dim, int cap,
-                    int nsplit);
-void attn_combine_frag(hipStream_t st, const float *o_part, const float *ml, void *Xf, int MT, int M, int n_heads,
-                       int nsplit, int head_dim);
+                 void *qf, void *kc, void *vc, int rows, int H, int n_heads, int head_dim, int cap, int rows_per_seq);
+// tree-masked attention over the cache, key splits merged in the kernel, rows written as fragments Xf of the
+// O projection's input; counters: max_batch * n_heads * 4 ints, zero before the first launch
+void attention_tree(hipStream_t st, const void *qf, const RowMeta &meta, const void *kc, const void *vc, float *o_part,
+                    size_t opart_bytes, float *ml, size_t ml_bytes, int *counters, void *Xf, int MT_out, int batch,
+                    int rows_per_seq, int n_heads, int head_dim, int cap, int nsplit);
 void silu_frag(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, void *Xf, int MT, int M,
                int F);
 void resblock_p(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int M, int H);
