@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
 // (16 U output columns) over a K range; its waves take the 64-k tiles of that range in turn (wave w:
 // tiles w, w + KW, ...) and every wave loads both operands of its tiles straight into MFMA registers -
 // the U 2 KiB weight pieces and the matching hi/lo activation fragments - so the streaming loop has no
-// barrier and no LDS traffic.  The waves' accumulators meet once, in LDS, and are added in wave order
+// barrier and no LDS traffic.  The waves' accumulators meet at the end, in LDS, and are added in a fixed order
 // (deterministic).  With S = 1 the workgroup then holds finished outputs and applies the consumer's
 // element-wise step itself:
 //   EPI_PARTIAL  store fp32 partial sums P[sp][row][n] (split-K, S >= 1), folded by a later kernel;
@@ -161,6 +161,9 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
 // RS > 1: RS waves share a tile position and split the MT * RS activation tiles between them.
 // ---------------------------------------------------------------------------------------------
 enum { EPI_PARTIAL = 0, EPI_QKV = 1, EPI_SWIGLU = 2 };
+
+// whether the wave accumulators of k_gemm_rows are combined in halving rounds (they do not all fit in LDS at once)
+constexpr bool gemm_rows_tree(int U, int MT, int NW) { return NW * U * MT > 96; }
 
 struct GemmEpi {
     float *P;           // EPI_PARTIAL
@@ -181,9 +184,11 @@ template <int U, int MT, int RS, int NW, int PF, int EPI>
 __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
                                                        int Npad, int K, int S, GemmEpi e) {
     constexpr int MTT = MT * RS, KW = NW / RS;
+    constexpr bool TREE = gemm_rows_tree(U, MT, NW);
+    constexpr int NRED = TREE ? NW / 2 : NW;
     extern __shared__ __attribute__((aligned(16))) unsigned char gsm[];
-    f32x4 *red = (f32x4 *)gsm;                                     // [NW][U][MT][64]
-    float *cs = (float *)(gsm + (size_t)NW * U * MT * 64 * 16);    // EPI_QKV: [MTT*16][U][8][cos, sin]
+    f32x4 *red = (f32x4 *)gsm;                                     // [NRED][U][MT][64]
+    float *cs = (float *)(gsm + (size_t)NRED * U * MT * 64 * 16);    // EPI_QKV: [MTT*16][U][8][cos, sin]
     const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
     const int kw = wave / RS, mh = wave % RS;
     const int nunits = Npad / 16, nwg = (nunits + U - 1) / U;
@@ -274,10 +279,42 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
             }
         }
     }
+    // The waves' sums meet in LDS.  Where it fits (TREE false) every wave stores its accumulators and the epilogue
+    // adds the KW copies of a piece in wave order; otherwise the number of live accumulators is halved per round
+    // (waves [n/2, n) hand theirs to waves [0, n/2)) and waves 0 .. RS-1 store the totals.  Either order is fixed,
+    // so results are bit-for-bit repeatable.
+    if (!TREE) {
 #pragma unroll
-    for (int j = 0; j < U; ++j)
+        for (int j = 0; j < U; ++j)
 #pragma unroll
-        for (int m = 0; m < MT; ++m) red[((size_t)(wave * U + j) * MT + m) * 64 + l] = acc[j][m];
+            for (int m = 0; m < MT; ++m) red[((size_t)(wave * U + j) * MT + m) * 64 + l] = acc[j][m];
+    } else {
+#pragma unroll
+        for (int n = NW; n > RS; n >>= 1) {
+            const int hn = n >> 1;
+            if (n < NW) __syncthreads();
+            if (wave >= hn && wave < n) {
+#pragma unroll
+                for (int j = 0; j < U; ++j)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) red[((size_t)((wave - hn) * U + j) * MT + m) * 64 + l] = acc[j][m];
+            }
+            __syncthreads();
+            if (wave < hn) {
+#pragma unroll
+                for (int j = 0; j < U; ++j)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) acc[j][m] += red[((size_t)(wave * U + j) * MT + m) * 64 + l];
+            }
+        }
+        __syncthreads();
+        if (wave < RS) {
+#pragma unroll
+            for (int j = 0; j < U; ++j)
+#pragma unroll
+                for (int m = 0; m < MT; ++m) red[((size_t)(wave * U + j) * MT + m) * 64 + l] = acc[j][m];
+        }
+    }
     __syncthreads();
 
     // output piece (j, mtt): weight rows of unit j x activation tile mtt; lane (li, lg) holds columns
@@ -286,8 +323,10 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
         const int j = u / MTT, mtt = u % MTT, umh = mtt / MT, um = mtt % MT;
         if (ug0 + j >= nunits) continue;
         f32x4 v = red[((size_t)(umh * U + j) * MT + um) * 64 + l];
+        if (!TREE) {
 #pragma unroll
-        for (int q = 1; q < KW; ++q) v += red[((size_t)((q * RS + umh) * U + j) * MT + um) * 64 + l];
+            for (int q = 1; q < KW; ++q) v += red[((size_t)((q * RS + umh) * U + j) * MT + um) * 64 + l];
+        }
         const int row = mtt * 16 + li, n = (ug0 + j) * 16 + 4 * lg;
         if (EPI == EPI_PARTIAL) {
             *(f32x4 *)(e.P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = v;
@@ -664,7 +703,7 @@ inline int cdiv(size_t a, size_t b) { return (int)((a + b - 1) / b); }
 template <int U, int MT, int RS, int NW, int PF, int EPI>
 void launch_gemm_rows(hipStream_t st, const void *Wp, const void *Xf, int Npad, int K, int S, const GemmEpi &e,
                       hipEvent_t ev_start, hipEvent_t ev_stop) {
-    const size_t sm = (size_t)NW * U * MT * 64 * 16 + (EPI == EPI_QKV ? (size_t)MT * RS * 16 * U * 8 * 2 * 4 : 0);
+    const size_t sm = (size_t)(gemm_rows_tree(U, MT, NW) ? NW / 2 : NW) * U * MT * 64 * 16 + (EPI == EPI_QKV ? (size_t)MT * RS * 16 * U * 8 * 2 * 4 : 0);
     static bool done = false;
     if (!done) {
         (void)hipFuncSetAttribute((const void *)k_gemm_rows<U, MT, RS, NW, PF, EPI>,
@@ -680,14 +719,15 @@ void launch_gemm_rows(hipStream_t st, const void *Wp, const void *Xf, int Npad, 
                                                                       e);
 }
 
-// MTT = 1, 2 or 4 activation tiles (four: two waves per tile position, two tiles each)
+// MTT = 1, 2 or 4 activation tiles
 template <int U, int EPI>
 void dispatch_gemm_rows_u(hipStream_t st, const void *Wp, const void *Xf, int Npad, int K, int MTT, int S,
                           const GemmEpi &e, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    constexpr int PF = U >= 7 ? 1 : 2;   // tiles in flight per wave; seven groups with two leave no registers for a second
+    // tiles in flight per wave: two, or one where the registers do not hold a second (seven groups, four tiles)
+    constexpr int PF = U >= 7 ? 1 : 2;
     if (MTT == 1) launch_gemm_rows<U, 1, 1, 8, 2, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
     else if (MTT == 2) launch_gemm_rows<U, 2, 1, 8, PF, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
-    else launch_gemm_rows<U, 2, 2, 8, PF, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
+    else launch_gemm_rows<U, 4, 1, 8, 1, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
 }
 
 // 16-row groups per workgroup for an S = 1 launch over Npad rows: the smallest supported count that covers the
@@ -963,6 +1003,7 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     }
     int nvis[MT], base[MT];
     uint64_t mask[MT];
+    int nvis_min = 0x7fffffff;   // keys below this are visible to every row of the workgroup: no masking there
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int row = (mt0 + mt) * 16 + li;
@@ -971,7 +1012,11 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
         nvis[mt] = ok ? a.meta.row_nvis[r] : 0;
         base[mt] = ok ? a.meta.row_base[r] : 0;
         mask[mt] = ok ? a.meta.row_mask[r] : 0ull;
+        if (ok) nvis_min = min(nvis_min, nvis[mt]);
     }
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) nvis_min = min(nvis_min, __shfl_xor(nvis_min, o));
+    nvis_min = __builtin_amdgcn_readfirstlane(nvis_min);
     // The 32-key steps of the sequence are dealt out round-robin, first over the key splits and then over the
     // waves: workgroup s, wave w takes steps s + nsplit * (w + NWV * k).  Which keys a wave starts with therefore
     // does not depend on the sequence's length, and its first K fragments (A operand) / V tile rows are
@@ -1050,15 +1095,23 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
         for (int mt = 0; mt < MT; ++mt) {
             float p[8];
             float tmax = -INFINITY;
+            if (k0 + 32 <= nvis_min) {   // same for the whole workgroup
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int key = k0 + 16 * (e >> 2) + 4 * lg + (e & 3);
-                const unsigned rel = (unsigned)(key - base[mt]);   // negative differences wrap to >= 64
-                const uint32_t half = rel < 32u ? (uint32_t)mask[mt] : (uint32_t)(mask[mt] >> 32);
-                const bool bit = rel < 64u && ((half >> (rel & 31u)) & 1u);
-                const bool vis = key < j1 && (key < nvis[mt] || bit);
-                p[e] = vis ? sc[e >> 2][mt][e & 3] : -INFINITY;
-                tmax = fmaxf(tmax, p[e]);
+                for (int e = 0; e < 8; ++e) {
+                    p[e] = sc[e >> 2][mt][e & 3];
+                    tmax = fmaxf(tmax, p[e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int key = k0 + 16 * (e >> 2) + 4 * lg + (e & 3);
+                    const unsigned rel = (unsigned)(key - base[mt]);   // negative differences wrap to >= 64
+                    const uint32_t half = rel < 32u ? (uint32_t)mask[mt] : (uint32_t)(mask[mt] >> 32);
+                    const bool bit = rel < 64u && ((half >> (rel & 31u)) & 1u);
+                    const bool vis = key < j1 && (key < nvis[mt] || bit);
+                    p[e] = vis ? sc[e >> 2][mt][e & 3] : -INFINITY;
+                    tmax = fmaxf(tmax, p[e]);
+                }
             }
             tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
@@ -1261,11 +1314,16 @@ void attention_tree(hipStream_t st, const void *qf, const RowMeta &meta, const v
     // up to 16 rows: one row tile per workgroup; more: two (sequences of more than 32 rows take two workgroups
     // per split and head)
     const int MT = rows_per_seq <= 16 ? 1 : 2;
+    static const int forced = getenv("KOALA_ATTN_WAVES") ? atoi(getenv("KOALA_ATTN_WAVES")) : 0;   // tuning: 4 or 8
+    const int nwv = forced == 4 || forced == 8 ? forced : 8;
+#define KOALA_ATT(DHV, MTV) \
+    { if (nwv == 8) launch_attn<DHV, MTV, 8>(st, a, batch); else launch_attn<DHV, MTV, 4>(st, a, batch); }
     if (head_dim == 128) {
-        if (MT == 1) launch_attn<128, 1, 8>(st, a, batch); else launch_attn<128, 2, 8>(st, a, batch);
+        if (MT == 1) KOALA_ATT(128, 1) else KOALA_ATT(128, 2)
     } else {
-        if (MT == 1) launch_attn<64, 1, 8>(st, a, batch); else launch_attn<64, 2, 8>(st, a, batch);
+        if (MT == 1) KOALA_ATT(64, 1) else KOALA_ATT(64, 2)
     }
+#undef KOALA_ATT
 }
 
 }  // namespace kb

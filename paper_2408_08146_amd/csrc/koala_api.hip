@@ -236,7 +236,9 @@ void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_se
                         void *kc, void *vc) {
     const koala_shape &s = c->shape;
     const int rows = batch * rows_per_seq, H = s.hidden, F = s.ffn, MT = kb::mt_of(rows), Mp = MT * 16;
-    const int ns = c->attn_ns;
+    // key splits of the attention: as many as keep the launch within one workgroup per compute unit (sequences of
+    // more than 32 rows take two workgroups per split and head), at most the count the workspace was carved for
+    const int ns = std::max(1, std::min(c->attn_ns, c->n_cu / (s.n_heads * batch * (rows_per_seq > 32 ? 2 : 1))));
     const bool fused = MT <= 4;
     fold_pending(c, st, rows, MT, lw[0]);
     int S;
