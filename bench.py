@@ -49,7 +49,8 @@ def device_weights(cfg, torch, K, dev):
     def layer():
         wqkv = KO.fragment_major(mat(3 * H, H))
         wo = KO.fragment_major(mat(H, H))
-        gu = mat(2 * F, H)                                       # rows already interleaved: random anyway
+        gu = mat(2 * F, H)                                       # rows already in the library's order (gate/up
+                                                                 # interleaved, rotary pairs adjacent): random anyway
         wgu = KO.fragment_major(gu)
         wd = KO.fragment_major(mat(H, F))
         one = torch.ones(H, dtype=torch.bfloat16, device=dev)
@@ -157,6 +158,8 @@ def generation_bench(args):
                          tokens_per_s=st["tokens"] / dt, ms_per_iteration=dt / st["iterations"] * 1e3,
                          mean_tokens_per_iteration=st["tokens"] / st["iterations"],
                          accept_hist=st["accept_hist"][:D + 1], first_tokens=out[:4].tolist())
+    spec.close()
+    plain.close()
     ratio = res["speculative"]["tokens_per_s"] / res["plain"]["tokens_per_s"]
     print(json.dumps({
         "metric": "speedup_over_autoregressive_decoding", "value": ratio, "unit": "x", "n_gpus": 1,
@@ -219,9 +222,23 @@ def cpu_baseline(cfg, tree, K, levels):
     passes = 1 + sum(1 for n in levels[1:tree.depth] if n > 0)
     t_layer = (t_full - t_head) / Ls
     est = cfg["n_layers"] * t_layer + t_head + passes * t_pass
+    one_thread = None
     try:
         import threadpoolctl
         threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] + [1])
+        with threadpoolctl.threadpool_limits(limits=1):          # the same sample once on a single core
+            t0 = time.perf_counter()
+            oracle.verify_tree(c, Wt, tc, C, tt, tree.parent, dt)
+            t1 = time.perf_counter()
+            oracle.verify_tree(c, Wt, tc, C, tt, tree.parent, dt, n_layers=0)
+            t2 = time.perf_counter()
+            oracle.eagle_expand(c, Wt, Wd, dc, C, feat, tt[:1], np.array([-1], np.int32), np.array([0], np.int32),
+                                np.array([], np.int32), dt)
+            _ = oracle.topk_desc(Wt.f32("lm_head") @ feat[0], 4)
+            t3 = time.perf_counter()
+        est1 = cfg["n_layers"] * ((t1 - t0) - (t2 - t1)) / Ls + (t2 - t1) + passes * (t3 - t2)
+        one_thread = dict(value=1.0 / est1, unit="iterations/s", cores=1, seconds_per_iteration_est=est1,
+                          sample="the same sample, one repetition, BLAS limited to one thread")
     except Exception:
         threads = os.cpu_count()
     return dict(value=1.0 / est, unit="iterations/s", cores=int(threads), kind="oracle",
@@ -230,7 +247,25 @@ def cpu_baseline(cfg, tree, K, levels):
                         f"EAGLE draft pass ({t_pass:.2f}s), scaled "
                         f"linearly to {cfg['n_layers']} layers and {passes} draft passes; "
                         f"host has {os.cpu_count()} logical CPUs"),
-                seconds_per_iteration_est=est)
+                seconds_per_iteration_est=est, single_thread=one_thread)
+
+
+def gpu_state():
+    """Clocks, power and performance level of GPU 0 as rocm-smi reports them (None if it cannot be run)."""
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "-d", "0", "--showclocks", "--showpower", "--showperflevel", "--json"],
+                           capture_output=True, text=True, timeout=20)
+        d = json.loads(r.stdout)
+        card = d[sorted(d.keys())[0]]
+        keep = {}
+        for k, v in card.items():
+            kl = k.lower()
+            if any(t in kl for t in ("sclk", "mclk", "fclk", "socclk", "power", "performance level")):
+                keep[k] = v
+        return keep or None
+    except Exception:
+        return None
 
 
 def main():
@@ -393,6 +428,7 @@ def main():
     torch.cuda.synchronize()
     stream_read_gbs = KO.measure_stream_read(probe, repeats=5)
     del probe
+    state = gpu_state()                                          # right after sustained work
 
     # dominant kernel: the weight-streaming GEMM; HIP events around each of its launches
     ctx.profile_begin(8192)
@@ -407,7 +443,7 @@ def main():
     vb, db = algorithmic_bytes(cfg, T, ctx_lens, D, K, levels, cfg["medusa_heads"])
     achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
     traffic = None                                               # HBM bytes per launch from the rocprofv3 PMC runs
-    tfile = os.path.join(ROOT, "profiles", f"traffic_k_gemm_packed_{args.config}.txt")
+    tfile = os.path.join(ROOT, "profiles", f"traffic_weight_gemm_{args.config}.txt")
     if os.path.exists(tfile) and K == 1 and not args.layers:
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch="):
@@ -429,7 +465,9 @@ def main():
         "verify_bytes": vb, "draft_bytes": db,
         "verify_hbm_frac": vb / (parts[1] * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "iteration_hbm_frac": (vb + db) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"bound": "hbm", "kernel": "k_gemm_packed", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "gpu_state": state,
+        "roofline": {"bound": "hbm", "kernel": "k_gemm_rows (weight-streaming GEMM; k_gemm_packed for the LM head)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "launches_timed": gemm_launches, "avg_launch_us": gemm_ms * 1e3 / max(1, gemm_launches),
                      "avg_launch_bytes": gemm_bytes / max(1, gemm_launches)},
@@ -442,6 +480,7 @@ def main():
                                           "tokens_per_s": 1e3 / ms_per_step * paper_l}
     if not args.no_cpu_baseline and eagle and B == 1:
         out["cpu_baseline"] = cpu_baseline(cfg, tree, K, levels)
+    ctx.close()
     print(json.dumps(out))
 
 

@@ -11,7 +11,9 @@
  * General rules
  *  - "device" pointers are HIP device memory owned by the caller; "host"
  *    pointers are ordinary host memory.  The library allocates no device
- *    memory: all scratch lives in the caller's workspace (koala_bind).
+ *    memory: all scratch lives in the caller's workspace (koala_bind), except
+ *    for the fixed array of koala_accept_sample_static, which is part of the
+ *    loaded library itself.
  *  - Tensors are dense, row-major, 16-byte aligned.  Weights and KV caches are
  *    stored in the model dtype (fp32 or bfloat16); features, logits and scores
  *    are always fp32; token ids, node ids and lengths are int32.
@@ -297,10 +299,11 @@ koala_status koala_generate_sample(koala_ctx *ctx, void *hip_stream, const float
 /* Measurement aid (not part of the method): the rate at which this device streams `bytes` of
  * `buffer` (device memory, 16-byte aligned) through a plain read kernel with the same load
  * instructions the weight-streaming GEMM uses, averaged over `repeats` back-to-back launches after
- * one warm-up; the attainable counterpart of the nominal HBM peak.  Allocates 256 bytes of device
- * memory for the duration of the call and synchronises on its own events.  Host only. */
+ * one warm-up; the attainable counterpart of the nominal HBM peak.  `sink` is 256 bytes of device
+ * memory of the caller's (16-byte aligned) that the kernel may write to.  Synchronises on its own
+ * events.  Host only. */
 koala_status koala_measure_stream_read(void *hip_stream, const void *buffer, size_t bytes,
-                                       int repeats, double *gb_per_s);
+                                       void *sink, int repeats, double *gb_per_s);
 
 /* Measurement aid for benchmarks (not part of the method).  Between koala_profile_begin and
  * koala_profile_end every weight-streaming GEMM launch of the bfloat16 path carries a pair

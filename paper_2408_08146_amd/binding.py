@@ -85,7 +85,7 @@ def load_library():
     lib.koala_accept_sample.argtypes = [vp, vp, ip, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, ip]
     lib.koala_accept_sample_static.argtypes = lib.koala_accept_sample.argtypes
     lib.koala_generate_sample.argtypes = [vp, vp, vp, vp, ip, ip, ip, vp, ip, C.c_float, vp, C.POINTER(_GenStats)]
-    lib.koala_measure_stream_read.argtypes = [vp, vp, C.c_size_t, ip, C.POINTER(C.c_double)]
+    lib.koala_measure_stream_read.argtypes = [vp, vp, C.c_size_t, vp, ip, C.POINTER(C.c_double)]
     lib.koala_profile_begin.argtypes = [vp, ip]
     lib.koala_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(ip), C.POINTER(C.c_double)]
     lib.koala_last_error.argtypes = [vp]
@@ -100,10 +100,13 @@ def load_library():
 
 def measure_stream_read(buffer, repeats=5, stream=None):
     """GB/s at which the device streams the whole tensor `buffer` through a plain read kernel."""
+    import torch
     lib = load_library()
     out = C.c_double()
+    sink = torch.zeros(64, dtype=torch.int32, device=buffer.device)
     rc = lib.koala_measure_stream_read(_stream(stream), C.c_void_p(buffer.data_ptr()),
-                                       buffer.numel() * buffer.element_size(), repeats, C.byref(out))
+                                       buffer.numel() * buffer.element_size(), C.c_void_p(sink.data_ptr()), repeats,
+                                       C.byref(out))
     if rc != 0:
         raise KoalaError(rc, "koala_measure_stream_read failed")
     return out.value

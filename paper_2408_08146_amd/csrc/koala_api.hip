@@ -543,7 +543,8 @@ static koala_status draft_expand_impl(koala_ctx *c, void *hip_stream, int batch,
                 if (bf) {
                     const int MT = kb::mt_of(batch);
                     rows_to_frags(c, st, xj, H, batch, H, MT);
-                    const int S = bf_gemm(c, st, c->w.draft_w[j * K + k], H, H, MT);
+                    const int S = MT <= 4 ? bf_gemm_rows(c, st, c->w.draft_w[j * K + k], c->xf, H, H, MT)
+                                          : bf_gemm(c, st, c->w.draft_w[j * K + k], H, H, MT);
                     kb::resblock_p(st, xj, H, c->part, S, MT * 16, H, batch, H);
                 } else {
                     kg::gemm(st, bf, xj, H, c->w.draft_w[j * K + k], c->gu, H, batch, H, H, false);
@@ -591,7 +592,7 @@ static koala_status draft_expand_impl(koala_ctx *c, void *hip_stream, int batch,
         if (bf) {
             const int MT = kb::mt_of(rows), Mp = MT * 16;
             rows_to_frags(c, st, c->act, 2 * H, rows, 2 * H, MT);
-            c->pend_S = bf_gemm(c, st, c->w.fc, H, 2 * H, MT);
+            c->pend_S = MT <= 4 ? bf_gemm_rows(c, st, c->w.fc, c->xf, H, 2 * H, MT) : bf_gemm(c, st, c->w.fc, H, 2 * H, MT);
             c->pend_ld = H;
             c->pend_mode = 2;
             for (int k = 0; k < K; ++k)
@@ -841,19 +842,18 @@ koala_status koala_generate_sample(koala_ctx *c, void *hip_stream, const float *
                          out_tokens, stats);
 }
 
-koala_status koala_measure_stream_read(void *hip_stream, const void *buffer, size_t bytes, int repeats,
+koala_status koala_measure_stream_read(void *hip_stream, const void *buffer, size_t bytes, void *sink, int repeats,
                                        double *gb_per_s) {
-    if (!buffer || !gb_per_s) return KOALA_E_NULL;
-    if (bytes < 16 || repeats < 1 || ((uintptr_t)buffer & 15)) return KOALA_E_SHAPE;
+    if (!buffer || !gb_per_s || !sink) return KOALA_E_NULL;
+    if (bytes < 16 || repeats < 1) return KOALA_E_SHAPE;
+    if (((uintptr_t)buffer & 15) || ((uintptr_t)sink & 15)) return KOALA_E_ALIGN;
     hipStream_t st = (hipStream_t)hip_stream;
-    unsigned *sink = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     koala_status rc = KOALA_E_DEVICE;
-    if (hipMalloc((void **)&sink, 256) == hipSuccess && hipEventCreate(&e0) == hipSuccess &&
-        hipEventCreate(&e1) == hipSuccess) {
-        kg::stream_read(st, buffer, bytes, sink);   // warm-up
+    if (hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess) {
+        kg::stream_read(st, buffer, bytes, (unsigned *)sink);   // warm-up
         bool ok = hipEventRecord(e0, st) == hipSuccess;
-        for (int r = 0; r < repeats; ++r) kg::stream_read(st, buffer, bytes, sink);
+        for (int r = 0; r < repeats; ++r) kg::stream_read(st, buffer, bytes, (unsigned *)sink);
         float ms = 0.f;
         ok = ok && hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
              hipEventElapsedTime(&ms, e0, e1) == hipSuccess && hipGetLastError() == hipSuccess;
@@ -864,7 +864,6 @@ koala_status koala_measure_stream_read(void *hip_stream, const void *buffer, siz
     }
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
-    if (sink) (void)hipFree(sink);
     return rc;
 }
 
