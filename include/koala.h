@@ -281,8 +281,8 @@ koala_status koala_generate(koala_ctx *ctx, void *hip_stream, const float *feat_
                             const int32_t *tok_in, int m, int ctx_len0, int max_new, int use_draft,
                             int32_t *out_tokens, koala_gen_stats *stats);
 
-/* Non-greedy generation loop (sections 2.2 and 4.4): as koala_generate with an EAGLE-style head,
- * but every iteration is koala_draft_expand_sample -> koala_tree_verify -> koala_accept_sample
+/* Non-greedy generation loop (sections 2.2 and 4.4): as koala_generate with a draft head of either
+ * kind, but every iteration is koala_draft_expand_sample -> koala_tree_verify -> koala_accept_sample
  * (commit) at the given temperature.
  *   uniforms device fp32 [max_iters, 3, n_nodes_padded], n_nodes_padded = n_nodes rounded up to a
  *            multiple of 4: iteration i uses row [i,0] as u_draw, [i,1] as u_accept, [i,2] as

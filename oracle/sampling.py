@@ -131,16 +131,20 @@ def eagle_expand_sample(cfg, Wt, Wd, dcache, C, feat_in, tok_in, parent, rank, u
 
 
 def generate_sampled(cfg, Wt, Wd, prompt, n_new, parent, rank, uniforms, temperature=1.0, dt=np.float64):
-    """Non-greedy generation loop with an EAGLE-style head: prefill, then repeat sampled draft ->
-    verify -> stochastic acceptance -> commit until n_new tokens exist (the first is drawn from the
-    prefill's last distribution with uniforms[0][2][0]).  uniforms[i] = (u_draw[T], u_accept[T],
-    u_resample[T]) of iteration i.  Returns dict(tokens, accept_lens, C)."""
+    """Non-greedy generation loop (section 2.2 repeated; section 4.4 evaluates both kinds of head): prefill,
+    then repeat sampled draft -> verify -> stochastic acceptance -> commit until n_new tokens exist (the
+    first is drawn from the prefill's last distribution with uniforms[0][2][0]).  cfg["draft"] selects the
+    head: "eagle" (Wd = its weights; the accepted path's features and tokens are its next catch-up rows) or
+    "medusa" (Wd = the heads' blocks; only the newest feature is used).  uniforms[i] = (u_draw[T],
+    u_accept[T], u_resample[T]) of iteration i.  Returns dict(tokens, accept_lens, C)."""
     from .spec import prefill, verify_tree, commit_path
     from .llama import KVCache
     T = len(parent)
+    medusa = cfg.get("draft", "eagle") == "medusa"
+    D = int(tree_depths(parent).max()) if T > 1 else 0
     cap = len(prompt) + n_new + 2 * T + 2
     tcache = KVCache(cfg["n_layers"], cfg["n_heads"], cap, cfg["head_dim"], dt)
-    dcache = KVCache(cfg["K"], cfg["n_heads"], cap, cfg["head_dim"], dt)
+    dcache = None if medusa else KVCache(cfg["K"], cfg["n_heads"], cap, cfg["head_dim"], dt)
     feats, logits = prefill(cfg, Wt, tcache, prompt, dt)
     root = inverse_cdf(softmax_t(logits[-1], temperature), uniforms[0][2][0])
     out, accept_lens = [root], []
@@ -149,7 +153,10 @@ def generate_sampled(cfg, Wt, Wd, prompt, n_new, parent, rank, uniforms, tempera
     it = 0
     while len(out) < n_new:
         u_draw, u_acc, u_res = uniforms[it]
-        dr = eagle_expand_sample(cfg, Wt, Wd, dcache, C, feat_in, tok_in, parent, rank, u_draw, temperature, dt)
+        if medusa:
+            dr = medusa_expand_sample(cfg, Wt, Wd, feat_in[-1], int(tok_in[-1]), parent, rank, D, u_draw, temperature, dt)
+        else:
+            dr = eagle_expand_sample(cfg, Wt, Wd, dcache, C, feat_in, tok_in, parent, rank, u_draw, temperature, dt)
         tokens = dr["tokens"]
         feat, tl, _ = verify_tree(cfg, Wt, tcache, C, tokens, parent, dt)
         q = {i: softmax_t(tl[i], temperature) for i in range(T)}

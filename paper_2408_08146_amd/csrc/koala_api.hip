@@ -747,8 +747,7 @@ static koala_status generate_impl(koala_ctx *c, void *hip_stream, const float *f
     const bool sampling = uniforms != nullptr;
     const int Tp = (c->T + 3) & ~3;   // row stride of the uniforms: rows stay 16-byte aligned
     if (sampling) {
-        if (c->draft.kind != KOALA_DRAFT_EAGLE || !use_draft)
-            return fail(c, KOALA_E_UNSUPPORTED, "non-greedy generation needs an EAGLE-style draft head");
+        if (!use_draft) return fail(c, KOALA_E_UNSUPPORTED, "non-greedy generation needs a draft head");
         if (!(temperature > 0.f)) return fail(c, KOALA_E_SHAPE, "temperature must be positive");
         if (max_iters < 1) return fail(c, KOALA_E_SHAPE, "max_iters must be positive");
         if (!aligned16(uniforms)) return fail(c, KOALA_E_ALIGN, "uniforms must be 16-byte aligned");

@@ -167,6 +167,48 @@ def test_nongreedy_generation_matches_oracle_loop(temperature):
     assert int(case.kv["ctx_len"][0].item()) == ref[2]
 
 
+@pytest.mark.parametrize("temperature", [0.1, 0.05])
+def test_nongreedy_generation_with_medusa_heads_matches_oracle_loop(temperature):
+    """koala_generate_sample with Medusa-style heads (section 4.4 evaluates both kinds) against the oracle's
+    loop with the same uniforms, compared exactly where the oracle's own run does not change when every
+    uniform moves by +-2e-5.  The random model's distributions over 1000 tokens are nearly flat at
+    temperature 1 (draw boundaries then lie closer together than that margin), so the temperatures are low;
+    accepted lengths 0, 1 and 2 all occur."""
+    from koala_synth import tensor_uniform01
+    case = None
+    for seed in (61, 62, 63, 64):
+        case = case or Case("cfg1", draft="medusa", medusa_heads=2, K=1)
+        tree, T = case.tree, case.T
+        Tp = (T + 3) // 4 * 4
+        prompt = np.arange(5, 13)
+        n, iters = 16, 40
+        U = tensor_uniform01(seed, "gen_uniforms_medusa", (iters, 3, Tp))
+
+        def run(delta):
+            us = [tuple(np.clip(U[i, j, :T].astype(np.float64) + delta, 0.0, 1.0 - 1e-12) for j in range(3))
+                  for i in range(iters)]
+            r = oracle.generate_sampled(case.cfg, case.Wt, case.Wd, prompt, n, tree.parent, tree.rank, us, temperature)
+            return r["tokens"], r["accept_lens"], r["C"]
+        ref = run(0.0)
+        if ref == run(-2e-5) == run(2e-5):
+            break
+    else:
+        pytest.fail("no seed whose oracle run is outside the margin")
+    case.tc[0] = oracle.KVCache(case.cfg["n_layers"], case.cfg["n_heads"], case.cap, case.cfg["head_dim"])
+    feats, logits = case.prefill_oracle(prompt)
+    case.upload_kv()
+    root = oracle.inverse_cdf(oracle.softmax_t(logits[-1], temperature), U[0, 2, 0])
+    assert root == ref[0][0]
+    torch = case.torch
+    out = torch.full((n - 1,), -1, dtype=torch.int32, device=case.device)
+    stats = case.gpu.generate_sample(case.t(feats[-1:].astype(np.float32)), case.t(np.array([root], np.int32)), 1,
+                                     len(prompt), n - 1, case.t(U), temperature, out)
+    got = [root] + [int(t) for t in out.cpu().numpy()]
+    assert got == ref[0]
+    assert stats["accept_hist"] == _hist(ref[1]) and stats["iterations"] == len(ref[1])
+    assert int(case.kv["ctx_len"][0].item()) == ref[2]
+
+
 def test_nongreedy_generation_runs_out_of_uniforms_cleanly():
     import paper_2408_08146_amd as K
     from koala_synth import tensor_uniform01

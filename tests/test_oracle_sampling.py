@@ -276,3 +276,32 @@ def test_inverse_cdf_definition_and_degenerate_cases():
     assert oracle.inverse_cdf(np.array([0.0, 0.0, 1.0, 0.0]), 0.999999) == 2
     # a one-hot distribution drawn three times: the one positive id, then the degenerate reading twice
     assert oracle.draw_without_replacement([0.0, 0.0, 0.0, 1.0, 0.0], [0.5, 0.5, 0.9]) == [3, 0, 0]
+
+
+def test_medusa_sampled_generation_pins():
+    """Non-greedy loop with Medusa-style heads.  At vanishing temperature it emits plain greedy decoding of the
+    target (the method is lossless whatever the heads propose).  At temperature 1 the bookkeeping must hold:
+    the committed length is the prompt plus every emitted token but the last, and every emitted token has
+    positive probability under the target when the run is replayed by plain decoding."""
+    from helpers import NANO
+    from koala_synth.weights import target_weights, medusa_weights
+    cfg = dict(NANO, draft="medusa")
+    Wt = target_weights(cfg, 6, norm_gain="random", cache=True)
+    Wm = medusa_weights(cfg, 6, cache=True)
+    tree = make_tree([2, 2, 1], [1, 2, 3, 2])
+    prompt = np.array([8, 3, 41, 7])
+    rng = np.random.default_rng(19)
+    uniforms = [(rng.random(tree.n_nodes), rng.random(tree.n_nodes), rng.random(tree.n_nodes)) for _ in range(24)]
+    cold = oracle.generate_sampled(cfg, Wt, Wm, prompt, 11, tree.parent, tree.rank, uniforms, temperature=1e-7)
+    assert cold["tokens"] == oracle.greedy_reference(cfg, Wt, prompt, 11)
+    warm = oracle.generate_sampled(cfg, Wt, Wm, prompt, 11, tree.parent, tree.rank, uniforms, temperature=1.0)
+    assert warm["C"] == len(prompt) + sum(a + 1 for a in warm["accept_lens"])
+    assert len(warm["tokens"]) == 11 and warm["tokens"] != cold["tokens"]
+    # replaying the emitted tokens through plain decoding: each had positive probability under the target
+    cache = oracle.KVCache(cfg["n_layers"], cfg["n_heads"], 64, cfg["head_dim"])
+    _, logits = oracle.prefill(cfg, Wt, cache, prompt)
+    last, C = logits[-1], len(prompt)
+    for t in warm["tokens"][:-1]:
+        assert oracle.softmax_t(last, 1.0)[t] > 0
+        _, last = oracle.decode_one(cfg, Wt, cache, C, t)
+        C += 1
