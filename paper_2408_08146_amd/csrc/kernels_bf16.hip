@@ -385,6 +385,128 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// GEMM for many activation rows (batched verification: hundreds of rows), where the matrix pipe and the
+// operand traffic, not the weight stream alone, set the pace.  One workgroup of four waves per compute unit
+// (one wave per SIMD, so a wave may use the whole register file) owns 4 U weight row groups of 16 rows and up
+// to MTW activation tiles over a K range.  Wave w keeps its U groups' weight fragments of the current and the
+// next 64-k tile in registers (loaded straight from HBM) and all U x MTW accumulator tiles; the activation
+// fragments of a 64-k tile are shared by the four waves through LDS, filled by loads that go from global
+// memory to LDS directly (no staging registers), double-buffered.  Every activation fragment fetched from
+// LDS feeds U MFMAs (hi) + U (lo).  Output: fp32 partial sums P[sp][row][n] like the other GEMMs.
+// grid: (row-group blocks) x (activation tile blocks) x S.
+// ---------------------------------------------------------------------------------------------
+// acc += A * B on the matrix pipe with the accumulator tile held in place in the accumulation registers.  Written
+// as an instruction of its own because the compiler's MFMA builtin, once a wave uses more than 256 registers,
+// gives every result a new register and copies it back, which costs more than the MFMA itself.  An MFMA may
+// follow another that wrote its accumulator operand without waiting when both name the same registers, as here.
+__device__ __forceinline__ void mfma_acc(f32x4 &acc, bf16x8 a, bf16x8 b) {
+    asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+template <int U, int MTW>
+__global__ __launch_bounds__(256, U * MTW <= 24 ? 2 : 1) void k_gemm_big(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
+                                                     float *__restrict__ P, int Npad, int K, int S, int MTT, int n_mt,
+                                                     int n_pm) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char bsm[];
+    typedef __attribute__((address_space(3))) void lds_void;
+    typedef const __attribute__((address_space(1))) void glb_void;
+    constexpr int XT = 2 * MTW * 2 * 64;   // 16-byte units of one 64-k tile of activations: [s][m][hi, lo][64]
+    u32x4 *xs = (u32x4 *)bsm;              // [2][XT]
+    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
+    const int nunits = Npad / 16, ngrp = (nunits + 4 * U - 1) / (4 * U);
+    int bid = blockIdx.x;
+    const int g = bid % ngrp; bid /= ngrp;
+    const int pm = bid % n_pm, sp = bid / n_pm;
+    const int mt0 = pm * MTW, mt_cnt = min(MTW, n_mt - mt0);
+    const int nkt = K / 64;
+    const int kt0 = (int)((long long)sp * nkt / S), kt1 = (int)((long long)(sp + 1) * nkt / S);
+    const int ug0 = (g * 4 + wave) * U;
+    const u32x4 *w[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        const int ug = min(ug0 + j, nunits - 1);
+        w[j] = Wp + ((size_t)(ug >> 2) * nkt * 8 + (ug & 3) * 2) * 64 + l;
+    }
+    u32x4 wr[4][U][2];   // ring of weight fragments: tile t lives in slot (t - kt0) % 4
+    auto wload = [&](int kt, int slot) {
+#pragma unroll
+        for (int j = 0; j < U; ++j)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) wr[slot][j][s] = __builtin_nontemporal_load(w[j] + (size_t)kt * 512 + s * 64);
+    };
+    // fragments (s, m, hl) of tile kt -> LDS buffer b: 2 * MTW * 2 one-KiB pieces, dealt to the waves in turn
+    // (tiles past the last one re-read it: computed, never stored)
+    auto xfill = [&](int kt, int b) {
+#pragma unroll
+        for (int i = 0; i < MTW; ++i) {
+            const int f = wave + 4 * i, hl = f & 1, m = (f >> 1) % MTW, s = (f >> 1) / MTW;
+            const u32x4 *src = Xf + (((size_t)(2 * kt + s) * MTT + min(mt0 + m, MTT - 1)) * 2 + hl) * 64 + l;
+            u32x4 *dst = xs + (size_t)b * XT + ((s * MTW + m) * 2 + hl) * 64;   // wave-uniform; lane i lands at dst + i
+            __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)dst, 16, 0, 0);
+        }
+    };
+    f32x4 acc[U][MTW];
+#pragma unroll
+    for (int j = 0; j < U; ++j)
+#pragma unroll
+        for (int m = 0; m < MTW; ++m) acc[j][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // Memory operations complete in issue order.  Issued before the loop: W(kt0), W(kt0+1), W(kt0+2), X(kt0), all
+    // awaited.  The iteration of tile t issues X(t+1) and then W(t+3) (into the ring slot tile t-1 has left).  At
+    // the top of the next iteration only those 2 U weight loads may still be under way: X(t+1) and every older
+    // load have landed, and a weight tile has two iterations to arrive from HBM.  Past the last tile the same
+    // loads are issued again for the last tile, so that the count the wait relies on stays the same.
+    constexpr int VM = 2 * U;
+    constexpr int WAIT_BUT_NEWEST = (VM & 15) | (7 << 4) | (15 << 8) | ((VM >> 4) << 14);   // s_waitcnt vmcnt(2U)
+    const int last = kt1 - 1;
+    if (kt0 < kt1) {
+        wload(kt0, 0);
+        wload(min(kt0 + 1, last), 1);
+        wload(min(kt0 + 2, last), 2);
+        xfill(kt0, 0);
+        __builtin_amdgcn_s_waitcnt(0);
+    }
+    for (int t = kt0; t < kt1; t += 4) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int tt = t + p;
+            if (tt < kt1) {
+                if (tt > kt0) __builtin_amdgcn_s_waitcnt(WAIT_BUT_NEWEST);
+                __syncthreads();   // every wave's part of X(tt) is in LDS; nobody still reads the other buffer
+                xfill(min(tt + 1, last), (p + 1) & 1);
+                wload(min(tt + 3, last), (p + 3) & 3);
+                const u32x4 *xb = xs + (size_t)(p & 1) * XT + l;
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+#pragma unroll
+                    for (int m = 0; m < MTW; ++m) {
+                        const bf16x8 xh = __builtin_bit_cast(bf16x8, xb[((s * MTW + m) * 2 + 0) * 64]);
+                        const bf16x8 xl = __builtin_bit_cast(bf16x8, xb[((s * MTW + m) * 2 + 1) * 64]);
+#pragma unroll
+                        for (int j = 0; j < U; ++j) mfma_acc(acc[j][m], __builtin_bit_cast(bf16x8, wr[p][j][s]), xh);
+#pragma unroll
+                        for (int j = 0; j < U; ++j) mfma_acc(acc[j][m], __builtin_bit_cast(bf16x8, wr[p][j][s]), xl);
+                    }
+                }
+            }
+        }
+    }
+    // results of the matrix pipe may be read by other instructions only some cycles after the last MFMA was issued
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        if (ug0 + j >= nunits) continue;
+#pragma unroll
+        for (int m = 0; m < MTW; ++m) {
+            if (m < mt_cnt) {
+                const int row = (mt0 + m) * 16 + li, n = (ug0 + j) * 16 + 4 * lg;
+                *(f32x4 *)(P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = acc[j][m];
+            }
+        }
+    }
+}
+
 // Sums of split-K partials.  Loads are issued in batches (16 vector loads / 24 scalar loads in
 // flight) so that a sum costs one or two memory round trips; the order of the additions is fixed.
 __device__ __forceinline__ float psum(const float *P, int S, int Mp, int ld, int row, int col) {
@@ -868,6 +990,67 @@ void gemm_rows_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int
     e.rows = rows; e.Xo = (uint32_t *)Xo; e.F = F;
     dispatch_gemm_rows<EPI_SWIGLU>(st, Wp, Xf, pad64(2 * F), K, MTT, rows_units(pad64(2 * F), n_cu), e, ev_start,
                                    ev_stop);
+}
+
+// Launch shape of gemm_big for `rows` activation rows: activation tiles per workgroup (at most 15), weight row
+// groups per wave (3, 4 or 5) and K splits, chosen so that the workgroups (one per compute unit) cover the
+// chip in as few, as full rounds as possible; splits cost partial-sum traffic and are taken only when they pay.
+BigShape big_shape(int Npad, int K, int rows, int n_cu) {
+    BigShape b{};
+    b.n_mt = (rows + 15) / 16;
+    b.n_pm = (b.n_mt + 14) / 15;
+    static const int fpm = getenv("KOALA_BIG_PM") ? atoi(getenv("KOALA_BIG_PM")) : 0;   // tuning aid: tile blocks
+    if (fpm > b.n_pm && fpm <= b.n_mt) b.n_pm = fpm;
+    b.mtw = (b.n_mt + b.n_pm - 1) / b.n_pm;
+    const int units = Npad / 16, nkt = K / 64;
+    double best = -1.0;
+    const int tmpl = b.mtw <= 8 ? 8 : b.mtw <= 10 ? 10 : 15;   // activation tiles the kernel is instantiated for
+    for (int U = 5; U >= 3; --U)
+        for (int S = 1; S <= 4 && S <= nkt; ++S) {
+            if (U * tmpl > 60) continue;   // the accumulator tiles of a wave must fit the 256 accumulation registers
+            const int wgs = ((units + 4 * U - 1) / (4 * U)) * b.n_pm * S, rounds = (wgs + n_cu - 1) / n_cu;
+            // fewer row groups per wave mean more LDS reads per MFMA; more splits, more partial sums
+            const double score = (double)wgs / ((double)rounds * n_cu) - 0.04 * (S - 1) - 0.03 * (5 - U);
+            if (score > best) { best = score; b.U = U; b.S = S; }
+        }
+    // tuning aids, read once: force the row groups per wave / the K splits
+    static const int fu = getenv("KOALA_BIG_U") ? atoi(getenv("KOALA_BIG_U")) : 0;
+    static const int fs = getenv("KOALA_BIG_S") ? atoi(getenv("KOALA_BIG_S")) : 0;
+    if (fu >= 3 && fu <= 5 && fu * tmpl <= 60) b.U = fu;
+    if (fs >= 1 && fs <= 4 && fs <= nkt) b.S = fs;
+    return b;
+}
+
+template <int U, int MTW>
+static void launch_gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT,
+                            const BigShape &b, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    const size_t sm = (size_t)2 * 2 * MTW * 2 * 64 * 16;
+    static bool done = false;
+    if (!done) {
+        (void)hipFuncSetAttribute((const void *)k_gemm_big<U, MTW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+        done = true;
+    }
+    const dim3 grid(((Npad / 16 + 4 * U - 1) / (4 * U)) * b.n_pm * b.S);
+    if (ev_start || ev_stop)
+        hipExtLaunchKernelGGL((k_gemm_big<U, MTW>), grid, dim3(256), sm, st, ev_start, ev_stop, 0, (const u32x4 *)Wp,
+                              (const u32x4 *)Xf, P, Npad, K, b.S, MTT, b.n_mt, b.n_pm);
+    else
+        k_gemm_big<U, MTW><<<grid, 256, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, b.S, MTT, b.n_mt,
+                                                  b.n_pm);
+}
+
+void gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, const BigShape &b,
+              hipEvent_t ev_start, hipEvent_t ev_stop) {
+#define KOALA_BIG(UV)                                                                                         \
+    {                                                                                                         \
+        if (b.mtw <= 8) launch_gemm_big<UV, 8>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);            \
+        else if (b.mtw <= 10) launch_gemm_big<UV, 10>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);     \
+        else launch_gemm_big<UV, 15>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);                      \
+    }
+    if (b.U == 3) KOALA_BIG(3) else if (b.U == 4) KOALA_BIG(4)
+    else if (b.mtw <= 8) launch_gemm_big<5, 8>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);
+    else launch_gemm_big<5, 10>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);
+#undef KOALA_BIG
 }
 
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,

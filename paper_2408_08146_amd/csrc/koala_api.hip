@@ -138,8 +138,8 @@ size_t carve(koala_ctx *c, char *base) {
         size_t worst = 0;
         for (auto &sh : shapes) {
             const int Np = kb::pad64(sh[0]);
-            const int S = std::max(std::max(kb::gemm_splits(Np, sh[1]), kb::gemm_splits(Np, sh[1], MTmax)),
-                                   kb::rows_splits(Np, sh[1]));
+            const int S = std::max(std::max(std::max(kb::gemm_splits(Np, sh[1]), kb::gemm_splits(Np, sh[1], MTmax)),
+                                            kb::rows_splits(Np, sh[1])), MTmax >= 8 ? 4 : 1);
             worst = std::max(worst, (size_t)S * Np);
         }
         c->part_bytes = worst * MTmax * 16 * sizeof(float);
@@ -188,10 +188,22 @@ LaunchEvents timed_launch(koala_ctx *c, double weight_bytes) {
     return ev;
 }
 
+// KOALA_GEMM_BIG=0 (tuning aid, read once): batches of more than 64 rows take the passes of the skinny kernel
+bool big_gemm_enabled() {
+    static const bool on = !(getenv("KOALA_GEMM_BIG") && atoi(getenv("KOALA_GEMM_BIG")) == 0);
+    return on;
+}
+
 // Split-K GEMM on the fragments in c->xf: partial sums of X * W^T into c->part; returns the split count.
-int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT) {
-    const int Npad = kb::pad64(N), S = kb::gemm_splits(Npad, K, MT);
+int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT, int rows = 0) {
+    const int Npad = kb::pad64(N);
     const LaunchEvents ev = timed_launch(c, (double)Npad * K * 2.0);
+    if (MT >= 8 && big_gemm_enabled()) {   // many rows: one pass over the weights with large register tiles
+        const kb::BigShape b = kb::big_shape(Npad, K, rows > 0 ? rows : MT * 16, c->n_cu);
+        kb::gemm_big(st, Wp, c->xf, c->part, Npad, K, MT, b, ev.start, ev.stop);
+        return b.S;
+    }
+    const int S = kb::gemm_splits(Npad, K, MT);
     kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S, ev.start, ev.stop);
     return S;
 }
@@ -247,22 +259,22 @@ void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_se
         kb::gemm_rows_qkv(st, lw[1], c->xf, H, MT, hidden_scale(c), rows, rows_per_seq, c->meta, c->qf, kc, vc, H,
                           s.n_heads, s.head_dim, c->kv.capacity, c->n_cu, ev.start, ev.stop);
     } else {
-        S = bf_gemm(c, st, lw[1], 3 * H, H, MT);
+        S = bf_gemm(c, st, lw[1], 3 * H, H, MT, rows);
         kb::rope_append(st, c->part, S, Mp, 3 * H, hidden_scale(c), c->meta, c->qf, kc, vc, rows, H, s.n_heads,
                         s.head_dim, c->kv.capacity, rows_per_seq);
     }
     kb::attention_tree(st, c->qf, c->meta, kc, vc, c->o_part, c->opart_bytes, c->ml, c->ml_bytes, c->attn_cnt, c->xf,
                        MT, batch, rows_per_seq, s.n_heads, s.head_dim, c->kv.capacity, ns);
-    S = fused ? bf_gemm_rows(c, st, lw[2], c->xf, H, H, MT) : bf_gemm(c, st, lw[2], H, H, MT);
+    S = fused ? bf_gemm_rows(c, st, lw[2], c->xf, H, H, MT) : bf_gemm(c, st, lw[2], H, H, MT, rows);
     kb::fold(st, c->x, H, c->part, S, Mp, H, 1, rows, H, lw[3], c->xf, MT, c->row_sums, c->max_rows);
     if (fused) {
         const LaunchEvents ev = timed_launch(c, (double)kb::pad64(2 * F) * H * 2.0);
         kb::gemm_rows_swiglu(st, lw[4], c->xf, H, MT, hidden_scale(c), rows, c->xf2, F, c->n_cu, ev.start, ev.stop);
         S = bf_gemm_rows(c, st, lw[5], c->xf2, H, F, MT);
     } else {
-        S = bf_gemm(c, st, lw[4], 2 * F, H, MT);
+        S = bf_gemm(c, st, lw[4], 2 * F, H, MT, rows);
         kb::silu_frag(st, c->part, S, Mp, 2 * F, hidden_scale(c), c->xf, MT, rows, F);
-        S = bf_gemm(c, st, lw[5], H, F, MT);
+        S = bf_gemm(c, st, lw[5], H, F, MT, rows);
     }
     c->pend_S = S;
     c->pend_ld = H;
