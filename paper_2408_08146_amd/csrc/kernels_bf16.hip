@@ -16,12 +16,32 @@
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 struct __attribute__((may_alias, aligned(8))) u64_pair { uint32_t x, y; };
 struct __attribute__((may_alias, aligned(8))) f32_pair { float x, y; };
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
 __device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
+// (a, b) as bfloat16 pairs hi and lo with a ~ hi.x + lo.x, b ~ hi.y + lo.y (~16 mantissa bits): one packed
+// round-to-nearest-even conversion per pair
+struct HiLo { uint32_t hi, lo; };
+__device__ __forceinline__ HiLo split_pair(float a, float b) {
+    HiLo r;
+    r.hi = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){a, b}, bf16x2));
+    r.lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){a - __uint_as_float(r.hi << 16),
+                                                                          b - __uint_as_float(r.hi & 0xFFFF0000u)}, bf16x2));
+    return r;
+}
+// eight values -> the hi and lo 16-byte pieces of a fragment lane
+__device__ __forceinline__ void split8(const float *y, u32x4 &h, u32x4 &w) {
+    const HiLo p0 = split_pair(y[0], y[1]), p1 = split_pair(y[2], y[3]), p2 = split_pair(y[4], y[5]), p3 = split_pair(y[6], y[7]);
+    h = (u32x4){p0.hi, p1.hi, p2.hi, p3.hi};
+    w = (u32x4){p0.lo, p1.lo, p2.lo, p3.lo};
+}
 __device__ __forceinline__ uint32_t f2bf(float v) {  // round to nearest even
     uint32_t u = __float_as_uint(v);
     u += 0x7FFFu + ((u >> 16) & 1u);
@@ -359,11 +379,11 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
 #pragma unroll
                     for (int z = 0; z < 2; ++z) {
                         const int d = dd + z * half;
-                        const uint32_t h0 = f2bf(y[2 * z]), h1 = f2bf(y[2 * z + 1]);
-                        const uint32_t l0 = f2bf(y[2 * z] - bf2f(h0)), l1 = f2bf(y[2 * z + 1] - bf2f(h1));
+                        const HiLo pr = split_pair(y[2 * z], y[2 * z + 1]);
+                        const uint32_t hi = pr.hi, lo = pr.lo;
                         uint32_t *dst = qt + (((size_t)(d >> 5) * 2) * 64 + (i & 15) + 16 * ((d & 31) >> 3)) * 4 + ((d & 7) >> 1);
-                        dst[0] = h0 | (h1 << 16);
-                        dst[64 * 4] = l0 | (l1 << 16);
+                        dst[0] = hi;
+                        dst[64 * 4] = lo;
                     }
                 } else {
                     *(uint32_t *)(e.kc + o + dd) = f2bf(a0) | (f2bf(a1) << 16);
@@ -375,12 +395,12 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
             if (f0 >= e.F) continue;
             const float g0 = v[0], g1 = v[2];
             const float y0 = g0 / (1.0f + __expf(-g0)) * v[1], y1 = g1 / (1.0f + __expf(-g1)) * v[3];
-            const uint32_t h0 = f2bf(y0), h1 = f2bf(y1);
-            const uint32_t l0 = f2bf(y0 - bf2f(h0)), l1 = f2bf(y1 - bf2f(h1));
+            const HiLo pr = split_pair(y0, y1);
+            const uint32_t hi = pr.hi, lo = pr.lo;
             const int ks = f0 >> 5, lane = li + 16 * ((f0 & 31) >> 3);
             uint32_t *dst = e.Xo + ((((size_t)ks * MTT + mtt) * 2) * 64 + lane) * 4 + ((f0 & 7) >> 1);
-            dst[0] = h0 | (h1 << 16);
-            dst[64 * 4] = l0 | (l1 << 16);
+            dst[0] = hi;
+            dst[64 * 4] = lo;
         }
     }
 }
@@ -583,16 +603,9 @@ __device__ __forceinline__ void psum8(const float *P, int S, int Mp, int ld, int
 
 // store 8 consecutive k of row m (k0 % 8 == 0) as hi/lo fragments
 __device__ __forceinline__ void store_frag8(u32x4 *Xf, int MT, int m, int k0, const float *y) {
-    uint32_t hi[8], lo[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        hi[e] = f2bf(y[e]);
-        lo[e] = f2bf(y[e] - bf2f(hi[e]));
-    }
-    const int ks = k0 >> 5, lane = (m & 15) + 16 * ((k0 & 31) >> 3), mt = m >> 4;
     u32x4 h, w;
-    h.x = hi[0] | (hi[1] << 16); h.y = hi[2] | (hi[3] << 16); h.z = hi[4] | (hi[5] << 16); h.w = hi[6] | (hi[7] << 16);
-    w.x = lo[0] | (lo[1] << 16); w.y = lo[2] | (lo[3] << 16); w.z = lo[4] | (lo[5] << 16); w.w = lo[6] | (lo[7] << 16);
+    split8(y, h, w);
+    const int ks = k0 >> 5, lane = (m & 15) + 16 * ((k0 & 31) >> 3), mt = m >> 4;
     u32x4 *dst = Xf + ((size_t)(ks * MT + mt) * 2) * 64 + lane;
     dst[0] = h;
     dst[64] = w;
@@ -979,7 +992,8 @@ void gemm_rows_qkv(hipStream_t st, const void *Wp, const void *Xf, int K, int MT
     e.sums = ns.sums; e.nparts = ns.nparts; e.srows = ns.srows; e.Kn = ns.K; e.eps = ns.eps;
     e.rows = rows; e.meta = meta; e.qf = (uint32_t *)qf; e.kc = (bf16_t *)kc; e.vc = (bf16_t *)vc;
     e.H = H; e.n_heads = n_heads; e.DH = head_dim; e.cap = cap;
-    e.rows_per_seq = rows_per_seq; e.MTQ = (rows_per_seq + 15) / 16; e.qscale = 1.0f / sqrtf((float)head_dim);
+    e.rows_per_seq = rows_per_seq; e.MTQ = (rows_per_seq + 15) / 16;
+    e.qscale = 1.4426950408889634f / sqrtf((float)head_dim);   // the attention kernel works in powers of two
     dispatch_gemm_rows<EPI_QKV>(st, Wp, Xf, 3 * H, K, MTT, rows_units(3 * H, n_cu), e, ev_start, ev_stop);
 }
 
@@ -1064,7 +1078,7 @@ void rope_append(hipStream_t st, const float *P, int S, int Mp, int ldp, const N
     k_rope_append_p<<<dim3(rows, n_heads), head_dim / 2, 0, st>>>(P, S, Mp, ldp, mk_scale(ns), meta, (bf16_t *)qf,
                                                                   (bf16_t *)kc, (bf16_t *)vc, H, n_heads, head_dim, cap,
                                                                   rows_per_seq, (rows_per_seq + 15) / 16,
-                                                                  1.0f / sqrtf((float)head_dim));
+                                                                  1.4426950408889634f / sqrtf((float)head_dim));
 }
 
 void silu_frag(hipStream_t st, const float *P, int S, int Mp, int ldp, const NormScale &ns, void *Xf, int MT, int M,
@@ -1093,7 +1107,8 @@ void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *o
 
 // =====================================================================================================
 // Tree-masked attention on MFMA (bf16 KV cache; queries arrive as bf16 hi + lo MFMA fragments, already
-// multiplied by 1/sqrt(head_dim), written by the QKV projection's epilogue).
+// multiplied by log2(e)/sqrt(head_dim), written by the QKV projection's epilogue; the softmax is computed
+// with powers of two, which is the same function).
 //
 // grid (nsplit * row groups, n_heads, batch), NWV waves.  The 32-key steps of the sequence's visible key range
 // [0, kv_end) are dealt out round-robin over the nsplit workgroups and their waves, each wave keeping an
@@ -1158,7 +1173,8 @@ template <int DH, int MT, int NWV>
 __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     constexpr int KS = DH / 32;            // contraction steps over the head dimension
     constexpr int DT = DH / 16;            // 16-wide output tiles over the head dimension
-    constexpr int VS = DH * 2 + 8;         // bytes per key row of the transposed-read V tile (padded)
+    constexpr int VS = DH * 2 + 32;        // bytes per key row of the V tile in LDS: rows 8 banks apart, so that a
+                                           // transposing load's 16 lanes (4 rows x 32 B) hit 32 different banks
     constexpr int LPR = DH / 8;            // lanes that cover one cache row with 16 B each
     constexpr int VI = DH / 16;            // load instructions per 32-key V tile
     constexpr int NTH = 64 * NWV;
@@ -1298,45 +1314,40 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
             }
             tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            // scores are in units of log 2 (the queries carry the factor log2(e)): weights are 2^(score - max)
             const float m_new = fmaxf(m_run[mt], tmax);
-            const float alpha = (m_run[mt] == -INFINITY) ? 0.f : __expf(m_run[mt] - m_new);
-            float psum = 0.f;
-            uint32_t hi[8], lo[8];
+            const float alpha = (m_run[mt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[mt] - m_new);
+            float psum = 0.f, v[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float v = (p[e] == -INFINITY) ? 0.f : __expf(p[e] - m_new);
-                psum += v;
-                hi[e] = f2bf(v);
-                lo[e] = f2bf(v - bf2f(hi[e]));
+                v[e] = (p[e] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(p[e] - m_new);
+                psum += v[e];
             }
             l_run[mt] = l_run[mt] * alpha + psum;
             m_run[mt] = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {   // once the maxima have settled nothing is rescaled
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                acc_o[mt][dt][0] *= alpha; acc_o[mt][dt][1] *= alpha;
-                acc_o[mt][dt][2] *= alpha; acc_o[mt][dt][3] *= alpha;
+                for (int dt = 0; dt < DT; ++dt) {
+                    acc_o[mt][dt][0] *= alpha; acc_o[mt][dt][1] *= alpha;
+                    acc_o[mt][dt][2] *= alpha; acc_o[mt][dt][3] *= alpha;
+                }
             }
             u32x4 x, c;
-            x.x = hi[0] | (hi[1] << 16); x.y = hi[2] | (hi[3] << 16); x.z = hi[4] | (hi[5] << 16); x.w = hi[6] | (hi[7] << 16);
-            c.x = lo[0] | (lo[1] << 16); c.y = lo[2] | (lo[3] << 16); c.z = lo[4] | (lo[5] << 16); c.w = lo[6] | (lo[7] << 16);
+            split8(v, x, c);
             ph[mt] = __builtin_bit_cast(bf16x8, x);
             pl[mt] = __builtin_bit_cast(bf16x8, c);
         }
-        // ---- O^T += V^T P^T ; A operand gathered from the LDS tile: lane (d%16, g), slot e -> key 16*(e/4)+4g+e%4
-        const u16_alias *vt16 = (const u16_alias *)vt;
+        // ---- O^T += V^T P^T ; A operand: lane (d%16, g), slot e -> key 16*(e/4)+4g+e%4, read from the row-major LDS
+        //      tile with the transposing LDS load: in every group of 16 lanes, lane i hands in the address of four
+        //      consecutive 16-bit values and receives element i%4 of the lanes 4e + i/4, e = 0..3.  Lane i therefore
+        //      points at key row 4g + i/4, columns 16 dt + 4 (i%4) .., and gets keys 4g .. 4g+3 of column 16 dt + i.
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            uint32_t w[4];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const int ka = 16 * ((2 * e2) >> 2) + 4 * lg + ((2 * e2) & 3);
-                const uint32_t v0 = vt16[(size_t)ka * (VS / 2) + dt * 16 + li];
-                const uint32_t v1 = vt16[(size_t)(ka + 1) * (VS / 2) + dt * 16 + li];
-                w[e2] = v0 | (v1 << 16);
-            }
-            u32x4 x;
-            x.x = w[0]; x.y = w[1]; x.z = w[2]; x.w = w[3];
-            const bf16x8 va = __builtin_bit_cast(bf16x8, x);
+            typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+            const unsigned char *src = vt + (size_t)(4 * lg + (li >> 2)) * VS + dt * 32 + (li & 3) * 8;
+            const bf16x4 k0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)src);
+            const bf16x4 k1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(src + 16 * VS));
+            const bf16x8 va = __builtin_shufflevector(k0, k1, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 acc_o[mt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, ph[mt], acc_o[mt][dt], 0, 0, 0);
@@ -1375,8 +1386,8 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
             for (int mt = 0; mt < MT; ++mt) {
                 const float mw = mm[((wave * MT + mt) * 64 + l) * 2], lw = mm[((wave * MT + mt) * 64 + l) * 2 + 1];
                 const float M = fmaxf(m_run[mt], mw);
-                const float a0 = (m_run[mt] == -INFINITY) ? 0.f : __expf(m_run[mt] - M);
-                const float aw = (mw == -INFINITY) ? 0.f : __expf(mw - M);
+                const float a0 = (m_run[mt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[mt] - M);
+                const float aw = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
                 l_run[mt] = l_run[mt] * a0 + lw * aw;
                 m_run[mt] = M;
 #pragma unroll
@@ -1450,7 +1461,7 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
         float den = 0.f;
 #pragma unroll
         for (int q = 0; q < KOALA_NSPLIT_MAX; ++q) {
-            const float w = (ms[q] == -INFINITY) ? 0.f : __expf(ms[q] - Mx);
+            const float w = (ms[q] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms[q] - Mx);
             den += w * ls[q];
             ya += w * oa[q];
             yc += w * oc[q];
@@ -1464,7 +1475,7 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
 
 template <int DH, int MT, int NWV>
 void launch_attn(hipStream_t st, const AttnArgs &a, int batch) {
-    constexpr int KS = DH / 32, DT = DH / 16, VS = DH * 2 + 8;
+    constexpr int KS = DH / 32, DT = DH / 16, VS = DH * 2 + 32;
     const size_t main_b = (size_t)MT * KS * 2 * 64 * 16 + (size_t)NWV * 32 * VS;
     const size_t merge_b = (size_t)(NWV / 2) * MT * DT * 256 * 4 + (size_t)(NWV / 2) * MT * 64 * 2 * 4;
     const size_t sm = main_b > merge_b ? main_b : merge_b;
