@@ -1,5 +1,6 @@
 """CPU oracle for one draft-then-verify iteration of multi-layer-draft-head
-speculative decoding (paper sections 2.1, 2.2 and 3.1).
+speculative decoding (paper sections 2.1, 2.2 and 3.1) and, in `oracle.train`,
+for one adversarial training step of a draft head (section 3.2, Algorithm 1).
 
 TEST INFRASTRUCTURE ONLY.  Plain NumPy, written for checking by eye against the
 paper, not for speed.  Only the tests, the smoke check and the `cpu_baseline`
@@ -9,7 +10,8 @@ from the product.
 
 Parity status: every function here is pinned by CPU tests against something
 other than itself (sequential decoding per Eq. 1, brute-force ancestor closure,
-brute-force longest match, full sorts, closed forms).  The paper prints no
+brute-force longest match, full sorts, closed forms; the training step's
+backward formulas against finite differences of its losses).  The paper prints no
 worked numeric example for this path and its Tables 1-2 need trained weights
 and a benchmark that are not available, so those table cells are
 "parity unpinned" and out of scope.
@@ -22,3 +24,4 @@ from .spec import (target_rows, decode_one, prefill, verify_tree, accept_greedy,
                    greedy_reference, generate_speculative, mean_tokens_per_iteration, n_alpha)
 from .sampling import (softmax_t, inverse_cdf, draw_without_replacement, accept_sample,  # noqa: F401
                        eagle_expand_sample, generate_sampled, medusa_expand_sample)
+from . import train  # noqa: F401,E402
