@@ -314,6 +314,70 @@ koala_status koala_measure_stream_read(void *hip_stream, const void *buffer, siz
 koala_status koala_profile_begin(koala_ctx *ctx, int max_launches);
 koala_status koala_profile_end(koala_ctx *ctx, double *gemm_ms, int *gemm_launches, double *gemm_bytes);
 
+/* ---------------------------------------------------------------------------------------------
+ * Adversarial training step of a draft head (section 3.2, Algorithm 1).  These calls need no koala_ctx:
+ * every tensor is a dense row-major fp32 device array of the caller's, the calls only enqueue kernels on
+ * the given stream, and parameters are updated in place by plain gradient descent.
+ *
+ * The discriminator D (section 3.2: a linear layer followed by fully connected layers, as many as the
+ * draft head has layers) scores a row of token logits together with the target model's last hidden
+ * state h of that position: z = W_lin h (hidden -> vocab), u = z + logits, then n_fc fully connected
+ * layers with biases, ReLU between them, the last of width 1, and a sigmoid: D = sigmoid(s).  How the
+ * mapped hidden state and the logits are joined, the widths, the biases and the activation are this
+ * build's readings (the paper names the layers only); expectations are means over the n_rows positions.
+ * --------------------------------------------------------------------------------------------- */
+typedef struct {
+    int hidden, vocab;
+    int fc_hidden; /* width of the inner fully connected layers (unused when n_fc = 1) */
+    int n_fc;      /* fully connected layers, 1..3: vocab -> fc_hidden -> .. -> 1 */
+} koala_disc_shape;
+
+/* w_lin [vocab, hidden]; w_fc[k] [out_k, in_k] and b_fc[k] [out_k] with in_0 = vocab, inner widths
+ * fc_hidden, out of the last layer = 1; entries k >= n_fc are ignored. */
+typedef struct {
+    float *w_lin;
+    float *w_fc[3];
+    float *b_fc[3];
+} koala_disc_params;
+
+/* Bytes of device workspace the two discriminator calls need for n_rows positions. */
+koala_status koala_train_workspace_bytes(const koala_disc_shape *shape, int n_rows, size_t *out);
+
+/* Discriminator step (Algorithm 1, Eq. 6): L_D = -mean log(1 - D(d)) - mean log D(q) over the n_rows
+ * positions, its gradient with respect to every discriminator parameter, and params <- params - lr * grad
+ * (lr = 0: loss only).  h [n_rows, hidden], q_logits / d_logits [n_rows, vocab] (the target's and the draft
+ * head's logits of the same positions); loss_out device fp32 [1]: L_D before the update. */
+koala_status koala_train_disc_step(const koala_disc_shape *shape, const koala_disc_params *params,
+                                   void *hip_stream, int n_rows, const float *h, const float *q_logits,
+                                   const float *d_logits, float lr, void *workspace,
+                                   size_t workspace_bytes, float *loss_out);
+
+/* Draft-head side (Algorithm 1, Eq. 5) at the logits: L_G = -lambda * mean log D(d) + L_Distill(d, q) with
+ * L_Distill the cross-entropy of softmax(d) against softmax(q) (mean over positions).
+ *   loss_out device fp32 [2] (out): the adversarial term and the distillation term;
+ *   grad_d   device fp32 [n_rows, vocab] (out): dL_G / dd, what the draft head's backward pass starts from.
+ * The discriminator's parameters are read only. */
+koala_status koala_train_gen_grad(const koala_disc_shape *shape, const koala_disc_params *params,
+                                  void *hip_stream, int n_rows, const float *h, const float *q_logits,
+                                  const float *d_logits, float lambda, void *workspace,
+                                  size_t workspace_bytes, float *loss_out, float *grad_d);
+
+/* A Medusa-style head in training (section 3.1: K residual blocks x <- x + SiLU(W_k x) followed by the
+ * target's LM head, which stays fixed): blocks_w host array of K device pointers to W_k [hidden, hidden],
+ * w_lm [vocab, hidden], h [n_rows, hidden].
+ *   _forward: d_logits [n_rows, vocab] (out) = the head's logits;
+ *   _step:    given grad_d = dL_G / dd (koala_train_gen_grad), the head's backward pass and
+ *             W_k <- W_k - lr * dL_G/dW_k for every block (the draft-head update of Algorithm 1).
+ * An EAGLE-style head's backward pass (decoder layers with attention) is not provided.  K <= 8. */
+koala_status koala_train_medusa_workspace_bytes(int n_rows, int hidden, int K, size_t *out);
+koala_status koala_train_medusa_head_forward(void *hip_stream, int n_rows, int hidden, int vocab, int K,
+                                             float *const *blocks_w, const float *w_lm, const float *h,
+                                             void *workspace, size_t workspace_bytes, float *d_logits);
+koala_status koala_train_medusa_head_step(void *hip_stream, int n_rows, int hidden, int vocab, int K,
+                                          float *const *blocks_w, const float *w_lm, const float *h,
+                                          const float *grad_d, float lr, void *workspace,
+                                          size_t workspace_bytes);
+
 /* Text of the last error on this context ("" if none); valid until the next call. */
 const char *koala_last_error(const koala_ctx *ctx);
 

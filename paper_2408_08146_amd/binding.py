@@ -10,7 +10,9 @@ KOALA_DRAFT_EAGLE, KOALA_DRAFT_MEDUSA = 0, 1
 EXPORTS = ("koala_create", "koala_workspace_bytes", "koala_bind", "koala_draft_expand",
            "koala_tree_verify", "koala_accept_prefix", "koala_generate", "koala_draft_expand_sample",
            "koala_accept_sample", "koala_accept_sample_static", "koala_generate_sample", "koala_measure_stream_read", "koala_profile_begin",
-           "koala_profile_end", "koala_last_error", "koala_destroy")
+           "koala_profile_end", "koala_train_workspace_bytes", "koala_train_disc_step", "koala_train_gen_grad",
+           "koala_train_medusa_workspace_bytes", "koala_train_medusa_head_forward", "koala_train_medusa_head_step",
+           "koala_last_error", "koala_destroy")
 
 _STATUS = {0: "KOALA_OK", -1: "KOALA_E_NULL", -2: "KOALA_E_SHAPE", -3: "KOALA_E_ALIGN",
            -4: "KOALA_E_CAPACITY", -5: "KOALA_E_UNSUPPORTED", -6: "KOALA_E_WORKSPACE",
@@ -46,6 +48,14 @@ class _Weights(C.Structure):
 
 class _GenStats(C.Structure):
     _fields_ = [("iterations", C.c_int32), ("tokens", C.c_int32), ("accept_hist", C.c_int32 * 64)]
+
+
+class _DiscShape(C.Structure):
+    _fields_ = [("hidden", C.c_int), ("vocab", C.c_int), ("fc_hidden", C.c_int), ("n_fc", C.c_int)]
+
+
+class _DiscParams(C.Structure):
+    _fields_ = [("w_lin", C.c_void_p), ("w_fc", C.c_void_p * 3), ("b_fc", C.c_void_p * 3)]
 
 
 class _KV(C.Structure):
@@ -88,11 +98,20 @@ def load_library():
     lib.koala_measure_stream_read.argtypes = [vp, vp, C.c_size_t, vp, ip, C.POINTER(C.c_double)]
     lib.koala_profile_begin.argtypes = [vp, ip]
     lib.koala_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(ip), C.POINTER(C.c_double)]
+    fl = C.c_float
+    lib.koala_train_workspace_bytes.argtypes = [C.POINTER(_DiscShape), ip, C.POINTER(C.c_size_t)]
+    lib.koala_train_disc_step.argtypes = [C.POINTER(_DiscShape), C.POINTER(_DiscParams), vp, ip, vp, vp, vp, fl, vp,
+                                          C.c_size_t, vp]
+    lib.koala_train_gen_grad.argtypes = [C.POINTER(_DiscShape), C.POINTER(_DiscParams), vp, ip, vp, vp, vp, fl, vp,
+                                         C.c_size_t, vp, vp]
+    lib.koala_train_medusa_workspace_bytes.argtypes = [ip, ip, ip, C.POINTER(C.c_size_t)]
+    lib.koala_train_medusa_head_forward.argtypes = [vp, ip, ip, ip, ip, C.POINTER(vp), vp, vp, vp, C.c_size_t, vp]
+    lib.koala_train_medusa_head_step.argtypes = [vp, ip, ip, ip, ip, C.POINTER(vp), vp, vp, vp, fl, vp, C.c_size_t]
     lib.koala_last_error.argtypes = [vp]
     lib.koala_last_error.restype = C.c_char_p
     lib.koala_destroy.argtypes = [vp]
     lib.koala_destroy.restype = None
-    for n in EXPORTS[:14]:
+    for n in EXPORTS[:20]:
         getattr(lib, n).restype = C.c_int
     _LIB = lib
     return lib
@@ -244,3 +263,86 @@ class KoalaContext:
             self.close()
         except Exception:
             pass
+
+
+class Discriminator:
+    """Discriminator of the adversarial training step (section 3.2) bound to fp32 device tensors:
+    w_lin [vocab, hidden], w_fc / b_fc lists of the fully connected layers' weights and biases."""
+
+    def __init__(self, w_lin, w_fc, b_fc, fc_hidden=0):
+        self.lib = load_library()
+        self.w_lin, self.w_fc, self.b_fc = w_lin, list(w_fc), list(b_fc)
+        V, H = w_lin.shape
+        self.shape = _DiscShape(H, V, int(fc_hidden), len(self.w_fc))
+        p = _DiscParams()
+        p.w_lin = w_lin.data_ptr()
+        for k in range(len(self.w_fc)):
+            p.w_fc[k] = self.w_fc[k].data_ptr()
+            p.b_fc[k] = self.b_fc[k].data_ptr()
+        self.params = p
+        self._ws = None
+
+    def _workspace(self, n):
+        import torch
+        need = C.c_size_t()
+        rc = self.lib.koala_train_workspace_bytes(C.byref(self.shape), n, C.byref(need))
+        if rc != 0:
+            raise KoalaError(rc, "koala_train_workspace_bytes")
+        if self._ws is None or self._ws.numel() < need.value:
+            self._ws = torch.empty(need.value, dtype=torch.uint8, device=self.w_lin.device)
+        return self._ws
+
+    def step(self, h, q_logits, d_logits, lr, loss_out, stream=None):
+        ws = self._workspace(h.shape[0])
+        rc = self.lib.koala_train_disc_step(C.byref(self.shape), C.byref(self.params), _stream(stream), h.shape[0],
+                                            _ptr(h), _ptr(q_logits), _ptr(d_logits), float(lr), _ptr(ws), ws.numel(),
+                                            _ptr(loss_out))
+        if rc != 0:
+            raise KoalaError(rc, "koala_train_disc_step")
+
+    def gen_grad(self, h, q_logits, d_logits, lam, loss_out, grad_d, stream=None):
+        ws = self._workspace(h.shape[0])
+        rc = self.lib.koala_train_gen_grad(C.byref(self.shape), C.byref(self.params), _stream(stream), h.shape[0],
+                                           _ptr(h), _ptr(q_logits), _ptr(d_logits), float(lam), _ptr(ws), ws.numel(),
+                                           _ptr(loss_out), _ptr(grad_d))
+        if rc != 0:
+            raise KoalaError(rc, "koala_train_gen_grad")
+
+
+class MedusaHeadTrainer:
+    """One Medusa-style head in training: blocks = list of K fp32 device tensors [hidden, hidden] (updated in
+    place), w_lm [vocab, hidden] fixed."""
+
+    def __init__(self, blocks, w_lm):
+        self.lib = load_library()
+        self.blocks, self.w_lm = list(blocks), w_lm
+        self.K = len(self.blocks)
+        self.V, self.H = w_lm.shape
+        self._arr = (C.c_void_p * self.K)(*[b.data_ptr() for b in self.blocks])
+        self._ws = None
+
+    def _workspace(self, n):
+        import torch
+        need = C.c_size_t()
+        rc = self.lib.koala_train_medusa_workspace_bytes(n, self.H, self.K, C.byref(need))
+        if rc != 0:
+            raise KoalaError(rc, "koala_train_medusa_workspace_bytes")
+        if self._ws is None or self._ws.numel() < need.value:
+            self._ws = torch.empty(need.value, dtype=torch.uint8, device=self.w_lm.device)
+        return self._ws
+
+    def forward(self, h, d_logits, stream=None):
+        ws = self._workspace(h.shape[0])
+        rc = self.lib.koala_train_medusa_head_forward(_stream(stream), h.shape[0], self.H, self.V, self.K,
+                                                      C.cast(self._arr, C.POINTER(C.c_void_p)), _ptr(self.w_lm),
+                                                      _ptr(h), _ptr(ws), ws.numel(), _ptr(d_logits))
+        if rc != 0:
+            raise KoalaError(rc, "koala_train_medusa_head_forward")
+
+    def step(self, h, grad_d, lr, stream=None):
+        ws = self._workspace(h.shape[0])
+        rc = self.lib.koala_train_medusa_head_step(_stream(stream), h.shape[0], self.H, self.V, self.K,
+                                                   C.cast(self._arr, C.POINTER(C.c_void_p)), _ptr(self.w_lm), _ptr(h),
+                                                   _ptr(grad_d), float(lr), _ptr(ws), ws.numel())
+        if rc != 0:
+            raise KoalaError(rc, "koala_train_medusa_head_step")

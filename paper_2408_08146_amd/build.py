@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libkoala.so")
-SOURCES = ["koala_api.hip", "kernels_generic.hip", "kernels_bf16.hip", "kernels_sampling.hip"]
+SOURCES = ["koala_api.hip", "kernels_generic.hip", "kernels_bf16.hip", "kernels_sampling.hip", "koala_train.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
