@@ -172,6 +172,46 @@ def generation_bench(args):
         "speculative": res["speculative"], "plain": res["plain"]}))
 
 
+def training_bench(args):
+    """One adversarial training step (section 3.2, Algorithm 1) at the 7B head's sizes: discriminator step,
+    draft-head loss/gradient at the logits, and a Medusa-style head's forward + update; fp32, synthetic data."""
+    import torch
+    import paper_2408_08146_amd as KO
+    dev = "cuda:0"
+    H, V, DH, n_fc, Kb, N = 4096, 32000, 1024, 2, 2, args.train
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    rnd = lambda *s: torch.randn(*s, generator=g, device=dev, dtype=torch.float32)
+    D = KO.Discriminator(rnd(V, H) * 0.02, [rnd(DH, V) * 0.02, rnd(1, DH) * 0.02], [rnd(DH) * 0.02, rnd(1) * 0.02],
+                         fc_hidden=DH)
+    head = KO.MedusaHeadTrainer([rnd(H, H) * 0.02 for _ in range(Kb)], rnd(V, H) * 0.02)
+    h, q = rnd(N, H), rnd(N, V) * 2.0
+    d = torch.zeros(N, V, device=dev)
+    grad = torch.zeros(N, V, device=dev)
+    loss = torch.zeros(3, device=dev)
+
+    def step():
+        head.forward(h, d)
+        D.gen_grad(h, q, d, 0.5, loss[:2], grad)
+        head.step(h, grad, 1e-3)
+        D.step(h, q, d, 1e-3, loss[2:])
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    flops = 2.0 * N * (V * H * 4 + DH * V * 5 + Kb * H * H * 3 + V * H * 2)   # dense products of one g-step + d-step
+    print(json.dumps({"metric": "adversarial_training_steps_per_s", "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1,
+                      "steps": args.steps, "ms_per_step": ms, "higher_is_better": True, "dtype": "f32",
+                      "data": "synthetic", "vs_baseline": None,
+                      "config": {"workload": f"one g-step + one d-step, {N} positions, hidden {H}, vocab {V}, "
+                                             f"discriminator Linear + {n_fc} FC (width {DH}), Medusa-style head K={Kb}"},
+                      "approx_tflops": flops / (ms * 1e-3) / 1e12, "losses_adv_distill_disc": loss.tolist()}))
+
+
 def cpu_baseline(cfg, tree, K, levels):
     """Time the unmodified fp32 oracle on a bounded sample: tree_verify over 2 of the target layers
     plus final norm / LM head / argmax, and one EAGLE draft pass (fc + K layers + LM head + top-k) for
@@ -288,6 +328,8 @@ def main():
                          "negative = random weights (the draft is almost never right)")
     ap.add_argument("--sample", type=int, default=0,
                     help="1: time the non-greedy iteration (sampled draft, stochastic acceptance) instead of the greedy one")
+    ap.add_argument("--train", type=int, default=0,
+                    help="N > 0: time one adversarial training step (g-step + d-step) on N positions instead")
     ap.add_argument("--warmup-gen", type=int, default=1)
     ap.add_argument("--repeat-gen", type=int, default=3)
     args = ap.parse_args()
@@ -296,6 +338,8 @@ def main():
         sys.exit(2)
     if args.generate > 0:
         return generation_bench(args)
+    if args.train > 0:
+        return training_bench(args)
 
     import torch
     import paper_2408_08146_amd as KO
