@@ -291,21 +291,32 @@ def cpu_baseline(cfg, tree, K, levels):
 
 
 def gpu_state():
-    """Clocks, power and performance level of GPU 0 as rocm-smi reports them (None if it cannot be run)."""
-    import subprocess
-    try:
-        r = subprocess.run(["rocm-smi", "-d", "0", "--showclocks", "--showpower", "--showperflevel", "--json"],
-                           capture_output=True, text=True, timeout=20)
-        d = json.loads(r.stdout)
-        card = d[sorted(d.keys())[0]]
-        keep = {}
-        for k, v in card.items():
-            kl = k.lower()
-            if any(t in kl for t in ("sclk", "mclk", "fclk", "socclk", "power", "performance level")):
-                keep[k] = v
-        return keep or None
-    except Exception:
-        return None
+    """Clock levels, power and performance level of the first AMD GPU as sysfs reports them (plain file reads:
+    no child process is started once the GPU is in use); None where the files are not there."""
+    import glob
+    out = {}
+    for dev in sorted(glob.glob("/sys/class/drm/card*/device")):
+        if not os.path.exists(os.path.join(dev, "pp_dpm_sclk")):
+            continue
+
+        def rd(name):
+            try:
+                return open(os.path.join(dev, name)).read().strip()
+            except OSError:
+                return None
+        for key in ("pp_dpm_sclk", "pp_dpm_mclk", "pp_dpm_fclk", "power_dpm_force_performance_level"):
+            v = rd(key)
+            if v is not None:
+                active = [ln.strip() for ln in v.splitlines() if ln.strip().endswith("*")]
+                out[key] = active[0] if active else v.splitlines()[-1] if key.startswith("pp_dpm") else v
+        for hw in glob.glob(os.path.join(dev, "hwmon", "hwmon*")):
+            for key in ("power1_average", "power1_input", "power1_cap"):
+                try:
+                    out[key + "_W"] = int(open(os.path.join(hw, key)).read()) / 1e6
+                except (OSError, ValueError):
+                    pass
+        break
+    return out or None
 
 
 def main():
