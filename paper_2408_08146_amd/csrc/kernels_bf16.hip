@@ -421,19 +421,38 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
 // gives every result a new register and copies it back, which costs more than the MFMA itself.  An MFMA may
 // follow another that wrote its accumulator operand without waiting when both name the same registers, as here.
 __device__ __forceinline__ void mfma_acc(f32x4 &acc, bf16x8 a, bf16x8 b) {
-    asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// 16 bytes per lane from LDS at base + a constant byte offset (below 64 KiB), as an instruction of its own: the
+// result may be used only after a wait that covers it (wait_lds_reads).
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+__device__ __forceinline__ u32x4 lds_read16(lds_u32x4 *base, int byte_offset) {
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(base), "n"(byte_offset));
+    return v;
+}
+// waits until at most n of this wave's LDS reads are still under way (they complete in issue order)
+__device__ __forceinline__ void wait_lds_reads(int n) {
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(n));
 }
 
 template <int U, int MTW>
-__global__ __launch_bounds__(256, U * MTW <= 24 ? 2 : 1) void k_gemm_big(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
+__global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
                                                      float *__restrict__ P, int Npad, int K, int S, int MTT, int n_mt,
                                                      int n_pm) {
     extern __shared__ __attribute__((aligned(16))) unsigned char bsm[];
     typedef __attribute__((address_space(3))) void lds_void;
     typedef const __attribute__((address_space(1))) void glb_void;
     constexpr int XT = 2 * MTW * 2 * 64;   // 16-byte units of one 64-k tile of activations: [s][m][hi, lo][64]
+    constexpr int XD = 4;                  // (s, m) pairs of activation fragments read from LDS ahead of their use
+    constexpr int NP = 2 * MTW;            // (s, m) pairs per tile
+    constexpr int NOPS = MTW + 1 + 2 * U;  // load steps of a wave per tile: its share of X(t+1), the touches, then W(t+3)
     u32x4 *xs = (u32x4 *)bsm;              // [2][XT]
-    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
+    // the wave number as a scalar: everything derived from it (which weight rows, which pieces of the activation
+    // tile this wave fetches, where they land in LDS) is then computed once per wave, not per lane
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
     const int nunits = Npad / 16, ngrp = (nunits + 4 * U - 1) / (4 * U);
     int bid = blockIdx.x;
     const int g = bid % ngrp; bid /= ngrp;
@@ -442,29 +461,43 @@ __global__ __launch_bounds__(256, U * MTW <= 24 ? 2 : 1) void k_gemm_big(const u
     const int nkt = K / 64;
     const int kt0 = (int)((long long)sp * nkt / S), kt1 = (int)((long long)(sp + 1) * nkt / S);
     const int ug0 = (g * 4 + wave) * U;
-    const u32x4 *w[U];
+    // Addresses are a kernel argument plus a 32-bit byte offset (the launcher checks that both operands are
+    // smaller than 4 GiB): the per-lane part of the offset is computed once, the per-tile part is one addition.
+    const char *Wb = (const char *)Wp, *Xb = (const char *)Xf;
+    unsigned woff[U];
 #pragma unroll
     for (int j = 0; j < U; ++j) {
         const int ug = min(ug0 + j, nunits - 1);
-        w[j] = Wp + ((size_t)(ug >> 2) * nkt * 8 + (ug & 3) * 2) * 64 + l;
+        woff[j] = (unsigned)(((size_t)(ug >> 2) * nkt * 8 + (ug & 3) * 2) * 1024) + l * 16;
     }
     u32x4 wr[4][U][2];   // ring of weight fragments: tile t lives in slot (t - kt0) % 4
-    auto wload = [&](int kt, int slot) {
-#pragma unroll
-        for (int j = 0; j < U; ++j)
-#pragma unroll
-            for (int s = 0; s < 2; ++s) wr[slot][j][s] = __builtin_nontemporal_load(w[j] + (size_t)kt * 512 + s * 64);
+    // weight fragment (j, s) of tile kt into ring slot `slot`
+    auto wload1 = [&](int q, int kt, int slot) {
+        const int j = q >> 1, s = q & 1;
+        wr[slot][j][s] = __builtin_nontemporal_load((const u32x4 *)(Wb + (woff[j] + (unsigned)kt * 8192u + s * 1024u)));
     };
-    // fragments (s, m, hl) of tile kt -> LDS buffer b: 2 * MTW * 2 one-KiB pieces, dealt to the waves in turn
-    // (tiles past the last one re-read it: computed, never stored)
-    auto xfill = [&](int kt, int b) {
+    // The 2 * MTW * 2 one-KiB pieces (s, m, hl) of an activation tile are dealt to the waves in turn; piece i of this
+    // wave for tile kt goes to LDS buffer b (tiles past the last one re-read it: computed, never stored)
+    const unsigned xstride = (unsigned)MTT * 4096u;   // bytes of the activation fragments of one 64-k tile
+    auto xfill1 = [&](int i, int kt, int b) {
+        const int f = wave + 4 * i, hl = f & 1, m = (f >> 1) % MTW, s = (f >> 1) / MTW;
+        const unsigned off = (unsigned)((s * MTT + min(mt0 + m, MTT - 1)) * 2 + hl) * 1024u + (unsigned)kt * xstride;
+        u32x4 *dst = xs + (size_t)b * XT + ((s * MTW + m) * 2 + hl) * 64;   // wave-uniform; lane i lands at dst + i
+        __builtin_amdgcn_global_load_lds((glb_void *)(Xb + (off + (unsigned)l * 16u)), (lds_void *)dst, 16, 0, 0);
+    };
+    // The activation fragments of a 64-k tile are two runs of MTW * 2 KiB (one per k half).  They are touched two
+    // tiles ahead with one 4-byte load per 128-byte line (one line per lane and run, lanes past the end repeat the
+    // last line), so that the copy into LDS one tile later finds them in L2 instead of waiting for HBM.  The
+    // touches are loads to LDS as well, into 256 bytes per wave behind the tile buffers that nobody reads: a load
+    // into a register nobody reads would have that register handed to another value while the load is under way.
+    const int pf_lines = min(MTW, MTT - mt0) * 16;
+    const unsigned pf_off = (unsigned)mt0 * 2048u + (unsigned)min((int)threadIdx.x, pf_lines - 1) * 128u;
+    unsigned char *pf_sink = bsm + (size_t)2 * XT * 16 + wave * 256;
+    auto xtouch = [&](int kt) {
 #pragma unroll
-        for (int i = 0; i < MTW; ++i) {
-            const int f = wave + 4 * i, hl = f & 1, m = (f >> 1) % MTW, s = (f >> 1) / MTW;
-            const u32x4 *src = Xf + (((size_t)(2 * kt + s) * MTT + min(mt0 + m, MTT - 1)) * 2 + hl) * 64 + l;
-            u32x4 *dst = xs + (size_t)b * XT + ((s * MTW + m) * 2 + hl) * 64;   // wave-uniform; lane i lands at dst + i
-            __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)dst, 16, 0, 0);
-        }
+        for (int s = 0; s < 2; ++s)
+            __builtin_amdgcn_global_load_lds((glb_void *)(Xb + (pf_off + (unsigned)(2 * kt + s) * ((unsigned)MTT * 2048u))),
+                                             (lds_void *)pf_sink, 4, 0, 0);
     };
     f32x4 acc[U][MTW];
 #pragma unroll
@@ -472,45 +505,96 @@ __global__ __launch_bounds__(256, U * MTW <= 24 ? 2 : 1) void k_gemm_big(const u
 #pragma unroll
         for (int m = 0; m < MTW; ++m) acc[j][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
     // Memory operations complete in issue order.  Issued before the loop: W(kt0), W(kt0+1), W(kt0+2), X(kt0), all
-    // awaited.  The iteration of tile t issues X(t+1) and then W(t+3) (into the ring slot tile t-1 has left).  At
-    // the top of the next iteration only those 2 U weight loads may still be under way: X(t+1) and every older
-    // load have landed, and a weight tile has two iterations to arrive from HBM.  Past the last tile the same
-    // loads are issued again for the last tile, so that the count the wait relies on stays the same.
-    constexpr int VM = 2 * U;
-    constexpr int WAIT_BUT_NEWEST = (VM & 15) | (7 << 4) | (15 << 8) | ((VM >> 4) << 14);   // s_waitcnt vmcnt(2U)
+    // awaited.  The iteration of tile t issues this wave's pieces of X(t+1) and then W(t+3) (into the ring slot
+    // tile t-1 has left), one load between the MFMAs of every (s, m) pair, so that neither the address arithmetic
+    // nor the issue of the loads holds the matrix pipe up.  At the top of the next iteration only those 2 U weight
+    // loads may still be under way: X(t+1) and every older load have landed, and a weight tile has two iterations
+    // to arrive from HBM.  Between the two come the two touches of X(t+3), which may stay under way as well (X(t+1),
+    // issued before them, has landed all the same).  Past the last tile the same loads are issued again for the last tile, so that the count the wait
+    // relies on stays the same.
+    constexpr int VM = 2 * U + 2;
+    constexpr int WAIT_BUT_NEWEST = (VM & 15) | (7 << 4) | (15 << 8) | ((VM >> 4) << 14);   // s_waitcnt vmcnt(2U + 2)
     const int last = kt1 - 1;
     if (kt0 < kt1) {
-        wload(kt0, 0);
-        wload(min(kt0 + 1, last), 1);
-        wload(min(kt0 + 2, last), 2);
-        xfill(kt0, 0);
+#pragma unroll
+        for (int q = 0; q < 2 * U; ++q) wload1(q, kt0, 0);
+#pragma unroll
+        for (int q = 0; q < 2 * U; ++q) wload1(q, min(kt0 + 1, last), 1);
+#pragma unroll
+        for (int q = 0; q < 2 * U; ++q) wload1(q, min(kt0 + 2, last), 2);
+#pragma unroll
+        for (int i = 0; i < MTW; ++i) xfill1(i, kt0, 0);
+        xtouch(min(kt0 + 1, last));
+        xtouch(min(kt0 + 2, last));
         __builtin_amdgcn_s_waitcnt(0);
     }
-    for (int t = kt0; t < kt1; t += 4) {
+    // One 64-k tile; p = (tt - kt0) % 4 says where it lives in the weight ring and the LDS buffers.  The tiles come
+    // in groups of four with no decisions in between (so that the compiler's view of which loads are under way
+    // stays exact from one group to the next), followed by up to three tiles of a last, partial group.
+    auto tile = [&](int tt, auto pc) __attribute__((always_inline)) {
+        constexpr int p = decltype(pc)::value;
+        __builtin_amdgcn_s_waitcnt(WAIT_BUT_NEWEST);   // nothing is under way before the first tile
+        // every wave's part of X(tt) is in LDS; nobody still reads the other buffer.  A bare barrier instruction
+        // (the waits it needs are the ones above), fenced for the compiler so that no LDS access crosses it
+        asm volatile("s_barrier" ::: "memory");
+        // The activation fragments come from LDS through a ring of XD + 1 register pairs (hi, lo), read XD
+        // (s, m) pairs ahead of the MFMAs that use them, because an LDS read takes longer than the 2 U MFMAs
+        // of one pair.  Reads and waits are written out as instructions: LDS reads complete in issue order,
+        // so "at most 2 (XD - 1) reads still under way" says exactly that the pair about to be used has
+        // arrived, which the compiler's own bookkeeping rounds down to "none under way" for operands of the
+        // MFMA statement above.  The results of such a read must stay where they are until that wait, which
+        // holds as long as the kernel does not spill (one workgroup per compute unit: 512 registers a lane).
+        // The scheduling fences keep the statements in the order written: other instructions go between
+        // the MFMAs, a few at a time, where the matrix pipe is busy anyway.
+        lds_u32x4 *xb = (lds_u32x4 *)(xs + (size_t)(p & 1) * XT + l);
+        const int ktx = min(tt + 1, last), ktw = min(tt + 3, last);
+        u32x4 xr[XD + 1][2];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int tt = t + p;
-            if (tt < kt1) {
-                if (tt > kt0) __builtin_amdgcn_s_waitcnt(WAIT_BUT_NEWEST);
-                __syncthreads();   // every wave's part of X(tt) is in LDS; nobody still reads the other buffer
-                xfill(min(tt + 1, last), (p + 1) & 1);
-                wload(min(tt + 3, last), (p + 3) & 3);
-                const u32x4 *xb = xs + (size_t)(p & 1) * XT + l;
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-#pragma unroll
-                    for (int m = 0; m < MTW; ++m) {
-                        const bf16x8 xh = __builtin_bit_cast(bf16x8, xb[((s * MTW + m) * 2 + 0) * 64]);
-                        const bf16x8 xl = __builtin_bit_cast(bf16x8, xb[((s * MTW + m) * 2 + 1) * 64]);
-#pragma unroll
-                        for (int j = 0; j < U; ++j) mfma_acc(acc[j][m], __builtin_bit_cast(bf16x8, wr[p][j][s]), xh);
-#pragma unroll
-                        for (int j = 0; j < U; ++j) mfma_acc(acc[j][m], __builtin_bit_cast(bf16x8, wr[p][j][s]), xl);
-                    }
-                }
-            }
+        for (int i = 0; i < XD; ++i) {
+            xr[i][0] = lds_read16(xb, (i * 2 + 0) * 1024);
+            xr[i][1] = lds_read16(xb, (i * 2 + 1) * 1024);
         }
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int s = i / MTW, m = i % MTW;
+            wait_lds_reads(2 * (NP - 1 - i < XD - 1 ? NP - 1 - i : XD - 1));   // reads issued after pair i's
+            const bf16x8 xh = __builtin_bit_cast(bf16x8, xr[i % (XD + 1)][0]);
+            const bf16x8 xl = __builtin_bit_cast(bf16x8, xr[i % (XD + 1)][1]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_acc(acc[0][m], __builtin_bit_cast(bf16x8, wr[p][0][s]), xh);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + XD < NP) xr[(i + XD) % (XD + 1)][0] = lds_read16(xb, ((i + XD) * 2 + 0) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_acc(acc[1][m], __builtin_bit_cast(bf16x8, wr[p][1][s]), xh);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + XD < NP) xr[(i + XD) % (XD + 1)][1] = lds_read16(xb, ((i + XD) * 2 + 1) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 2; j < U; ++j) mfma_acc(acc[j][m], __builtin_bit_cast(bf16x8, wr[p][j][s]), xh);
+            __builtin_amdgcn_sched_barrier(0);
+            // this pair's share of the tile's global loads: X pieces first, then W fragments
+#pragma unroll
+            for (int q = i * NOPS / NP; q < (i + 1) * NOPS / NP; ++q) {
+                if (q < MTW) xfill1(q, ktx, (p + 1) & 1);
+                else if (q == MTW) xtouch(ktw);
+                else wload1(q - MTW - 1, ktw, (p + 3) & 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < U; ++j) mfma_acc(acc[j][m], __builtin_bit_cast(bf16x8, wr[p][j][s]), xl);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    int t = kt0;
+    for (; t + 4 <= kt1; t += 4) {
+        tile(t, std::integral_constant<int, 0>{});
+        tile(t + 1, std::integral_constant<int, 1>{});
+        tile(t + 2, std::integral_constant<int, 2>{});
+        tile(t + 3, std::integral_constant<int, 3>{});
     }
+    if (t < kt1) tile(t, std::integral_constant<int, 0>{});
+    if (t + 1 < kt1) tile(t + 1, std::integral_constant<int, 1>{});
+    if (t + 2 < kt1) tile(t + 2, std::integral_constant<int, 2>{});
     // results of the matrix pipe may be read by other instructions only some cycles after the last MFMA was issued
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     __syncthreads();
@@ -1006,39 +1090,48 @@ void gemm_rows_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int
                                    ev_stop);
 }
 
-// Launch shape of gemm_big for `rows` activation rows: activation tiles per workgroup (at most 15), weight row
-// groups per wave (3, 4 or 5) and K splits, chosen so that the workgroups (one per compute unit) cover the
-// chip in as few, as full rounds as possible; splits cost partial-sum traffic and are taken only when they pay.
+// Launch shape of gemm_big for `rows` activation rows: how many blocks the activation tiles are cut into (each
+// block streams the weights once, with up to 15 tiles per workgroup), weight row groups per wave (3, 4 or 5) and
+// K splits.  Every candidate is priced with a small model of the kernel, in cycles: a workgroup's 64-k tiles cost
+// their MFMAs plus a fixed amount (barrier, first LDS reads), a workgroup costs its start-up and its stores, the
+// launch takes as many rounds as its workgroups need on the chip's compute units (one workgroup each) but at
+// least the time to stream the weights once per tile block, and the partial sums of the splits are written once and read once by the kernel that folds them.
 BigShape big_shape(int Npad, int K, int rows, int n_cu) {
     BigShape b{};
     b.n_mt = (rows + 15) / 16;
-    b.n_pm = (b.n_mt + 14) / 15;
-    static const int fpm = getenv("KOALA_BIG_PM") ? atoi(getenv("KOALA_BIG_PM")) : 0;   // tuning aid: tile blocks
-    if (fpm > b.n_pm && fpm <= b.n_mt) b.n_pm = fpm;
-    b.mtw = (b.n_mt + b.n_pm - 1) / b.n_pm;
     const int units = Npad / 16, nkt = K / 64;
-    double best = -1.0;
-    const int tmpl = b.mtw <= 8 ? 8 : b.mtw <= 10 ? 10 : 15;   // activation tiles the kernel is instantiated for
-    for (int U = 5; U >= 3; --U)
-        for (int S = 1; S <= 4 && S <= nkt; ++S) {
-            if (U * tmpl > 60) continue;   // the accumulator tiles of a wave must fit the 256 accumulation registers
-            const int wgs = ((units + 4 * U - 1) / (4 * U)) * b.n_pm * S, rounds = (wgs + n_cu - 1) / n_cu;
-            // fewer row groups per wave mean more LDS reads per MFMA; more splits, more partial sums
-            const double score = (double)wgs / ((double)rounds * n_cu) - 0.04 * (S - 1) - 0.03 * (5 - U);
-            if (score > best) { best = score; b.U = U; b.S = S; }
-        }
-    // tuning aids, read once: force the row groups per wave / the K splits
+    // tuning aids, read once: force the tile blocks / the row groups per wave / the K splits
+    static const int fpm = getenv("KOALA_BIG_PM") ? atoi(getenv("KOALA_BIG_PM")) : 0;
     static const int fu = getenv("KOALA_BIG_U") ? atoi(getenv("KOALA_BIG_U")) : 0;
     static const int fs = getenv("KOALA_BIG_S") ? atoi(getenv("KOALA_BIG_S")) : 0;
-    if (fu >= 3 && fu <= 5 && fu * tmpl <= 60) b.U = fu;
-    if (fs >= 1 && fs <= 4 && fs <= nkt) b.S = fs;
+    double best = 1e300;
+    const int pm_lo = (b.n_mt + 14) / 15;
+    for (int n_pm = pm_lo; n_pm <= std::min(b.n_mt, pm_lo + 3); ++n_pm) {
+        if (fpm >= pm_lo && fpm <= b.n_mt && n_pm != fpm && fpm <= pm_lo + 3) continue;
+        const int mtw = (b.n_mt + n_pm - 1) / n_pm;
+        const int tmpl = mtw <= 8 ? 8 : mtw <= 10 ? 10 : 15;   // activation tiles the kernel is instantiated for
+        for (int U = 5; U >= 3; --U) {
+            if (U * tmpl > 60) continue;   // the accumulator tiles of a wave must fit the 256 accumulation registers
+            if (fu >= 3 && fu <= 5 && fu * tmpl <= 60 && U != fu) continue;
+            for (int S = 1; S <= 4 && S <= nkt; ++S) {
+                if (fs >= 1 && fs <= 4 && fs <= nkt && S != fs) continue;
+                const int wgs = ((units + 4 * U - 1) / (4 * U)) * n_pm * S, rounds = (wgs + n_cu - 1) / n_cu;
+                const double tiles = (double)((nkt + S - 1) / S);
+                const double wg = tiles * (64.0 * tmpl * U / 0.8 + 400.0) + 6000.0 + 30.0 * tmpl * U;
+                const double partials = S > 1 ? 2.0 * S * (double)rows * Npad * 4.0 / 4.0e12 * 2.2e9 : 0.0;
+                const double hbm = (double)n_pm * Npad * K * 2.0 / 5.0e12 * 2.2e9;   // every tile block streams the weights
+                const double cost = std::max(rounds * wg, hbm) + partials;
+                if (cost < best) { best = cost; b.n_pm = n_pm; b.mtw = mtw; b.U = U; b.S = S; }
+            }
+        }
+    }
     return b;
 }
 
 template <int U, int MTW>
 static void launch_gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT,
                             const BigShape &b, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    const size_t sm = (size_t)2 * 2 * MTW * 2 * 64 * 16;
+    const size_t sm = (size_t)2 * 2 * MTW * 2 * 64 * 16 + 4 * 256;   // two tile buffers + the sink of the touches
     static bool done = false;
     if (!done) {
         (void)hipFuncSetAttribute((const void *)k_gemm_big<U, MTW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);

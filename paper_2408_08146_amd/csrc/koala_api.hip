@@ -198,7 +198,10 @@ bool big_gemm_enabled() {
 int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT, int rows = 0) {
     const int Npad = kb::pad64(N);
     const LaunchEvents ev = timed_launch(c, (double)Npad * K * 2.0);
-    if (MT >= 8 && big_gemm_enabled()) {   // many rows: one pass over the weights with large register tiles
+    // many rows: one pass over the weights with large register tiles (the kernel addresses both operands with
+    // 32-bit byte offsets)
+    const bool fits32 = (double)Npad * K * 2.0 < 4.0e9 && (double)(K / 32) * MT * 2048.0 < 4.0e9;
+    if (MT >= 8 && fits32 && big_gemm_enabled()) {
         const kb::BigShape b = kb::big_shape(Npad, K, rows > 0 ? rows : MT * 16, c->n_cu);
         kb::gemm_big(st, Wp, c->xf, c->part, Npad, K, MT, b, ev.start, ev.stop);
         return b.S;
