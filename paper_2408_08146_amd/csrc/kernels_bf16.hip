@@ -437,10 +437,10 @@ __device__ __forceinline__ void wait_lds_reads(int n) {
     asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(n));
 }
 
-template <int U, int MTW>
+template <int U, int MTW, int EPI>
 __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xf,
                                                      float *__restrict__ P, int Npad, int K, int S, int MTT, int n_mt,
-                                                     int n_pm) {
+                                                     int n_pm, GemmEpi e) {
     extern __shared__ __attribute__((aligned(16))) unsigned char bsm[];
     typedef __attribute__((address_space(3))) void lds_void;
     typedef const __attribute__((address_space(1))) void glb_void;
@@ -493,6 +493,24 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
     const int pf_lines = min(MTW, MTT - mt0) * 16;
     const unsigned pf_off = (unsigned)mt0 * 2048u + (unsigned)min((int)threadIdx.x, pf_lines - 1) * 128u;
     unsigned char *pf_sink = bsm + (size_t)2 * XT * 16 + wave * 256;
+    // EPI_SWIGLU: RMSNorm's scale of each of the workgroup's rows (from the per-chunk sums of squares of the input
+    // rows), one row per thread, fetched now and parked in LDS behind the sinks until the epilogue
+    float *rsc_s = (float *)(bsm + (size_t)2 * XT * 16 + 4 * 256);   // [MTW * 16]
+    if (EPI == EPI_SWIGLU && threadIdx.x < MTW * 16) {
+        const int row = mt0 * 16 + threadIdx.x;
+        float tot = 0.f;
+        if (e.sums && row < e.rows) {
+            for (int c0 = 0; c0 < e.nparts; c0 += 8) {
+                float part[8];
+#pragma unroll
+                for (int c = 0; c < 8; ++c)
+                    part[c] = c0 + c < e.nparts ? e.sums[(size_t)(c0 + c) * e.srows + row] : 0.f;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) tot += part[c];
+            }
+        }
+        rsc_s[threadIdx.x] = e.sums ? 1.0f / sqrtf(tot / (float)e.Kn + e.eps) : 1.f;
+    }
     auto xtouch = [&](int kt) {
 #pragma unroll
         for (int s = 0; s < 2; ++s)
@@ -598,14 +616,39 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
     // results of the matrix pipe may be read by other instructions only some cycles after the last MFMA was issued
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     __syncthreads();
+    if (EPI == EPI_PARTIAL) {
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-        if (ug0 + j >= nunits) continue;
+        for (int j = 0; j < U; ++j) {
+            if (ug0 + j >= nunits) continue;
+#pragma unroll
+            for (int m = 0; m < MTW; ++m) {
+                if (m < mt_cnt) {
+                    const int row = (mt0 + m) * 16 + li, n = (ug0 + j) * 16 + 4 * lg;
+                    *(f32x4 *)(P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = acc[j][m];
+                }
+            }
+        }
+    } else {
+        // EPI_SWIGLU (one K split): the weight rows interleave gate and up, so a lane's four columns are (gate, up)
+        // of two features of one activation row.  RMSNorm's row scale (from the per-chunk sums of squares of the
+        // input rows) is applied, then SiLU(gate) * up, stored as hi/lo fragments of the down projection's input.
 #pragma unroll
         for (int m = 0; m < MTW; ++m) {
-            if (m < mt_cnt) {
-                const int row = (mt0 + m) * 16 + li, n = (ug0 + j) * 16 + 4 * lg;
-                *(f32x4 *)(P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = acc[j][m];
+            const int row = (mt0 + m) * 16 + li;
+            if (m >= mt_cnt || row >= e.rows) continue;
+            const float rsc = rsc_s[m * 16 + li];
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                const int n = (ug0 + j) * 16 + 4 * lg, f0 = n >> 1;
+                if (ug0 + j >= nunits || f0 >= e.F) continue;
+                const f32x4 v = acc[j][m] * rsc;
+                const float g0 = v[0], g1 = v[2];
+                const float y0 = g0 / (1.0f + __expf(-g0)) * v[1], y1 = g1 / (1.0f + __expf(-g1)) * v[3];
+                const HiLo pr = split_pair(y0, y1);
+                const int ks = f0 >> 5, lane = li + 16 * ((f0 & 31) >> 3);
+                uint32_t *dst = e.Xo + ((((size_t)ks * MTT + (mt0 + m)) * 2) * 64 + lane) * 4 + ((f0 & 7) >> 1);
+                dst[0] = pr.hi;
+                dst[64 * 4] = pr.lo;
             }
         }
     }
@@ -1096,7 +1139,7 @@ void gemm_rows_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int
 // their MFMAs plus a fixed amount (barrier, first LDS reads), a workgroup costs its start-up and its stores, the
 // launch takes as many rounds as its workgroups need on the chip's compute units (one workgroup each) but at
 // least the time to stream the weights once per tile block, and the partial sums of the splits are written once and read once by the kernel that folds them.
-BigShape big_shape(int Npad, int K, int rows, int n_cu) {
+BigShape big_shape(int Npad, int K, int rows, int n_cu, bool one_split) {
     BigShape b{};
     b.n_mt = (rows + 15) / 16;
     const int units = Npad / 16, nkt = K / 64;
@@ -1114,7 +1157,7 @@ BigShape big_shape(int Npad, int K, int rows, int n_cu) {
             if (U * tmpl > 60) continue;   // the accumulator tiles of a wave must fit the 256 accumulation registers
             if (fu >= 3 && fu <= 5 && fu * tmpl <= 60 && U != fu) continue;
             for (int S = 1; S <= 4 && S <= nkt; ++S) {
-                if (fs >= 1 && fs <= 4 && fs <= nkt && S != fs) continue;
+                if (one_split ? S != 1 : (fs >= 1 && fs <= 4 && fs <= nkt && S != fs)) continue;
                 const int wgs = ((units + 4 * U - 1) / (4 * U)) * n_pm * S, rounds = (wgs + n_cu - 1) / n_cu;
                 const double tiles = (double)((nkt + S - 1) / S);
                 const double wg = tiles * (64.0 * tmpl * U / 0.8 + 400.0) + 6000.0 + 30.0 * tmpl * U;
@@ -1128,36 +1171,53 @@ BigShape big_shape(int Npad, int K, int rows, int n_cu) {
     return b;
 }
 
-template <int U, int MTW>
+template <int U, int MTW, int EPI>
 static void launch_gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT,
-                            const BigShape &b, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    const size_t sm = (size_t)2 * 2 * MTW * 2 * 64 * 16 + 4 * 256;   // two tile buffers + the sink of the touches
+                            const BigShape &b, const GemmEpi &e, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    // two tile buffers + the sink of the touches + the rows' scales
+    const size_t sm = (size_t)2 * 2 * MTW * 2 * 64 * 16 + 4 * 256 + MTW * 16 * 4;
     static bool done = false;
     if (!done) {
-        (void)hipFuncSetAttribute((const void *)k_gemm_big<U, MTW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+        (void)hipFuncSetAttribute((const void *)k_gemm_big<U, MTW, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)sm);
         done = true;
     }
     const dim3 grid(((Npad / 16 + 4 * U - 1) / (4 * U)) * b.n_pm * b.S);
     if (ev_start || ev_stop)
-        hipExtLaunchKernelGGL((k_gemm_big<U, MTW>), grid, dim3(256), sm, st, ev_start, ev_stop, 0, (const u32x4 *)Wp,
-                              (const u32x4 *)Xf, P, Npad, K, b.S, MTT, b.n_mt, b.n_pm);
+        hipExtLaunchKernelGGL((k_gemm_big<U, MTW, EPI>), grid, dim3(256), sm, st, ev_start, ev_stop, 0,
+                              (const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, b.S, MTT, b.n_mt, b.n_pm, e);
     else
-        k_gemm_big<U, MTW><<<grid, 256, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, b.S, MTT, b.n_mt,
-                                                  b.n_pm);
+        k_gemm_big<U, MTW, EPI><<<grid, 256, sm, st>>>((const u32x4 *)Wp, (const u32x4 *)Xf, P, Npad, K, b.S, MTT,
+                                                       b.n_mt, b.n_pm, e);
+}
+
+template <int EPI>
+static void dispatch_gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT,
+                              const BigShape &b, const GemmEpi &e, hipEvent_t ev_start, hipEvent_t ev_stop) {
+#define KOALA_BIG(UV)                                                                                              \
+    {                                                                                                              \
+        if (b.mtw <= 8) launch_gemm_big<UV, 8, EPI>(st, Wp, Xf, P, Npad, K, MTT, b, e, ev_start, ev_stop);         \
+        else if (b.mtw <= 10) launch_gemm_big<UV, 10, EPI>(st, Wp, Xf, P, Npad, K, MTT, b, e, ev_start, ev_stop);  \
+        else launch_gemm_big<UV, 15, EPI>(st, Wp, Xf, P, Npad, K, MTT, b, e, ev_start, ev_stop);                   \
+    }
+    if (b.U == 3) KOALA_BIG(3) else if (b.U == 4) KOALA_BIG(4)
+    else if (b.mtw <= 8) launch_gemm_big<5, 8, EPI>(st, Wp, Xf, P, Npad, K, MTT, b, e, ev_start, ev_stop);
+    else launch_gemm_big<5, 10, EPI>(st, Wp, Xf, P, Npad, K, MTT, b, e, ev_start, ev_stop);
+#undef KOALA_BIG
 }
 
 void gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, const BigShape &b,
               hipEvent_t ev_start, hipEvent_t ev_stop) {
-#define KOALA_BIG(UV)                                                                                         \
-    {                                                                                                         \
-        if (b.mtw <= 8) launch_gemm_big<UV, 8>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);            \
-        else if (b.mtw <= 10) launch_gemm_big<UV, 10>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);     \
-        else launch_gemm_big<UV, 15>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);                      \
-    }
-    if (b.U == 3) KOALA_BIG(3) else if (b.U == 4) KOALA_BIG(4)
-    else if (b.mtw <= 8) launch_gemm_big<5, 8>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);
-    else launch_gemm_big<5, 10>(st, Wp, Xf, P, Npad, K, MTT, b, ev_start, ev_stop);
-#undef KOALA_BIG
+    dispatch_gemm_big<EPI_PARTIAL>(st, Wp, Xf, P, Npad, K, MTT, b, GemmEpi{}, ev_start, ev_stop);
+}
+
+// gate/up projection of many rows with SwiGLU applied to the accumulators: `b` must have one K split
+void gemm_big_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const BigShape &b,
+                     const NormScale &ns, int rows, void *Xo, int F, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    GemmEpi e{};
+    e.sums = ns.sums; e.nparts = ns.nparts; e.srows = ns.srows; e.Kn = ns.K; e.eps = ns.eps;
+    e.rows = rows; e.Xo = (uint32_t *)Xo; e.F = F;
+    dispatch_gemm_big<EPI_SWIGLU>(st, Wp, Xf, nullptr, pad64(2 * F), K, MTT, b, e, ev_start, ev_stop);
 }
 
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,
@@ -1250,6 +1310,23 @@ __device__ __forceinline__ float ld1_sc1(rsrc_t r, size_t off) {
     return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, AUX_SC1));
 }
 
+// Maximum / sum over the four 16-lane groups of a wave (lanes l, l^16, l^32, l^48), result in every lane.  The
+// swap instructions exchange 16-lane (32-lane) blocks between two registers: with the same value in both, one
+// result holds every lane's own block pair partner, so each level is one swap and one operation, all in the
+// vector unit (a shuffle through LDS costs a round trip there).
+__device__ __forceinline__ float lane_groups_max(float x) {
+    const auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float lane_groups_sum(float x) {
+    const auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(q[0]) + __uint_as_float(q[1]);
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 struct AttnArgs {
     const u32x4 *qf;      // [batch][n_heads][MTQ][KS][hi, lo][64] query fragments
     RowMeta meta;
@@ -1259,7 +1336,7 @@ struct AttnArgs {
     int *counters;        // [batch][n_heads][row groups], zero between launches
     u32x4 *Xf;            // merged output: hi/lo fragments, K = n_heads * DH, MT_out activation tiles
     int MT_out;
-    int rows_per_seq, MTQ, n_heads, cap, nsplit;
+    int rows_per_seq, MTQ, n_heads, cap, nsplit, batch, ngroups;
 };
 
 template <int DH, int MT, int NWV>
@@ -1276,15 +1353,38 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     u32x4 *qf = (u32x4 *)smem;                                   // [MT][KS][2][64]
     unsigned char *vt_all = smem + (size_t)MT * KS * 2 * 64 * 16;  // [NWV waves][32][VS]
     const int nsplit = a.nsplit, rows_per_seq = a.rows_per_seq, n_heads = a.n_heads, cap = a.cap;
-    // blockIdx.x = key split + nsplit * (group of MT row tiles): sequences of more than MT*16 rows are
-    // covered by several workgroups per (split, head), each with its own MT tiles of rows
-    const int s = blockIdx.x % nsplit, grp = blockIdx.x / nsplit, mt0 = grp * MT, h = blockIdx.y, b = blockIdx.z;
+    // One workgroup per (key split, head, sequence) and group of MT row tiles (sequences of more than MT*16 rows
+    // take several groups, each with its own row tiles over the same keys).  Workgroups go to the chip's eight
+    // dies in turn by their index, each die with an L2 of its own: the groups of one (split, head, sequence) get
+    // indices 8 apart, so they run on the same die at about the same time and the keys and values they share are
+    // fetched from memory once.  Indices past the last item (the grid is padded to whole rounds) do nothing.
+    const int ngroups = a.ngroups, items = nsplit * n_heads * a.batch;
+    const int die = blockIdx.x & 7, round = blockIdx.x >> 3;
+    const int item = (round / ngroups) * 8 + die, grp = round % ngroups;
+    if (item >= items) return;
+    const int s = item % nsplit, h = (item / nsplit) % n_heads, mt0 = grp * MT;
     const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, li = l & 15, lg = l >> 4;
     unsigned char *vt = vt_all + (size_t)wave * 32 * VS;
+    // Sequences are taken longest first: a workgroup's run time grows with its sequence's length, and the ones
+    // that run longest must not be the ones that start last.  Every wave ranks the batch's lengths itself (lane j
+    // holds sequence j's; equal lengths rank by index), and the item's sequence slot picks the one of that rank.
+    int b = item / (nsplit * n_heads), kv_end;
+    if (a.batch > 1 && a.batch <= 64) {
+        const int len = l < a.batch ? a.meta.kv_end[l] : -1;
+        int rank = 0;
+        for (int j = 0; j < a.batch; ++j) {
+            const int lj = __builtin_amdgcn_readlane(len, j);
+            rank += (lj > len || (lj == len && j < l)) ? 1 : 0;
+        }
+        const uint64_t hit = __builtin_amdgcn_ballot_w64(l < a.batch && rank == b);
+        if (hit) b = (int)__builtin_ctzll(hit);
+        kv_end = __builtin_amdgcn_readlane(len, b);
+    } else {
+        kv_end = a.meta.kv_end[b];
+    }
 
     // everything that does not depend on the key range is requested first: the query fragments and the rows'
-    // visibility data travel while the sequence's length is fetched
-    const int kv_end = a.meta.kv_end[b];
+    // visibility data
     u32x4 qreg[(MT * KS * 2 * 64 + NTH - 1) / NTH];
 #pragma unroll
     for (int i = 0; i < (MT * KS * 2 * 64 + NTH - 1) / NTH; ++i) {
@@ -1310,9 +1410,8 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     for (int o = 1; o < 16; o <<= 1) nvis_min = min(nvis_min, __shfl_xor(nvis_min, o));
     nvis_min = __builtin_amdgcn_readfirstlane(nvis_min);
     // The 32-key steps of the sequence are dealt out round-robin, first over the key splits and then over the
-    // waves: workgroup s, wave w takes steps s + nsplit * (w + NWV * k).  Which keys a wave starts with therefore
-    // does not depend on the sequence's length, and its first K fragments (A operand) / V tile rows are
-    // requested before that length has arrived (a step past the end is loaded from clamped rows and unused).
+    // waves: workgroup s, wave w takes steps s + splits * (w + NWV * k) (a step past the end is loaded from clamped
+    // rows and unused).
     const int j1 = kv_end;
     const int nsteps = (kv_end + 31) / 32;
     const int tstride = nsplit * NWV;
@@ -1372,27 +1471,51 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
                 }
             }
         // ---- V tile -> LDS (row-major, padded), written as 8-byte halves
+        // a step whose 32 keys every row of the workgroup sees (all but the last few of a sequence) needs no masks,
+        // no zeroing of rows past the end and no care for rows that have seen nothing yet
+        const bool full = k0 + 32 <= nvis_min && k0 + 32 <= j1;
+        if (full) {
 #pragma unroll
-        for (int i = 0; i < VI; ++i) {
-            const int kl = i * (64 / LPR) + l / LPR;
-            u64_alias *dst = (u64_alias *)(vt + (size_t)kl * VS + (l % LPR) * 16);
-            const bool in = k0 + kl < j1;   // rows past the end contribute exact zeros (0 * garbage could be NaN)
-            dst[0] = in ? u64_alias{vr[i].x, vr[i].y} : u64_alias{0u, 0u};
-            dst[1] = in ? u64_alias{vr[i].z, vr[i].w} : u64_alias{0u, 0u};
+            for (int i = 0; i < VI; ++i) {
+                const int kl = i * (64 / LPR) + l / LPR;
+                u64_alias *dst = (u64_alias *)(vt + (size_t)kl * VS + (l % LPR) * 16);
+                dst[0] = u64_alias{vr[i].x, vr[i].y};
+                dst[1] = u64_alias{vr[i].z, vr[i].w};
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < VI; ++i) {
+                const int kl = i * (64 / LPR) + l / LPR;
+                u64_alias *dst = (u64_alias *)(vt + (size_t)kl * VS + (l % LPR) * 16);
+                const bool in = k0 + kl < j1;   // rows past the end contribute exact zeros (0 * garbage could be NaN)
+                dst[0] = in ? u64_alias{vr[i].x, vr[i].y} : u64_alias{0u, 0u};
+                dst[1] = in ? u64_alias{vr[i].z, vr[i].w} : u64_alias{0u, 0u};
+            }
         }
         if (st + tstride < nsteps) load_step(st + tstride);   // kf / vr are free again: next step's loads overlap the rest
         // ---- mask, online softmax; probabilities stay in place as the B operand (hi, lo)
         bf16x8 ph[MT], pl[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            float p[8];
-            float tmax = -INFINITY;
-            if (k0 + 32 <= nvis_min) {   // same for the whole workgroup
+            float p[8], v[8];
+            float tmax = -INFINITY, psum = 0.f, alpha;
+            if (full) {   // same for the whole workgroup
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     p[e] = sc[e >> 2][mt][e & 3];
                     tmax = fmaxf(tmax, p[e]);
                 }
+                tmax = lane_groups_max(tmax);
+                // scores are in units of log 2 (the queries carry the factor log2(e)): weights are 2^(score - max);
+                // the new maximum is finite here, so a row that had seen nothing gets alpha = 2^(-inf) = 0
+                const float m_new = fmaxf(m_run[mt], tmax);
+                alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_new);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    v[e] = __builtin_amdgcn_exp2f(p[e] - m_new);
+                    psum += v[e];
+                }
+                m_run[mt] = m_new;
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
@@ -1404,20 +1527,17 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
                     p[e] = vis ? sc[e >> 2][mt][e & 3] : -INFINITY;
                     tmax = fmaxf(tmax, p[e]);
                 }
-            }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            // scores are in units of log 2 (the queries carry the factor log2(e)): weights are 2^(score - max)
-            const float m_new = fmaxf(m_run[mt], tmax);
-            const float alpha = (m_run[mt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[mt] - m_new);
-            float psum = 0.f, v[8];
+                tmax = lane_groups_max(tmax);
+                const float m_new = fmaxf(m_run[mt], tmax);
+                alpha = (m_run[mt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[mt] - m_new);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                v[e] = (p[e] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(p[e] - m_new);
-                psum += v[e];
+                for (int e = 0; e < 8; ++e) {
+                    v[e] = (p[e] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(p[e] - m_new);
+                    psum += v[e];
+                }
+                m_run[mt] = m_new;
             }
             l_run[mt] = l_run[mt] * alpha + psum;
-            m_run[mt] = m_new;
             if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {   // once the maxima have settled nothing is rescaled
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
@@ -1451,8 +1571,7 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     // ---- row sums across the four lane groups
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        l_run[mt] += __shfl_xor(l_run[mt], 16);
-        l_run[mt] += __shfl_xor(l_run[mt], 32);
+        l_run[mt] = lane_groups_sum(l_run[mt]);
     }
     // ---- merge the waves through LDS (the Q / V regions are free now), halving the number of live states per
     //      round: waves [n/2, n) hand theirs to waves [0, n/2)
@@ -1517,7 +1636,7 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_s_waitcnt(0);
         if (l == 0) {
-            int *cnt = a.counters + ((size_t)b * n_heads + h) * gridDim.x / nsplit + grp;
+            int *cnt = a.counters + ((size_t)b * n_heads + h) * ngroups + grp;
             const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             s_last = old == nsplit - 1;
             if (old == nsplit - 1) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1578,8 +1697,11 @@ void launch_attn(hipStream_t st, const AttnArgs &a, int batch) {
                                   (int)sm);
         done = true;
     }
-    const int groups = (a.rows_per_seq + MT * 16 - 1) / (MT * 16);   // row-tile groups per (split, head)
-    k_attn_tree<DH, MT, NWV><<<dim3(a.nsplit * groups, a.n_heads, batch), 64 * NWV, sm, st>>>(a);
+    AttnArgs b = a;
+    b.batch = batch;
+    b.ngroups = (a.rows_per_seq + MT * 16 - 1) / (MT * 16);   // row-tile groups per (split, head, sequence)
+    const int items = a.nsplit * a.n_heads * batch;
+    k_attn_tree<DH, MT, NWV><<<dim3((items + 7) / 8 * 8 * b.ngroups), 64 * NWV, sm, st>>>(b);
 }
 
 }  // namespace

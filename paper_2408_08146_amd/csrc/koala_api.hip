@@ -194,20 +194,24 @@ bool big_gemm_enabled() {
     return on;
 }
 
-// Split-K GEMM on the fragments in c->xf: partial sums of X * W^T into c->part; returns the split count.
-int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT, int rows = 0) {
+// the many-row GEMM addresses both operands with 32-bit byte offsets
+bool big_fits32(int Npad, int K, int MT) {
+    return (double)Npad * K * 2.0 < 4.0e9 && (double)(K / 32) * MT * 2048.0 < 4.0e9;
+}
+
+// Split-K GEMM on the fragments in Xf (default: c->xf): partial sums of X * W^T into c->part; returns the split count.
+int bf_gemm(koala_ctx *c, hipStream_t st, const void *Wp, int N, int K, int MT, int rows = 0, const void *Xf = nullptr) {
     const int Npad = kb::pad64(N);
+    if (!Xf) Xf = c->xf;
     const LaunchEvents ev = timed_launch(c, (double)Npad * K * 2.0);
-    // many rows: one pass over the weights with large register tiles (the kernel addresses both operands with
-    // 32-bit byte offsets)
-    const bool fits32 = (double)Npad * K * 2.0 < 4.0e9 && (double)(K / 32) * MT * 2048.0 < 4.0e9;
-    if (MT >= 8 && fits32 && big_gemm_enabled()) {
+    // many rows: one pass over the weights with large register tiles
+    if (MT >= 8 && big_fits32(Npad, K, MT) && big_gemm_enabled()) {
         const kb::BigShape b = kb::big_shape(Npad, K, rows > 0 ? rows : MT * 16, c->n_cu);
-        kb::gemm_big(st, Wp, c->xf, c->part, Npad, K, MT, b, ev.start, ev.stop);
+        kb::gemm_big(st, Wp, Xf, c->part, Npad, K, MT, b, ev.start, ev.stop);
         return b.S;
     }
     const int S = kb::gemm_splits(Npad, K, MT);
-    kb::gemm_packed(st, Wp, c->xf, c->part, Npad, K, MT, S, ev.start, ev.stop);
+    kb::gemm_packed(st, Wp, Xf, c->part, Npad, K, MT, S, ev.start, ev.stop);
     return S;
 }
 
@@ -275,9 +279,18 @@ void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_se
         kb::gemm_rows_swiglu(st, lw[4], c->xf, H, MT, hidden_scale(c), rows, c->xf2, F, c->n_cu, ev.start, ev.stop);
         S = bf_gemm_rows(c, st, lw[5], c->xf2, H, F, MT);
     } else {
-        S = bf_gemm(c, st, lw[4], 2 * F, H, MT, rows);
-        kb::silu_frag(st, c->part, S, Mp, 2 * F, hidden_scale(c), c->xf, MT, rows, F);
-        S = bf_gemm(c, st, lw[5], H, F, MT, rows);
+        const int Np = kb::pad64(2 * F);
+        if (MT >= 8 && big_fits32(Np, H, MT) && big_gemm_enabled()) {
+            // many rows: SwiGLU on the accumulators of the gate/up projection, straight into the down projection's input
+            const LaunchEvents ev = timed_launch(c, (double)Np * H * 2.0);
+            const kb::BigShape b = kb::big_shape(Np, H, rows, c->n_cu, true);
+            kb::gemm_big_swiglu(st, lw[4], c->xf, H, MT, b, hidden_scale(c), rows, c->xf2, F, ev.start, ev.stop);
+            S = bf_gemm(c, st, lw[5], H, F, MT, rows, c->xf2);
+        } else {
+            S = bf_gemm(c, st, lw[4], 2 * F, H, MT, rows);
+            kb::silu_frag(st, c->part, S, Mp, 2 * F, hidden_scale(c), c->xf, MT, rows, F);
+            S = bf_gemm(c, st, lw[5], H, F, MT, rows);
+        }
     }
     c->pend_S = S;
     c->pend_ld = H;

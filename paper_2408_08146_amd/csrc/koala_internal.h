@@ -209,9 +209,12 @@ void gemm_rows_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int
                       void *Xo, int F, int n_cu, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 // GEMM for many activation rows (MTT >= 8 tiles): P[S][MTT*16][Npad] partial sums; big_shape picks the launch
 struct BigShape { int n_mt, n_pm, mtw, U, S; };
-BigShape big_shape(int Npad, int K, int rows, int n_cu);
+BigShape big_shape(int Npad, int K, int rows, int n_cu, bool one_split = false);
 void gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, const BigShape &b,
               hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+void gemm_big_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const BigShape &b,
+                     const NormScale &ns, int rows, void *Xo, int F, hipEvent_t ev_start = nullptr,
+                     hipEvent_t ev_stop = nullptr);
 // v = (mode 1: x +) sum of partials (mode 0: x as is); x <- v for modes 1, 2; Xf (may be NULL) receives the
 // fragments of gain * v (gain NULL: v); sums (may be NULL) the sums of squares of v per 512-column chunk
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,
