@@ -423,6 +423,15 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
 __device__ __forceinline__ void mfma_acc(f32x4 &acc, bf16x8 a, bf16x8 b) {
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
+// Results of the matrix pipe may be read by other instructions only some cycles after the MFMA was issued; for
+// the compiler's own MFMAs the compiler sees to that, for mfma_acc it cannot.  These statements wait (WAIT) and
+// hand the accumulator tiles through, so that whatever reads them afterwards, wherever the compiler places it,
+// depends on a statement that comes after the wait.
+template <bool WAIT>
+__device__ __forceinline__ void mfma_settle(f32x4 &a, f32x4 &b, f32x4 &c, f32x4 &d) {
+    if (WAIT) asm volatile("s_nop 15\n\ts_nop 7" : "+a"(a), "+a"(b), "+a"(c), "+a"(d));
+    else asm volatile("" : "+a"(a), "+a"(b), "+a"(c), "+a"(d));
+}
 
 // 16 bytes per lane from LDS at base + a constant byte offset (below 64 KiB), as an instruction of its own: the
 // result may be used only after a wait that covers it (wait_lds_reads).
@@ -613,8 +622,17 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
     if (t < kt1) tile(t, std::integral_constant<int, 0>{});
     if (t + 1 < kt1) tile(t + 1, std::integral_constant<int, 1>{});
     if (t + 2 < kt1) tile(t + 2, std::integral_constant<int, 2>{});
-    // results of the matrix pipe may be read by other instructions only some cycles after the last MFMA was issued
-    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    {
+        f32x4 *t = &acc[0][0];
+        constexpr int NT = U * MTW;
+        static_assert(NT >= 4, "at least four accumulator tiles");
+#pragma unroll
+        for (int i = 0; i + 4 <= NT; i += 4) {
+            if (i == 0) mfma_settle<true>(t[i], t[i + 1], t[i + 2], t[i + 3]);
+            else mfma_settle<false>(t[i], t[i + 1], t[i + 2], t[i + 3]);
+        }
+        if (NT % 4) mfma_settle<false>(t[NT - 4], t[NT - 3], t[NT - 2], t[NT - 1]);   // the last tiles (again)
+    }
     __syncthreads();
     if (EPI == EPI_PARTIAL) {
 #pragma unroll
@@ -1363,7 +1381,8 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     const int item = (round / ngroups) * 8 + die, grp = round % ngroups;
     if (item >= items) return;
     const int s = item % nsplit, h = (item / nsplit) % n_heads, mt0 = grp * MT;
-    const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, li = l & 15, lg = l >> 4;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // a scalar: so is all that follows from it
+    const int l = tid & 63, li = l & 15, lg = l >> 4;
     unsigned char *vt = vt_all + (size_t)wave * 32 * VS;
     // Sequences are taken longest first: a workgroup's run time grows with its sequence's length, and the ones
     // that run longest must not be the ones that start last.  Every wave ranks the batch's lengths itself (lane j

@@ -91,7 +91,9 @@ class Case:
         w = K.pack_target_weights(self.Wt, cfg, self.device)
         w.update((K.pack_eagle_weights if self.eagle else K.pack_medusa_weights)(self.Wd, cfg, self.device))
         self.kv = K.alloc_kv(cfg, self.B, self.cap, self.device, cfg["K"] if self.eagle else 0)
-        self.ws = torch.empty(self.gpu.workspace_bytes(), dtype=torch.uint8, device=self.device)
+        # every byte 0x7f (3.4e38 as fp32 or bf16): a kernel that reads workspace memory nobody has written gets a
+        # value that wrecks the comparison instead of a zero that happens to be harmless
+        self.ws = torch.full((self.gpu.workspace_bytes(),), 0x7f, dtype=torch.uint8, device=self.device)
         self.gpu.bind(w, self.kv, self.ws)
         self.torch = torch
 
