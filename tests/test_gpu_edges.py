@@ -119,3 +119,24 @@ def test_results_are_run_to_run_identical():
         outs.append(case.gpu_verify(tt))
     np.testing.assert_array_equal(outs[0][1], outs[1][1])
     np.testing.assert_array_equal(outs[0][0], outs[1][0])
+
+
+@pytest.mark.parametrize("name,batch", [("cfg4_small", 1), ("cfg5_small", 5)])
+def test_results_do_not_depend_on_what_the_workspace_held(name, batch):
+    """Partial results cross workgroups inside kernels (key splits of the attention, split-K sums): a consumer that
+    read one before its producer had written it would pick up whatever the workspace held.  Twelve verifications,
+    the workspace refilled with 0x7f bytes (3.4e38) and bound again before each: every run must reproduce the first
+    bit for bit."""
+    case = Case(name, batch=batch, n_layers=2)
+    case.fill_kv_normal()
+    tt = case.random_tree_tokens()
+    case.upload_kv()
+    first = case.gpu_verify(tt)
+    assert np.isfinite(first[1]).all()
+    for _ in range(12):
+        case.ws.fill_(0x7f)
+        case.gpu.bind(*case.gpu._keep)
+        case.upload_kv()
+        again = case.gpu_verify(tt)
+        np.testing.assert_array_equal(first[1], again[1])
+        np.testing.assert_array_equal(first[0], again[0])
