@@ -505,7 +505,14 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
     // EPI_SWIGLU: RMSNorm's scale of each of the workgroup's rows (from the per-chunk sums of squares of the input
     // rows), one row per thread, fetched now and parked in LDS behind the sinks until the epilogue
     float *rsc_s = (float *)(bsm + (size_t)2 * XT * 16 + 4 * 256);   // [MTW * 16]
-    if (EPI == EPI_SWIGLU && threadIdx.x < MTW * 16) {
+    int *rslot_s = (int *)(rsc_s + MTW * 16), *rbat_s = rslot_s + MTW * 16;   // EPI_QKV: cache slot and sequence of a row
+    if (EPI == EPI_QKV && threadIdx.x < MTW * 16) {
+        const int row = mt0 * 16 + threadIdx.x;
+        const bool ok = row < e.rows;
+        rslot_s[threadIdx.x] = ok ? e.meta.row_slot[row] : 0;
+        rbat_s[threadIdx.x] = ok ? e.meta.row_b[row] : 0;
+    }
+    if (EPI != EPI_PARTIAL && threadIdx.x < MTW * 16) {
         const int row = mt0 * 16 + threadIdx.x;
         float tot = 0.f;
         if (e.sums && row < e.rows) {
@@ -643,6 +650,53 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
                 if (m < mt_cnt) {
                     const int row = (mt0 + m) * 16 + li, n = (ug0 + j) * 16 + 4 * lg;
                     *(f32x4 *)(P + ((size_t)sp * (MTT * 16) + row) * Npad + n) = acc[j][m];
+                }
+            }
+        }
+    } else if (EPI == EPI_QKV) {
+        // One K split.  RMSNorm's row scale, then per lane four columns of one activation row: of V as they are;
+        // of Q and K two rotary pairs (the weight rows interleave dimension i and i + head_dim/2), rotated with
+        // the row's cos/sin; K and V rows go to the bf16 cache at the row's slot, Q as hi/lo fragments of the
+        // attention kernel, times log2(e)/sqrt(head_dim).
+        const int half = e.DH / 2;
+#pragma unroll
+        for (int m = 0; m < MTW; ++m) {
+            const int row = (mt0 + m) * 16 + li;
+            if (m >= mt_cnt || row >= e.rows) continue;
+            const float rsc = rsc_s[m * 16 + li];
+            const int slot = rslot_s[m * 16 + li], bat = rbat_s[m * 16 + li];
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                const int n = (ug0 + j) * 16 + 4 * lg;
+                if (ug0 + j >= nunits || n >= 3 * e.H) continue;
+                const f32x4 v = acc[j][m] * rsc;
+                const int which = n / e.H, nn = n % e.H, h = nn / e.DH, r = nn % e.DH;
+                const size_t o = (((size_t)bat * e.n_heads + h) * e.cap + slot) * e.DH;
+                if (which == 2) {
+                    const uint32_t lo = f2bf(v[0]) | (f2bf(v[1]) << 16), hi = f2bf(v[2]) | (f2bf(v[3]) << 16);
+                    *(u64_pair *)(e.vc + o + r) = u64_pair{lo, hi};
+                    continue;
+                }
+                const int dd = r >> 1;   // even: the lane holds pairs dd and dd + 1
+                const float c0 = e.meta.rope_cos[(size_t)row * half + dd], s0 = e.meta.rope_sin[(size_t)row * half + dd];
+                const float c1 = e.meta.rope_cos[(size_t)row * half + dd + 1], s1 = e.meta.rope_sin[(size_t)row * half + dd + 1];
+                const float a0 = v[0] * c0 - v[1] * s0, b0 = v[1] * c0 + v[0] * s0;
+                const float a1 = v[2] * c1 - v[3] * s1, b1 = v[3] * c1 + v[2] * s1;
+                if (which == 1) {
+                    *(uint32_t *)(e.kc + o + dd) = f2bf(a0) | (f2bf(a1) << 16);
+                    *(uint32_t *)(e.kc + o + half + dd) = f2bf(b0) | (f2bf(b1) << 16);
+                } else {
+                    const int i = row - bat * e.rows_per_seq;   // row of its sequence
+                    uint32_t *qt = e.qf + ((((size_t)bat * e.n_heads + h) * e.MTQ + (i >> 4)) * (e.DH / 32)) * 2 * 64 * 4;
+                    const float y[4] = {a0 * e.qscale, a1 * e.qscale, b0 * e.qscale, b1 * e.qscale};
+#pragma unroll
+                    for (int z = 0; z < 2; ++z) {
+                        const int d = dd + z * half;
+                        const HiLo pr = split_pair(y[2 * z], y[2 * z + 1]);
+                        uint32_t *dst = qt + (((size_t)(d >> 5) * 2) * 64 + (i & 15) + 16 * ((d & 31) >> 3)) * 4 + ((d & 7) >> 1);
+                        dst[0] = pr.hi;
+                        dst[64 * 4] = pr.lo;
+                    }
                 }
             }
         }
@@ -1192,8 +1246,8 @@ BigShape big_shape(int Npad, int K, int rows, int n_cu, bool one_split) {
 template <int U, int MTW, int EPI>
 static void launch_gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT,
                             const BigShape &b, const GemmEpi &e, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    // two tile buffers + the sink of the touches + the rows' scales
-    const size_t sm = (size_t)2 * 2 * MTW * 2 * 64 * 16 + 4 * 256 + MTW * 16 * 4;
+    // two tile buffers + the sink of the touches + the rows' scales, cache slots and sequences
+    const size_t sm = (size_t)2 * 2 * MTW * 2 * 64 * 16 + 4 * 256 + 3 * MTW * 16 * 4;
     static bool done = false;
     if (!done) {
         (void)hipFuncSetAttribute((const void *)k_gemm_big<U, MTW, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1227,6 +1281,20 @@ static void dispatch_gemm_big(hipStream_t st, const void *Wp, const void *Xf, fl
 void gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, const BigShape &b,
               hipEvent_t ev_start, hipEvent_t ev_stop) {
     dispatch_gemm_big<EPI_PARTIAL>(st, Wp, Xf, P, Npad, K, MTT, b, GemmEpi{}, ev_start, ev_stop);
+}
+
+// QKV projection of many rows with rotary embedding, KV append and query fragments applied to the accumulators:
+// `b` must have one K split
+void gemm_big_qkv(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const BigShape &b, const NormScale &ns,
+                  int rows, int rows_per_seq, const RowMeta &meta, void *qf, void *kc, void *vc, int H, int n_heads,
+                  int head_dim, int cap, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    GemmEpi e{};
+    e.sums = ns.sums; e.nparts = ns.nparts; e.srows = ns.srows; e.Kn = ns.K; e.eps = ns.eps;
+    e.rows = rows; e.meta = meta; e.qf = (uint32_t *)qf; e.kc = (bf16_t *)kc; e.vc = (bf16_t *)vc;
+    e.H = H; e.n_heads = n_heads; e.DH = head_dim; e.cap = cap;
+    e.rows_per_seq = rows_per_seq; e.MTQ = (rows_per_seq + 15) / 16;
+    e.qscale = 1.4426950408889634f / sqrtf((float)head_dim);
+    dispatch_gemm_big<EPI_QKV>(st, Wp, Xf, nullptr, pad64(3 * H), K, MTT, b, e, ev_start, ev_stop);
 }
 
 // gate/up projection of many rows with SwiGLU applied to the accumulators: `b` must have one K split

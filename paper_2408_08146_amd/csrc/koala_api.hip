@@ -266,9 +266,18 @@ void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_se
         kb::gemm_rows_qkv(st, lw[1], c->xf, H, MT, hidden_scale(c), rows, rows_per_seq, c->meta, c->qf, kc, vc, H,
                           s.n_heads, s.head_dim, c->kv.capacity, c->n_cu, ev.start, ev.stop);
     } else {
-        S = bf_gemm(c, st, lw[1], 3 * H, H, MT, rows);
-        kb::rope_append(st, c->part, S, Mp, 3 * H, hidden_scale(c), c->meta, c->qf, kc, vc, rows, H, s.n_heads,
-                        s.head_dim, c->kv.capacity, rows_per_seq);
+        const int Np = kb::pad64(3 * H);
+        if (MT >= 8 && big_fits32(Np, H, MT) && big_gemm_enabled()) {
+            // many rows: rotary embedding, KV append and query fragments on the accumulators of the projection
+            const LaunchEvents ev = timed_launch(c, (double)Np * H * 2.0);
+            const kb::BigShape b = kb::big_shape(Np, H, rows, c->n_cu, true);
+            kb::gemm_big_qkv(st, lw[1], c->xf, H, MT, b, hidden_scale(c), rows, rows_per_seq, c->meta, c->qf, kc, vc, H,
+                             s.n_heads, s.head_dim, c->kv.capacity, ev.start, ev.stop);
+        } else {
+            S = bf_gemm(c, st, lw[1], 3 * H, H, MT, rows);
+            kb::rope_append(st, c->part, S, Mp, 3 * H, hidden_scale(c), c->meta, c->qf, kc, vc, rows, H, s.n_heads,
+                            s.head_dim, c->kv.capacity, rows_per_seq);
+        }
     }
     kb::attention_tree(st, c->qf, c->meta, kc, vc, c->o_part, c->opart_bytes, c->ml, c->ml_bytes, c->attn_cnt, c->xf,
                        MT, batch, rows_per_seq, s.n_heads, s.head_dim, c->kv.capacity, ns);

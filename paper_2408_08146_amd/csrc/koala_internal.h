@@ -212,6 +212,9 @@ struct BigShape { int n_mt, n_pm, mtw, U, S; };
 BigShape big_shape(int Npad, int K, int rows, int n_cu, bool one_split = false);
 void gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, const BigShape &b,
               hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+void gemm_big_qkv(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const BigShape &b, const NormScale &ns,
+                  int rows, int rows_per_seq, const RowMeta &meta, void *qf, void *kc, void *vc, int H, int n_heads,
+                  int head_dim, int cap, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 void gemm_big_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const BigShape &b,
                      const NormScale &ns, int rows, void *Xo, int F, hipEvent_t ev_start = nullptr,
                      hipEvent_t ev_stop = nullptr);
