@@ -420,6 +420,11 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
 // as an instruction of its own because the compiler's MFMA builtin, once a wave uses more than 256 registers,
 // gives every result a new register and copies it back, which costs more than the MFMA itself.  An MFMA may
 // follow another that wrote its accumulator operand without waiting when both name the same registers, as here.
+// The compiler does not know that this is a matrix instruction and keeps none of the distances the hardware wants
+// around one: `a` and `b` must not come straight out of a vector-unit instruction (loads are fine: the wait for
+// their data is distance enough; a value computed in the vector unit needs a few idle cycles before the matrix
+// instruction reads it, or the instruction now and then sees the register's old contents), and the result may be
+// read only after mfma_settle.
 __device__ __forceinline__ void mfma_acc(f32x4 &acc, bf16x8 a, bf16x8 b) {
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
