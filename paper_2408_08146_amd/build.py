@@ -13,6 +13,9 @@ LIB = os.path.join(PKG, "libkoala.so")
 SOURCES = ["koala_api.hip", "kernels_generic.hip", "kernels_bf16.hip", "kernels_sampling.hip", "koala_train.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # leading kernel arguments arrive in scalar registers with the wave instead of being fetched by its first
+         # instructions (measured: 1.2 us less per dependent launch of a short kernel)
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wno-unused-command-line-argument"]
 
 

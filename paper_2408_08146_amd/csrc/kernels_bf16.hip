@@ -36,6 +36,12 @@ __device__ __forceinline__ HiLo split_pair(float a, float b) {
                                                                           b - __uint_as_float(r.hi & 0xFFFF0000u)}, bf16x2));
     return r;
 }
+// first of the n units that split i of S takes (units are dealt out as evenly as whole numbers allow).  In 32-bit
+// unsigned arithmetic on purpose: i * n stays far below 2^32 here, and a 64-bit division is a long instruction
+// sequence in front of a kernel's first load.
+__device__ __forceinline__ int split_begin(int i, int n, int S) {
+    return S == 1 ? i * n : (int)((unsigned)(i * n) / (unsigned)S);
+}
 // eight values -> the hi and lo 16-byte pieces of a fragment lane
 __device__ __forceinline__ void split8(const float *y, u32x4 &h, u32x4 &w) {
     const HiLo p0 = split_pair(y[0], y[1]), p1 = split_pair(y[2], y[3]), p2 = split_pair(y[4], y[5]), p3 = split_pair(y[6], y[7]);
@@ -72,7 +78,7 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
     const int wv = wave & 3, rs = wave >> 2;
     const int wb = blockIdx.x % nwb, sp = blockIdx.x / nwb;
     const int nch = K / 128;
-    const int c_begin = (int)((long long)sp * nch / S), c_end = (int)((long long)(sp + 1) * nch / S);
+    const int c_begin = split_begin(sp, nch, S), c_end = split_begin(sp + 1, nch, S);
     const int nchunks = c_end - c_begin;
     const int rb = wb * 4 + wv;
     const bool active = rb < Npad / 64;
@@ -214,7 +220,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
     const int nunits = Npad / 16, nwg = (nunits + U - 1) / U;
     const int g = blockIdx.x % nwg, sp = blockIdx.x / nwg, ug0 = g * U;
     const int nkt = K / 64;
-    const int kt0 = (int)((long long)sp * nkt / S), kt1 = (int)((long long)(sp + 1) * nkt / S);
+    const int kt0 = split_begin(sp, nkt, S), kt1 = split_begin(sp + 1, nkt, S);
     const u32x4 *w[U];   // unit j, tile kt, half s: w[j] + kt * 512 + s * 64 (a ragged last group re-reads its last unit)
 #pragma unroll
     for (int j = 0; j < U; ++j) {
@@ -473,7 +479,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
     const int pm = bid % n_pm, sp = bid / n_pm;
     const int mt0 = pm * MTW, mt_cnt = min(MTW, n_mt - mt0);
     const int nkt = K / 64;
-    const int kt0 = (int)((long long)sp * nkt / S), kt1 = (int)((long long)(sp + 1) * nkt / S);
+    const int kt0 = split_begin(sp, nkt, S), kt1 = split_begin(sp + 1, nkt, S);
     const int ug0 = (g * 4 + wave) * U;
     // Addresses are a kernel argument plus a 32-bit byte offset (the launcher checks that both operands are
     // smaller than 4 GiB): the per-lane part of the offset is computed once, the per-tile part is one addition.
@@ -835,8 +841,8 @@ __device__ __forceinline__ float row_scale(const RowScale &rs, int row) {
 // each 512-column chunk to sums[chunk][m].  RMSNorm is linear in the row scale, so the GEMM runs
 // on gain * v and its consumer multiplies by row_scale().  grid (ceil(N/512), M), 64 threads x 8 cols.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_fold(float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode,
-                                             int N, const bf16_t *gain, u32x4 *Xf, int MT, float *sums, int srows) {
+__global__ __launch_bounds__(64) void k_fold(float *x, const float *P, const bf16_t *gain, u32x4 *Xf, int ldx, int S,
+                                             int Mp, int ldp, int mode, int N, int MT, float *sums, int srows) {
     const int c = blockIdx.x, m = blockIdx.y, j = (c * 64 + threadIdx.x) * 8;
     float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (j < N) {
@@ -1313,7 +1319,7 @@ void gemm_big_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int 
 
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,
           const void *gain, void *Xf, int MT, float *sums, int srows) {
-    k_fold<<<dim3((N + 511) / 512, M), 64, 0, st>>>(x, ldx, P, S, Mp, ldp, mode, N, (const bf16_t *)gain, (u32x4 *)Xf,
+    k_fold<<<dim3((N + 511) / 512, M), 64, 0, st>>>(x, P, (const bf16_t *)gain, (u32x4 *)Xf, ldx, S, Mp, ldp, mode, N,
                                                     MT, sums, srows);
 }
 
@@ -1430,8 +1436,12 @@ struct AttnArgs {
     int rows_per_seq, MTQ, n_heads, cap, nsplit, batch, ngroups;
 };
 
+// The arguments that the first loads depend on come first and one by one: leading scalar arguments are handed to a
+// wave in registers when it starts, the rest (`a`) it fetches itself.
 template <int DH, int MT, int NWV>
-__global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
+__global__ __launch_bounds__(64 * NWV) void k_attn_tree(const u32x4 *qf_in, const bf16_t *kc, const bf16_t *vc,
+                                                        const int *kv_end_of, int nsplit, int n_heads, int cap,
+                                                        int batch, int ngroups, int rows_per_seq, AttnArgs a) {
     constexpr int KS = DH / 32;            // contraction steps over the head dimension
     constexpr int DT = DH / 16;            // 16-wide output tiles over the head dimension
     constexpr int VS = DH * 2 + 32;        // bytes per key row of the V tile in LDS: rows 8 banks apart, so that a
@@ -1443,13 +1453,12 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     __shared__ int s_last;
     u32x4 *qf = (u32x4 *)smem;                                   // [MT][KS][2][64]
     unsigned char *vt_all = smem + (size_t)MT * KS * 2 * 64 * 16;  // [NWV waves][32][VS]
-    const int nsplit = a.nsplit, rows_per_seq = a.rows_per_seq, n_heads = a.n_heads, cap = a.cap;
     // One workgroup per (key split, head, sequence) and group of MT row tiles (sequences of more than MT*16 rows
     // take several groups, each with its own row tiles over the same keys).  Workgroups go to the chip's eight
     // dies in turn by their index, each die with an L2 of its own: the groups of one (split, head, sequence) get
     // indices 8 apart, so they run on the same die at about the same time and the keys and values they share are
     // fetched from memory once.  Indices past the last item (the grid is padded to whole rounds) do nothing.
-    const int ngroups = a.ngroups, items = nsplit * n_heads * a.batch;
+    const int items = nsplit * n_heads * batch, MTQ = (rows_per_seq + 15) / 16;
     const int die = blockIdx.x & 7, round = blockIdx.x >> 3;
     const int item = (round / ngroups) * 8 + die, grp = round % ngroups;
     if (item >= items) return;
@@ -1461,18 +1470,18 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     // that run longest must not be the ones that start last.  Every wave ranks the batch's lengths itself (lane j
     // holds sequence j's; equal lengths rank by index), and the item's sequence slot picks the one of that rank.
     int b = item / (nsplit * n_heads), kv_end;
-    if (a.batch > 1 && a.batch <= 64) {
-        const int len = l < a.batch ? a.meta.kv_end[l] : -1;
+    if (batch > 1 && batch <= 64) {
+        const int len = l < batch ? kv_end_of[l] : -1;
         int rank = 0;
-        for (int j = 0; j < a.batch; ++j) {
+        for (int j = 0; j < batch; ++j) {
             const int lj = __builtin_amdgcn_readlane(len, j);
             rank += (lj > len || (lj == len && j < l)) ? 1 : 0;
         }
-        const uint64_t hit = __builtin_amdgcn_ballot_w64(l < a.batch && rank == b);
+        const uint64_t hit = __builtin_amdgcn_ballot_w64(l < batch && rank == b);
         if (hit) b = (int)__builtin_ctzll(hit);
         kv_end = __builtin_amdgcn_readlane(len, b);
     } else {
-        kv_end = a.meta.kv_end[b];
+        kv_end = kv_end_of[b];
     }
 
     // everything that does not depend on the key range is requested first: the query fragments and the rows'
@@ -1481,8 +1490,8 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < (MT * KS * 2 * 64 + NTH - 1) / NTH; ++i) {
         const int u = tid + i * NTH, mt = u / (KS * 2 * 64);
-        qreg[i] = (u < MT * KS * 2 * 64 && mt0 + mt < a.MTQ)
-                      ? a.qf[(((size_t)b * n_heads + h) * a.MTQ + mt0) * (KS * 2 * 64) + u]
+        qreg[i] = (u < MT * KS * 2 * 64 && mt0 + mt < MTQ)
+                      ? qf_in[(((size_t)b * n_heads + h) * MTQ + mt0) * (KS * 2 * 64) + u]
                       : (u32x4){0u, 0u, 0u, 0u};
     }
     int nvis[MT], base[MT];
@@ -1507,8 +1516,8 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(AttnArgs a) {
     const int j1 = kv_end;
     const int nsteps = (kv_end + 31) / 32;
     const int tstride = nsplit * NWV;
-    const bf16_t *kb = a.kc + ((size_t)b * n_heads + h) * cap * DH;
-    const bf16_t *vb = a.vc + ((size_t)b * n_heads + h) * cap * DH;
+    const bf16_t *kb = kc + ((size_t)b * n_heads + h) * cap * DH;
+    const bf16_t *vb = vc + ((size_t)b * n_heads + h) * cap * DH;
     u32x4 kf[2][KS], vr[VI];
     auto load_step = [&](int st) {
         const int k0 = st * 32;
@@ -1793,7 +1802,8 @@ void launch_attn(hipStream_t st, const AttnArgs &a, int batch) {
     b.batch = batch;
     b.ngroups = (a.rows_per_seq + MT * 16 - 1) / (MT * 16);   // row-tile groups per (split, head, sequence)
     const int items = a.nsplit * a.n_heads * batch;
-    k_attn_tree<DH, MT, NWV><<<dim3((items + 7) / 8 * 8 * b.ngroups), 64 * NWV, sm, st>>>(b);
+    k_attn_tree<DH, MT, NWV><<<dim3((items + 7) / 8 * 8 * b.ngroups), 64 * NWV, sm, st>>>(
+        b.qf, b.kc, b.vc, b.meta.kv_end, b.nsplit, b.n_heads, b.cap, b.batch, b.ngroups, b.rows_per_seq, b);
 }
 
 }  // namespace
