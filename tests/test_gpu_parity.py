@@ -293,6 +293,32 @@ def test_bf16_long_context_softmax_with_a_dominant_late_key():
     assert rel_err_rows(feat, rfeat).max() < case.tol
 
 
+# --------------------------------------------------------------------------- bf16, heads of 64 dimensions
+@pytest.mark.parametrize("cfgname,ctx", [("cfg2_small", 200), ("cfg4_small", 1100)])
+def test_bf16_head_dim_64_matches_oracle(cfgname, ctx):
+    """The benchmark shapes all have heads of 128 dimensions; the library also takes 64 (its attention kernel,
+    the rotary pairs and the query fragments of the QKV projection are laid out per head size).  Same widths
+    with twice the heads: verification (26 and 60 rows, one and several key steps per wave) and drafting."""
+    from koala_synth import get_config
+    hidden = get_config(cfgname)["hidden"]
+    case = Case(cfgname, n_layers=2, ctx=ctx, capacity=ctx + 128, head_dim=64, n_heads=hidden // 64)
+    assert case.cfg["head_dim"] == 64 and case.cfg["n_heads"] * 64 == hidden
+    case.fill_kv_normal()
+    case.upload_kv()
+    tt = case.random_tree_tokens()
+    feat, logits, greedy = case.gpu_verify(tt)
+    rfeat, rlogits, rgreedy = case.oracle_verify(tt)
+    skipped, err = compare_logits_and_greedy(case, logits, greedy, rlogits, rgreedy)
+    assert skipped <= max(1, case.B * case.T // 10)
+    assert rel_err_rows(feat, rfeat).max() < case.tol
+    case.upload_kv()
+    feat_in, tok_in = case.normal_draft_inputs()
+    tokens, scores = case.gpu_draft(feat_in, tok_in)
+    ref = case.oracle_draft(feat_in.astype(np.float64), tok_in)
+    n_cmp, n_skip = compare_draft_tokens(case, tokens, scores, ref)
+    assert n_skip <= max(1, n_cmp // 10), f"{n_skip} of {n_cmp} drafted tokens skipped by the margin rule"
+
+
 # --------------------------------------------------------------------------- bf16, many rows
 @pytest.mark.parametrize("batch", [2, 4, 5])
 def test_bf16_batched_verify_many_rows_matches_oracle(batch):
