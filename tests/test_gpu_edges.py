@@ -35,6 +35,24 @@ def test_single_node_tree_is_plain_decoding_bf16():
         assert tok == greedy[0, 0]
 
 
+@pytest.mark.parametrize("topk,widths", [([3, 2, 1], [1, 3, 6, 6]), ([4, 2, 1], [1, 4, 6, 6]),
+                                         ([4, 2, 2, 1], [1, 4, 8, 10, 9]), ([4, 2, 2, 1], [1, 4, 8, 10, 10]),
+                                         ([4, 2, 2, 2], [1, 4, 8, 13, 14]), ([4, 2, 2, 2], [1, 4, 8, 16, 20])])
+def test_tree_sizes_around_the_row_tile_boundaries_bf16(topk, widths):
+    """Trees of 16, 17, 32, 33, 40 and 49 nodes: a full row tile, one row into the second, two full tiles, one
+    row into the second group of tiles, and groups with a part-filled and an empty tile."""
+    case = Case("cfg2_small", n_layers=2, tree=dict(topk=topk, widths=widths))
+    assert case.T == sum(widths)
+    case.fill_kv_normal()
+    case.upload_kv()
+    tt = case.random_tree_tokens()
+    feat, logits, greedy = case.gpu_verify(tt)
+    rfeat, rlogits, rgreedy = case.oracle_verify(tt)
+    skipped, err = compare_logits_and_greedy(case, logits, greedy, rlogits, rgreedy)
+    assert skipped <= max(1, case.T // 10)
+    assert rel_err_rows(feat, rfeat).max() < case.tol
+
+
 def test_largest_tree_and_most_catchup_rows_bf16():
     """64 tree nodes (Medusa template) verified, and an EAGLE catch-up of m = 64 rows."""
     case = Case("cfg3_small")
