@@ -3,7 +3,8 @@ reduced to two so that the fp64 oracle and the CPU weight generator finish in a 
   7B shape, EAGLE-style head, 26-node tree, 1024-token context (KOALA_FULL_DEPTH=1 runs all 32 layers);
   7B shape, Medusa-style heads, 64-node tree, 2048-token context;
   13B shape, 60-node tree, 4096-token context;
-  33B shape, two sequences of 60 nodes with ragged contexts of 8100 and 777 tokens.
+  33B shape, two sequences of 60 nodes with ragged contexts of 8100 and 777 tokens, and the benchmark's own
+  batch of eight sequences (480 rows, contexts of 1704 to 6999 tokens).
 Every logit of every tree row is compared with the oracle."""
 import os
 
@@ -59,7 +60,7 @@ def test_cfg2_full_width_draft_expand(case):
 
 
 # --------------------------------------------------------------------------- the other benchmarked shapes
-def _verify_full_width(case, max_skipped):
+def _verify_full_width(case, max_skipped, kv_tol=1e-2):
     case.upload_kv()
     tt = case.random_tree_tokens()
     feat, logits, greedy = case.gpu_verify(tt)
@@ -68,13 +69,14 @@ def _verify_full_width(case, max_skipped):
     print(f"{case.cfg['name']} full-width verify: max logit error {err:.2e}, rows skipped by the margin rule {skipped}")
     assert skipped <= max_skipped
     assert rel_err_rows(feat, rfeat).max() < case.tol
-    # the tree rows' keys/values of the last layer, as stored (bf16) against the oracle's exact rows
+    # the tree rows' keys/values of the last layer, as stored (bf16) against the oracle's exact rows: results of
+    # the second layer's projection, so within the bf16 bar of their largest value (kv_tol: usually half of it)
     k, v = case.download_kv()
     for b in range(case.B):
         C = case.ctx_lens[b]
         for got, ref in ((k, case.tc[b].k), (v, case.tc[b].v)):
             r = ref[-1][:, C:C + case.T]
-            assert np.abs(got[-1, b][:, C:C + case.T] - r).max() < 1e-2 * np.abs(r).max()
+            assert np.abs(got[-1, b][:, C:C + case.T] - r).max() < kv_tol * np.abs(r).max()
 
 
 def test_cfg3_full_width_verify_and_medusa_draft():
@@ -110,3 +112,14 @@ def test_cfg5_full_width_ragged_batch_verify():
     case = Case("cfg5", n_layers=2, K=1, batch=2, ctx=[8100, 777], norm_gain="ones")
     case.fill_kv_normal()
     _verify_full_width(case, 6)
+
+
+def test_cfg5_full_width_benchmark_batch_verify():
+    """The batch bench.py times at this shape: eight sequences x 60 rows = 480 rows with the seeded ragged
+    contexts (1704 ... 6999 tokens), i.e. the many-row GEMM in the tile and split shapes of the benchmark and
+    the attention kernel with its longest-first order over a ragged batch."""
+    case = Case("cfg5", n_layers=2, K=1, norm_gain="ones")
+    assert case.B == 8 and case.B * case.T == 480 and min(case.ctx_lens) < 2000 and max(case.ctx_lens) > 6500
+    case.fill_kv_normal()
+    _verify_full_width(case, 24, kv_tol=case.tol)   # 8 x 52 x 60 x 128 stored values per tensor: the largest deviation
+                                                    # seen is 1.05e-2 of the maximum, the bar is 2e-2
