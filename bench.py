@@ -47,23 +47,23 @@ def device_weights(cfg, torch, K, dev):
         return (torch.randn(n, k, generator=g, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
 
     def layer():
-        wqkv = KO.fragment_major(mat(3 * H, H))
-        wo = KO.fragment_major(mat(H, H))
+        wqkv = KO.device_matrix(mat(3 * H, H))
+        wo = KO.device_matrix(mat(H, H))
         gu = mat(2 * F, H)                                       # rows already in the library's order (gate/up
                                                                  # interleaved, rotary pairs adjacent): random anyway
-        wgu = KO.fragment_major(gu)
-        wd = KO.fragment_major(mat(H, F))
+        wgu = KO.device_matrix(gu)
+        wd = KO.device_matrix(mat(H, F))
         one = torch.ones(H, dtype=torch.bfloat16, device=dev)
         return (one, wqkv, wo, one.clone(), wgu, wd)
 
-    w = dict(embed=mat(V, H), lm_head=KO.fragment_major(mat(V, H)),
+    w = dict(embed=mat(V, H), lm_head=KO.device_matrix(mat(V, H)),
              final_norm=torch.ones(H, dtype=torch.bfloat16, device=dev),
              layers=[layer() for _ in range(cfg["n_layers"])])
     if cfg["draft"] == "medusa":
         w["fc"] = None
-        w["draft"] = [KO.fragment_major(mat(H, H)) for _ in range(cfg["medusa_heads"] * K)]
+        w["draft"] = [KO.device_matrix(mat(H, H)) for _ in range(cfg["medusa_heads"] * K)]
     else:
-        w["fc"] = KO.fragment_major(mat(H, 2 * H))
+        w["fc"] = KO.device_matrix(mat(H, 2 * H))
         w["draft"] = [t for _ in range(K) for t in layer()]
     return w
 
@@ -82,18 +82,18 @@ def predictable_device_weights(cfg, torch, K, dev, sigma, gain=4.0):
 
     def layer():
         one = torch.ones(H, dtype=bf, device=dev)
-        return (one, KO.fragment_major(mat(3 * H, H)), KO.fragment_major(torch.zeros(H, H, dtype=bf, device=dev)),
-                one.clone(), KO.fragment_major(mat(2 * F, H)), KO.fragment_major(torch.zeros(H, F, dtype=bf, device=dev)))
+        return (one, KO.device_matrix(mat(3 * H, H)), KO.device_matrix(torch.zeros(H, H, dtype=bf, device=dev)),
+                one.clone(), KO.device_matrix(mat(2 * F, H)), KO.device_matrix(torch.zeros(H, F, dtype=bf, device=dev)))
 
     embed = mat(V, H)
     lm = (torch.roll(embed.float(), 1, dims=0) * (gain / 0.02)).to(bf)
-    w = dict(embed=embed, lm_head=KO.fragment_major(lm), final_norm=torch.ones(H, dtype=bf, device=dev),
+    w = dict(embed=embed, lm_head=KO.device_matrix(lm), final_norm=torch.ones(H, dtype=bf, device=dev),
              layers=[layer() for _ in range(cfg["n_layers"])])
     fc = torch.zeros(H, 2 * H, dtype=torch.float32, device=dev)
     fc[:, :H] = torch.eye(H, device=dev)
     if sigma:
         fc[:, :H] += sigma / H ** 0.5 * torch.randn(H, H, generator=g, device=dev, dtype=torch.float32)
-    w["fc"] = KO.fragment_major(fc.to(bf))
+    w["fc"] = KO.device_matrix(fc.to(bf))
     w["draft"] = [t for _ in range(K) for t in layer()]
     return w
 

@@ -36,13 +36,18 @@
  * Matrix storage.  For KOALA_FP32 every matrix [N, K] is plain row-major.  For
  * KOALA_BF16 every Linear weight (wqkv, wo, wgu, wdown, lm_head, fc, Medusa
  * blocks) is stored "fragment-major", the order in which a gfx950 wave feeds a
- * 16x16x32 bf16 MFMA, so that the weight stream is read from HBM as contiguous
+ * 16x16x32 MFMA, so that the weight stream is read from HBM as contiguous
  * 1 KiB pieces.  With Npad = N rounded up to a multiple of 64 (extra rows zero)
- * and K a multiple of 64, element (n, k) lives at bf16 index
+ * and K a multiple of 64, element (n, k) lives at 16-bit index
  *     (((((n/64) * (K/64) + k/64) * 4 + (n%64)/16) * 2 + (k%64)/32) * 64
  *        + (n%16) + 16*((k%32)/8)) * 8 + k%8,
  * i.e. tiles of 64 rows x 64 k, each tile being 8 fragments of 64 lanes x 8
- * values.  The embedding table and the RMSNorm gains stay row-major / linear.
+ * values.  The matrix pipe multiplies in fp16 (with fp32 accumulation): a matrix
+ * laid out this way in bfloat16 is handed to koala_weights_to_half once, which
+ * rewrites it in place as fp16 (the same values: a bfloat16 number has eight
+ * significant bits, fp16 holds eleven), and it is that form koala_bind takes.
+ * The embedding table, the RMSNorm gains and the KV caches stay bfloat16,
+ * row-major / linear.
  */
 #ifndef KOALA_H
 #define KOALA_H
@@ -295,6 +300,13 @@ koala_status koala_generate_sample(koala_ctx *ctx, void *hip_stream, const float
                                    const int32_t *tok_in, int m, int ctx_len0, int max_new,
                                    const float *uniforms, int max_iters, float temperature,
                                    int32_t *out_tokens, koala_gen_stats *stats);
+
+/* Linear weights of the bfloat16 path, once, before koala_bind (see "Matrix storage"): `packed` is a
+ * fragment-major matrix of n_elements bfloat16 values in device memory (16-byte aligned, n_elements a
+ * multiple of 8) and is rewritten in place as fp16 by a kernel enqueued on the stream.  Exact for
+ * magnitudes from 2^-24 to 65504; smaller values round to the nearest multiple of 2^-24, larger ones
+ * become infinite.  Calling it twice on the same matrix destroys it.  No koala_ctx is needed. */
+koala_status koala_weights_to_half(void *hip_stream, void *packed, size_t n_elements);
 
 /* Measurement aid (not part of the method): the rate at which this device streams `bytes` of
  * `buffer` (device memory, 16-byte aligned) through a plain read kernel with the same load

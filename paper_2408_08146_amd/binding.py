@@ -9,7 +9,8 @@ KOALA_DRAFT_EAGLE, KOALA_DRAFT_MEDUSA = 0, 1
 
 EXPORTS = ("koala_create", "koala_workspace_bytes", "koala_bind", "koala_draft_expand",
            "koala_tree_verify", "koala_accept_prefix", "koala_generate", "koala_draft_expand_sample",
-           "koala_accept_sample", "koala_accept_sample_static", "koala_generate_sample", "koala_measure_stream_read", "koala_profile_begin",
+           "koala_accept_sample", "koala_accept_sample_static", "koala_generate_sample", "koala_weights_to_half",
+           "koala_measure_stream_read", "koala_profile_begin",
            "koala_profile_end", "koala_train_workspace_bytes", "koala_train_disc_step", "koala_train_gen_grad",
            "koala_train_medusa_workspace_bytes", "koala_train_medusa_head_forward", "koala_train_medusa_head_step",
            "koala_last_error", "koala_destroy")
@@ -95,6 +96,7 @@ def load_library():
     lib.koala_accept_sample.argtypes = [vp, vp, ip, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, ip]
     lib.koala_accept_sample_static.argtypes = lib.koala_accept_sample.argtypes
     lib.koala_generate_sample.argtypes = [vp, vp, vp, vp, ip, ip, ip, vp, ip, C.c_float, vp, C.POINTER(_GenStats)]
+    lib.koala_weights_to_half.argtypes = [vp, vp, C.c_size_t]
     lib.koala_measure_stream_read.argtypes = [vp, vp, C.c_size_t, vp, ip, C.POINTER(C.c_double)]
     lib.koala_profile_begin.argtypes = [vp, ip]
     lib.koala_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(ip), C.POINTER(C.c_double)]
@@ -115,6 +117,18 @@ def load_library():
         getattr(lib, n).restype = C.c_int
     _LIB = lib
     return lib
+
+
+def weights_to_f16(packed, stream=None):
+    """A fragment-major bfloat16 weight matrix (flat device tensor) rewritten in place as fp16 by the library
+    (koala_weights_to_half); returns the same memory viewed as float16.  Call once per matrix."""
+    import torch
+    lib = load_library()
+    assert packed.dtype == torch.bfloat16 and packed.is_cuda and packed.is_contiguous()
+    rc = lib.koala_weights_to_half(_stream(stream), C.c_void_p(packed.data_ptr()), packed.numel())
+    if rc != 0:
+        raise KoalaError(rc, "koala_weights_to_half failed")
+    return packed.view(torch.float16)
 
 
 def measure_stream_read(buffer, repeats=5, stream=None):

@@ -3,12 +3,13 @@
 // Every projection of the draft-then-verify iteration has only a handful of activation rows
 // (the tree nodes) against a large weight matrix, so it is bound by how fast the weights
 // stream out of HBM.  The kernels here are built around that:
-//   * weights are stored fragment-major (see koala.h): one wave load instruction reads 1 KiB of
-//     contiguous memory and lands exactly in the A operand of a 16x16x32 bf16 MFMA;
-//   * GEMM inputs are written by their producers as bf16 hi + lo parts (x = hi + lo to ~16
-//     mantissa bits) in MFMA fragment order, so results stay at fp32-class accuracy on the bf16
-//     MFMA; RMSNorm is split into the gain (applied by the producer) and the row scale (applied by
-//     whoever consumes the GEMM result), since the GEMM is linear in the row scale;
+//   * weights are stored fragment-major (see koala.h) as fp16 images of their bf16 values (exact: eight
+//     significant bits fit eleven; k_weights_to_f16 below converts a packed matrix once): one wave load
+//     instruction reads 1 KiB of contiguous memory and lands exactly in the A operand of a 16x16x32 fp16 MFMA;
+//   * GEMM inputs are written by their producers as fp16 in MFMA fragment order (eleven significant bits
+//     against the eight of a bf16 activation; products are exact and accumulate in fp32); RMSNorm is split
+//     into the gain (applied by the producer) and the row scale (applied by whoever consumes the GEMM
+//     result), since the GEMM is linear in the row scale;
 //   * K is split over workgroups; partial sums go to a scratch buffer that the consumer
 //     kernel adds up in a fixed order (deterministic, no float atomics).
 #include "koala_internal.h"
@@ -24,6 +25,8 @@ struct __attribute__((may_alias, aligned(8))) f32_pair { float x, y; };
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 
 __device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
 // (a, b) as bfloat16 pairs hi and lo with a ~ hi.x + lo.x, b ~ hi.y + lo.y (~16 mantissa bits): one packed
@@ -42,7 +45,17 @@ __device__ __forceinline__ HiLo split_pair(float a, float b) {
 __device__ __forceinline__ int split_begin(int i, int n, int S) {
     return S == 1 ? i * n : (int)((unsigned)(i * n) / (unsigned)S);
 }
-// eight values -> the hi and lo 16-byte pieces of a fragment lane
+// (a, b) as a pair of fp16 (round to nearest even), values beyond the fp16 range clamped to its largest finite one
+__device__ __forceinline__ uint32_t half_pair(float a, float b) {
+    a = __builtin_fminf(__builtin_fmaxf(a, -65504.f), 65504.f);
+    b = __builtin_fminf(__builtin_fmaxf(b, -65504.f), 65504.f);
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){a, b}, f16x2));
+}
+// eight values -> the 16 bytes of a GEMM input fragment lane
+__device__ __forceinline__ u32x4 half8(const float *y) {
+    return (u32x4){half_pair(y[0], y[1]), half_pair(y[2], y[3]), half_pair(y[4], y[5]), half_pair(y[6], y[7])};
+}
+// eight values -> the hi and lo 16-byte pieces of a fragment lane (bf16 pairs: the attention kernel's operands)
 __device__ __forceinline__ void split8(const float *y, u32x4 &h, u32x4 &w) {
     const HiLo p0 = split_pair(y[0], y[1]), p1 = split_pair(y[2], y[3]), p2 = split_pair(y[4], y[5]), p3 = split_pair(y[6], y[7]);
     h = (u32x4){p0.hi, p1.hi, p2.hi, p3.hi};
@@ -57,7 +70,7 @@ __device__ __forceinline__ uint32_t f2bf(float v) {  // round to nearest even
 // ---------------------------------------------------------------------------------------------
 // Packed GEMM.  Wp: [Npad/64][K/64] tiles of 64 rows x 64 k, each tile = 8 fragments
 // (t = row/16, s = k/32) of 64 lanes x 16 B; lane = (row%16) + 16*((k%32)/8).
-// Xf: [K/32][MTT][hi,lo][64 lanes] x 16 B; lane = (m%16) + 16*((k%32)/8); a launch handles the MT
+// Xf: [K/32][MTT][64 lanes] x 16 B (fp16); lane = (m%16) + 16*((k%32)/8); a launch handles the MT
 //     activation tiles mt0 .. mt0+MT-1 of the MTT present.
 // P:  [S][MTT*16][Npad] fp32 partial sums; split sp covers 128-k chunks [sp*nch/S, (sp+1)*nch/S).
 // Workgroup = 4 waves; wave w owns row block wb*4 + w (64 rows); the X chunk is shared in LDS.
@@ -72,7 +85,7 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
     extern __shared__ u32x4 xs[];            // [2][XCH]
     constexpr int MTW = MT * RS;             // activation tiles of the workgroup
     constexpr int NT = 256 * RS;
-    constexpr int XCH = 4 * MTW * 2 * 64;    // 16-byte units of X per 128-k chunk
+    constexpr int XCH = 4 * MTW * 64;        // 16-byte units of X per 128-k chunk
     constexpr int XPT = XCH / NT;            // per thread
     const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, li = l & 15, lg = l >> 4;
     const int wv = wave & 3, rs = wave >> 2;
@@ -83,9 +96,9 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
     const int rb = wb * 4 + wv;
     const bool active = rb < Npad / 64;
     const u32x4 *wsrc = Wp + ((size_t)(active ? rb : 0) * (K / 64) + (size_t)c_begin * 2) * 512 + l;
-    // 16-byte unit u of chunk c lives at xsrc + (c*4 + u / (MTW*128)) * MTT*128 + u % (MTW*128)
-    const u32x4 *xsrc = Xf + (size_t)c_begin * 4 * MTT * 128 + (size_t)mt0 * 128;
-    auto xaddr = [&](int c, int u) { return xsrc + ((size_t)c * 4 + u / (MTW * 128)) * (MTT * 128) + u % (MTW * 128); };
+    // 16-byte unit u of chunk c lives at xsrc + (c*4 + u / (MTW*64)) * MTT*64 + u % (MTW*64)
+    const u32x4 *xsrc = Xf + (size_t)c_begin * 4 * MTT * 64 + (size_t)mt0 * 64;
+    auto xaddr = [&](int c, int u) { return xsrc + ((size_t)c * 4 + u / (MTW * 64)) * (MTT * 64) + u % (MTW * 64); };
     f32x4 acc[4][MT];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
@@ -121,28 +134,20 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
         if (active) {
 #pragma unroll
             for (int bb = 0; bb < 2; ++bb) {
-                bf16x8 a[8];
+                f16x8 a[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) a[j] = __builtin_bit_cast(bf16x8, wr[bb][j]);
+                for (int j = 0; j < 8; ++j) a[j] = __builtin_bit_cast(f16x8, wr[bb][j]);
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
-                    const u32x4 *xk = xc + (bb * 2 + s) * (MTW * 2 * 64) + rs * (MT * 2 * 64);
-                    bf16x8 xh[MT], xl[MT];
+                    const u32x4 *xk = xc + (bb * 2 + s) * (MTW * 64) + rs * (MT * 64);
+                    f16x8 xv[MT];
 #pragma unroll
-                    for (int m = 0; m < MT; ++m) {
-                        xh[m] = __builtin_bit_cast(bf16x8, xk[(m * 2 + 0) * 64 + l]);
-                        xl[m] = __builtin_bit_cast(bf16x8, xk[(m * 2 + 1) * 64 + l]);
-                    }
+                    for (int m = 0; m < MT; ++m) xv[m] = __builtin_bit_cast(f16x8, xk[m * 64 + l]);
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
 #pragma unroll
                         for (int m = 0; m < MT; ++m)
-                            acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t * 2 + s], xh[m], acc[t][m], 0, 0, 0);
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-#pragma unroll
-                        for (int m = 0; m < MT; ++m)
-                            acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t * 2 + s], xl[m], acc[t][m], 0, 0, 0);
+                            acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t * 2 + s], xv[m], acc[t][m], 0, 0, 0);
                 }
                 // reloading a batch only after its MFMAs keeps the register count low enough for three (MT <= 2)
                 // or two (MT = 4) workgroups per CU; the other batch is in flight meanwhile
@@ -171,7 +176,7 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
 // Row-group GEMM with a fused epilogue.  One workgroup owns U consecutive 16-row groups of the weights
 // (16 U output columns) over a K range; its waves take the 64-k tiles of that range in turn (wave w:
 // tiles w, w + KW, ...) and every wave loads both operands of its tiles straight into MFMA registers -
-// the U 2 KiB weight pieces and the matching hi/lo activation fragments - so the streaming loop has no
+// the U 2 KiB weight pieces and the matching activation fragments - so the streaming loop has no
 // barrier and no LDS traffic.  The waves' accumulators meet at the end, in LDS, and are added in a fixed order
 // (deterministic).  With S = 1 the workgroup then holds finished outputs and applies the consumer's
 // element-wise step itself:
@@ -179,7 +184,7 @@ __global__ __launch_bounds__(256 * RS, RS > 1 ? 1 : MT == 4 ? 2 : 3) void k_gemm
 //   EPI_QKV      row scale of the pending RMSNorm, rotary embedding, queries (times 1/sqrt(head_dim)) as hi/lo
 //                MFMA fragments for the attention kernel, rotated keys and values to their cache slots (bf16).  W_q / W_k rows are stored pair-interleaved
 //                (koala.h), so the two halves of a rotary pair are neighbours in one lane;
-//   EPI_SWIGLU   row scale, SiLU(gate) * up (rows interleaved gate, up), written as hi/lo fragments of the
+//   EPI_SWIGLU   row scale, SiLU(gate) * up (rows interleaved gate, up), written as fragments of the
 //                down projection's input.
 // Every compute unit can take in only so many bytes per second (about 53 GB/s measured, weights and
 // activations together), and with S = 1 every workgroup reads all activation fragments; U is therefore
@@ -227,9 +232,9 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
         const int ug = min(ug0 + j, nunits - 1);
         w[j] = Wp + ((size_t)(ug >> 2) * nkt * 8 + (ug & 3) * 2) * 64 + l;
     }
-    const u32x4 *x = Xf + (size_t)mh * MT * 128 + l;
+    const u32x4 *x = Xf + (size_t)mh * MT * 64 + l;
 
-    u32x4 wr[PF][U][2], xr[PF][2][MT][2];
+    u32x4 wr[PF][U][2], xr[PF][2][MT];
     auto load = [&](int kt, int slot) {
 #pragma unroll
         for (int j = 0; j < U; ++j)
@@ -238,10 +243,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int m = 0; m < MT; ++m)
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    xr[slot][s][m][h] = x[(size_t)(2 * kt + s) * (MTT * 128) + (m * 2 + h) * 64];
+            for (int m = 0; m < MT; ++m) xr[slot][s][m] = x[(size_t)(2 * kt + s) * (MTT * 64) + m * 64];
     };
     int kt = kt0 + kw;
 #pragma unroll
@@ -291,14 +293,11 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
                 for (int s = 0; s < 2; ++s) {
 #pragma unroll
                     for (int j = 0; j < U; ++j) {
-                        const bf16x8 a = __builtin_bit_cast(bf16x8, wr[p][j][s]);
+                        const f16x8 a = __builtin_bit_cast(f16x8, wr[p][j][s]);
 #pragma unroll
-                        for (int m = 0; m < MT; ++m) {
-                            acc[j][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                a, __builtin_bit_cast(bf16x8, xr[p][s][m][0]), acc[j][m], 0, 0, 0);
-                            acc[j][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                a, __builtin_bit_cast(bf16x8, xr[p][s][m][1]), acc[j][m], 0, 0, 0);
-                        }
+                        for (int m = 0; m < MT; ++m)
+                            acc[j][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                                a, __builtin_bit_cast(f16x8, xr[p][s][m]), acc[j][m], 0, 0, 0);
                     }
                 }
                 if (kt + (p + PF) * KW < kt1) load(kt + (p + PF) * KW, p);
@@ -401,12 +400,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
             if (f0 >= e.F) continue;
             const float g0 = v[0], g1 = v[2];
             const float y0 = g0 / (1.0f + __expf(-g0)) * v[1], y1 = g1 / (1.0f + __expf(-g1)) * v[3];
-            const HiLo pr = split_pair(y0, y1);
-            const uint32_t hi = pr.hi, lo = pr.lo;
             const int ks = f0 >> 5, lane = li + 16 * ((f0 & 31) >> 3);
-            uint32_t *dst = e.Xo + ((((size_t)ks * MTT + mtt) * 2) * 64 + lane) * 4 + ((f0 & 7) >> 1);
-            dst[0] = hi;
-            dst[64 * 4] = lo;
+            e.Xo[(((size_t)ks * MTT + mtt) * 64 + lane) * 4 + ((f0 & 7) >> 1)] = half_pair(y0, y1);
         }
     }
 }
@@ -431,8 +426,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const u32x4 *__restrict__
 // their data is distance enough; a value computed in the vector unit needs a few idle cycles before the matrix
 // instruction reads it, or the instruction now and then sees the register's old contents), and the result may be
 // read only after mfma_settle.
-__device__ __forceinline__ void mfma_acc(f32x4 &acc, bf16x8 a, bf16x8 b) {
-    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+__device__ __forceinline__ void mfma_acc(f32x4 &acc, f16x8 a, f16x8 b) {
+    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 // Results of the matrix pipe may be read by other instructions only some cycles after the MFMA was issued; for
 // the compiler's own MFMAs the compiler sees to that, for mfma_acc it cannot.  These statements wait (WAIT) and
@@ -464,10 +459,11 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
     extern __shared__ __attribute__((aligned(16))) unsigned char bsm[];
     typedef __attribute__((address_space(3))) void lds_void;
     typedef const __attribute__((address_space(1))) void glb_void;
-    constexpr int XT = 2 * MTW * 2 * 64;   // 16-byte units of one 64-k tile of activations: [s][m][hi, lo][64]
-    constexpr int XD = 4;                  // (s, m) pairs of activation fragments read from LDS ahead of their use
-    constexpr int NP = 2 * MTW;            // (s, m) pairs per tile
-    constexpr int NOPS = MTW + 1 + 2 * U;  // load steps of a wave per tile: its share of X(t+1), the touches, then W(t+3)
+    constexpr int XT = 2 * MTW * 64;       // 16-byte units of one 64-k tile of activations: [s][m][64]
+    constexpr int XD = 4;                  // activation fragments read from LDS ahead of their use
+    constexpr int NP = 2 * MTW;            // (s, m) fragments per tile
+    constexpr int NXF = (NP + 3) / 4;      // one-KiB pieces of an activation tile a wave copies into LDS
+    constexpr int NOPS = NXF + 1 + 2 * U;  // load steps of a wave per tile: its share of X(t+1), the touches, then W(t+3)
     u32x4 *xs = (u32x4 *)bsm;              // [2][XT]
     // the wave number as a scalar: everything derived from it (which weight rows, which pieces of the activation
     // tile this wave fetches, where they land in LDS) is then computed once per wave, not per lane
@@ -496,22 +492,24 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
         const int j = q >> 1, s = q & 1;
         wr[slot][j][s] = __builtin_nontemporal_load((const u32x4 *)(Wb + (woff[j] + (unsigned)kt * 8192u + s * 1024u)));
     };
-    // The 2 * MTW * 2 one-KiB pieces (s, m, hl) of an activation tile are dealt to the waves in turn; piece i of this
-    // wave for tile kt goes to LDS buffer b (tiles past the last one re-read it: computed, never stored)
-    const unsigned xstride = (unsigned)MTT * 4096u;   // bytes of the activation fragments of one 64-k tile
+    // The 2 * MTW one-KiB pieces (s, m) of an activation tile are dealt to the waves in turn; piece i of this wave
+    // for tile kt goes to LDS buffer b (tiles past the last one re-read it: computed, never stored).  Every wave
+    // issues the same number of copies, which the waits below count on: where the pieces do not divide by four,
+    // the last one is copied by more than one wave (same bytes to the same place).
+    const unsigned xstride = (unsigned)MTT * 2048u;   // bytes of the activation fragments of one 64-k tile
     auto xfill1 = [&](int i, int kt, int b) {
-        const int f = wave + 4 * i, hl = f & 1, m = (f >> 1) % MTW, s = (f >> 1) / MTW;
-        const unsigned off = (unsigned)((s * MTT + min(mt0 + m, MTT - 1)) * 2 + hl) * 1024u + (unsigned)kt * xstride;
-        u32x4 *dst = xs + (size_t)b * XT + ((s * MTW + m) * 2 + hl) * 64;   // wave-uniform; lane i lands at dst + i
+        const int f = min(wave + 4 * i, NP - 1), m = f % MTW, s = f / MTW;
+        const unsigned off = (unsigned)(s * MTT + min(mt0 + m, MTT - 1)) * 1024u + (unsigned)kt * xstride;
+        u32x4 *dst = xs + (size_t)b * XT + (s * MTW + m) * 64;   // wave-uniform; lane i lands at dst + i
         __builtin_amdgcn_global_load_lds((glb_void *)(Xb + (off + (unsigned)l * 16u)), (lds_void *)dst, 16, 0, 0);
     };
-    // The activation fragments of a 64-k tile are two runs of MTW * 2 KiB (one per k half).  They are touched two
+    // The activation fragments of a 64-k tile are two runs of MTW KiB (one per k half).  They are touched two
     // tiles ahead with one 4-byte load per 128-byte line (one line per lane and run, lanes past the end repeat the
     // last line), so that the copy into LDS one tile later finds them in L2 instead of waiting for HBM.  The
     // touches are loads to LDS as well, into 256 bytes per wave behind the tile buffers that nobody reads: a load
     // into a register nobody reads would have that register handed to another value while the load is under way.
-    const int pf_lines = min(MTW, MTT - mt0) * 16;
-    const unsigned pf_off = (unsigned)mt0 * 2048u + (unsigned)min((int)threadIdx.x, pf_lines - 1) * 128u;
+    const int pf_lines = min(MTW, MTT - mt0) * 8;
+    const unsigned pf_off = (unsigned)mt0 * 1024u + (unsigned)min((int)threadIdx.x, pf_lines - 1) * 128u;
     unsigned char *pf_sink = bsm + (size_t)2 * XT * 16 + wave * 256;
     // EPI_SWIGLU: RMSNorm's scale of each of the workgroup's rows (from the per-chunk sums of squares of the input
     // rows), one row per thread, fetched now and parked in LDS behind the sinks until the epilogue
@@ -541,7 +539,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
     auto xtouch = [&](int kt) {
 #pragma unroll
         for (int s = 0; s < 2; ++s)
-            __builtin_amdgcn_global_load_lds((glb_void *)(Xb + (pf_off + (unsigned)(2 * kt + s) * ((unsigned)MTT * 2048u))),
+            __builtin_amdgcn_global_load_lds((glb_void *)(Xb + (pf_off + (unsigned)(2 * kt + s) * ((unsigned)MTT * 1024u))),
                                              (lds_void *)pf_sink, 4, 0, 0);
     };
     f32x4 acc[U][MTW];
@@ -568,7 +566,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
 #pragma unroll
         for (int q = 0; q < 2 * U; ++q) wload1(q, min(kt0 + 2, last), 2);
 #pragma unroll
-        for (int i = 0; i < MTW; ++i) xfill1(i, kt0, 0);
+        for (int i = 0; i < NXF; ++i) xfill1(i, kt0, 0);
         xtouch(min(kt0 + 1, last));
         xtouch(min(kt0 + 2, last));
         __builtin_amdgcn_s_waitcnt(0);
@@ -576,16 +574,21 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
     // One 64-k tile; p = (tt - kt0) % 4 says where it lives in the weight ring and the LDS buffers.  The tiles come
     // in groups of four with no decisions in between (so that the compiler's view of which loads are under way
     // stays exact from one group to the next), followed by up to three tiles of a last, partial group.
-    auto tile = [&](int tt, auto pc) __attribute__((always_inline)) {
+    // The tiles of the last, partial group wait for every load instead: the weight loads they would issue feed
+    // no later tile, the compiler drops them, and "all but the newest 2 U + 2" would then let copies of the
+    // activation tile pass that have not landed.
+    constexpr int WAIT_ALL_LOADS = (7 << 4) | (15 << 8);   // s_waitcnt vmcnt(0)
+    auto tile = [&](int tt, auto pc, auto lastgroup) __attribute__((always_inline)) {
         constexpr int p = decltype(pc)::value;
-        __builtin_amdgcn_s_waitcnt(WAIT_BUT_NEWEST);   // nothing is under way before the first tile
+        // nothing is under way before the first tile
+        __builtin_amdgcn_s_waitcnt(decltype(lastgroup)::value ? WAIT_ALL_LOADS : WAIT_BUT_NEWEST);
         // every wave's part of X(tt) is in LDS; nobody still reads the other buffer.  A bare barrier instruction
         // (the waits it needs are the ones above), fenced for the compiler so that no LDS access crosses it
         asm volatile("s_barrier" ::: "memory");
-        // The activation fragments come from LDS through a ring of XD + 1 register pairs (hi, lo), read XD
-        // (s, m) pairs ahead of the MFMAs that use them, because an LDS read takes longer than the 2 U MFMAs
-        // of one pair.  Reads and waits are written out as instructions: LDS reads complete in issue order,
-        // so "at most 2 (XD - 1) reads still under way" says exactly that the pair about to be used has
+        // The activation fragments come from LDS through a ring of XD + 1 registers, read XD fragments ahead
+        // of the MFMAs that use them, because an LDS read takes longer than the U MFMAs of one fragment.
+        // Reads and waits are written out as instructions: LDS reads complete in issue order,
+        // so "at most XD - 1 reads still under way" says exactly that the fragment about to be used has
         // arrived, which the compiler's own bookkeeping rounds down to "none under way" for operands of the
         // MFMA statement above.  The results of such a read must stay where they are until that wait, which
         // holds as long as the kernel does not spill (one workgroup per compute unit: 512 registers a lane).
@@ -593,53 +596,44 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
         // the MFMAs, a few at a time, where the matrix pipe is busy anyway.
         lds_u32x4 *xb = (lds_u32x4 *)(xs + (size_t)(p & 1) * XT + l);
         const int ktx = min(tt + 1, last), ktw = min(tt + 3, last);
-        u32x4 xr[XD + 1][2];
+        u32x4 xr[XD + 1];
 #pragma unroll
-        for (int i = 0; i < XD; ++i) {
-            xr[i][0] = lds_read16(xb, (i * 2 + 0) * 1024);
-            xr[i][1] = lds_read16(xb, (i * 2 + 1) * 1024);
-        }
+        for (int i = 0; i < XD; ++i) xr[i] = lds_read16(xb, i * 1024);
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             const int s = i / MTW, m = i % MTW;
-            wait_lds_reads(2 * (NP - 1 - i < XD - 1 ? NP - 1 - i : XD - 1));   // reads issued after pair i's
-            const bf16x8 xh = __builtin_bit_cast(bf16x8, xr[i % (XD + 1)][0]);
-            const bf16x8 xl = __builtin_bit_cast(bf16x8, xr[i % (XD + 1)][1]);
+            wait_lds_reads(NP - 1 - i < XD - 1 ? NP - 1 - i : XD - 1);   // reads issued after fragment i's
+            const f16x8 xv = __builtin_bit_cast(f16x8, xr[i % (XD + 1)]);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_acc(acc[0][m], __builtin_bit_cast(bf16x8, wr[p][0][s]), xh);
+            mfma_acc(acc[0][m], __builtin_bit_cast(f16x8, wr[p][0][s]), xv);
             __builtin_amdgcn_sched_barrier(0);
-            if (i + XD < NP) xr[(i + XD) % (XD + 1)][0] = lds_read16(xb, ((i + XD) * 2 + 0) * 1024);
+            if (i + XD < NP) xr[(i + XD) % (XD + 1)] = lds_read16(xb, (i + XD) * 1024);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_acc(acc[1][m], __builtin_bit_cast(bf16x8, wr[p][1][s]), xh);
+            mfma_acc(acc[1][m], __builtin_bit_cast(f16x8, wr[p][1][s]), xv);
             __builtin_amdgcn_sched_barrier(0);
-            if (i + XD < NP) xr[(i + XD) % (XD + 1)][1] = lds_read16(xb, ((i + XD) * 2 + 1) * 1024);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int j = 2; j < U; ++j) mfma_acc(acc[j][m], __builtin_bit_cast(bf16x8, wr[p][j][s]), xh);
-            __builtin_amdgcn_sched_barrier(0);
-            // this pair's share of the tile's global loads: X pieces first, then W fragments
+            // this fragment's share of the tile's global loads: X pieces first, then W fragments
 #pragma unroll
             for (int q = i * NOPS / NP; q < (i + 1) * NOPS / NP; ++q) {
-                if (q < MTW) xfill1(q, ktx, (p + 1) & 1);
-                else if (q == MTW) xtouch(ktw);
-                else wload1(q - MTW - 1, ktw, (p + 3) & 3);
+                if (q < NXF) xfill1(q, ktx, (p + 1) & 1);
+                else if (q == NXF) xtouch(ktw);
+                else wload1(q - NXF - 1, ktw, (p + 3) & 3);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < U; ++j) mfma_acc(acc[j][m], __builtin_bit_cast(bf16x8, wr[p][j][s]), xl);
+            for (int j = 2; j < U; ++j) mfma_acc(acc[j][m], __builtin_bit_cast(f16x8, wr[p][j][s]), xv);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     int t = kt0;
     for (; t + 4 <= kt1; t += 4) {
-        tile(t, std::integral_constant<int, 0>{});
-        tile(t + 1, std::integral_constant<int, 1>{});
-        tile(t + 2, std::integral_constant<int, 2>{});
-        tile(t + 3, std::integral_constant<int, 3>{});
+        tile(t, std::integral_constant<int, 0>{}, std::false_type{});
+        tile(t + 1, std::integral_constant<int, 1>{}, std::false_type{});
+        tile(t + 2, std::integral_constant<int, 2>{}, std::false_type{});
+        tile(t + 3, std::integral_constant<int, 3>{}, std::false_type{});
     }
-    if (t < kt1) tile(t, std::integral_constant<int, 0>{});
-    if (t + 1 < kt1) tile(t + 1, std::integral_constant<int, 1>{});
-    if (t + 2 < kt1) tile(t + 2, std::integral_constant<int, 2>{});
+    if (t < kt1) tile(t, std::integral_constant<int, 0>{}, std::true_type{});
+    if (t + 1 < kt1) tile(t + 1, std::integral_constant<int, 1>{}, std::true_type{});
+    if (t + 2 < kt1) tile(t + 2, std::integral_constant<int, 2>{}, std::true_type{});
     {
         f32x4 *t = &acc[0][0];
         constexpr int NT = U * MTW;
@@ -714,7 +708,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
     } else {
         // EPI_SWIGLU (one K split): the weight rows interleave gate and up, so a lane's four columns are (gate, up)
         // of two features of one activation row.  RMSNorm's row scale (from the per-chunk sums of squares of the
-        // input rows) is applied, then SiLU(gate) * up, stored as hi/lo fragments of the down projection's input.
+        // input rows) is applied, then SiLU(gate) * up, stored as fragments of the down projection's input.
 #pragma unroll
         for (int m = 0; m < MTW; ++m) {
             const int row = (mt0 + m) * 16 + li;
@@ -727,11 +721,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(const u32x4 *__restrict__ W
                 const f32x4 v = acc[j][m] * rsc;
                 const float g0 = v[0], g1 = v[2];
                 const float y0 = g0 / (1.0f + __expf(-g0)) * v[1], y1 = g1 / (1.0f + __expf(-g1)) * v[3];
-                const HiLo pr = split_pair(y0, y1);
                 const int ks = f0 >> 5, lane = li + 16 * ((f0 & 31) >> 3);
-                uint32_t *dst = e.Xo + ((((size_t)ks * MTT + (mt0 + m)) * 2) * 64 + lane) * 4 + ((f0 & 7) >> 1);
-                dst[0] = pr.hi;
-                dst[64 * 4] = pr.lo;
+                e.Xo[(((size_t)ks * MTT + (mt0 + m)) * 64 + lane) * 4 + ((f0 & 7) >> 1)] = half_pair(y0, y1);
             }
         }
     }
@@ -811,14 +802,10 @@ __device__ __forceinline__ void psum8(const float *P, int S, int Mp, int ld, int
     v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
 }
 
-// store 8 consecutive k of row m (k0 % 8 == 0) as hi/lo fragments
+// store 8 consecutive k of row m (k0 % 8 == 0) into the GEMM input fragments
 __device__ __forceinline__ void store_frag8(u32x4 *Xf, int MT, int m, int k0, const float *y) {
-    u32x4 h, w;
-    split8(y, h, w);
     const int ks = k0 >> 5, lane = (m & 15) + 16 * ((k0 & 31) >> 3), mt = m >> 4;
-    u32x4 *dst = Xf + ((size_t)(ks * MT + mt) * 2) * 64 + lane;
-    dst[0] = h;
-    dst[64] = w;
+    Xf[(size_t)(ks * MT + mt) * 64 + lane] = half8(y);
 }
 
 // RMSNorm row scale from the per-chunk sums of squares a fold left: 1/sqrt(mean(x^2) + eps).
@@ -835,9 +822,25 @@ __device__ __forceinline__ float row_scale(const RowScale &rs, int row) {
     return 1.0f / sqrtf(tot / (float)rs.K + rs.eps);
 }
 
+// A packed weight matrix from bf16 to fp16, in place, eight values (16 bytes) a thread and step.  Every bf16 value
+// of magnitude 2^-24 .. 65504 has an exact fp16 image (at most eight significant bits, fp16 holds eleven, fewer
+// below 2^-14); smaller ones round to the nearest multiple of 2^-24, larger ones become infinite.
+__global__ __launch_bounds__(256) void k_weights_to_f16(u32x4 *w, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+        const u32x4 v = w[i];
+        const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            o[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(
+                                                    (f32x2){__uint_as_float(d[q] << 16), __uint_as_float(d[q] & 0xFFFF0000u)}, f16x2));
+        w[i] = (u32x4){o[0], o[1], o[2], o[3]};
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Fold: v = (mode 1: x +) sum of partials (mode 0: x as is); x <- v (modes 1, 2); optionally the
-// hi/lo fragments of gain * v (gain == nullptr: of v) for the next GEMM, and the sum of squares of
+// fragments of gain * v (gain == nullptr: of v) for the next GEMM, and the sum of squares of
 // each 512-column chunk to sums[chunk][m].  RMSNorm is linear in the row scale, so the GEMM runs
 // on gain * v and its consumer multiplies by row_scale().  grid (ceil(N/512), M), 64 threads x 8 cols.
 // ---------------------------------------------------------------------------------------------
@@ -915,7 +918,7 @@ __global__ void k_rope_append_p(const float *P, int S, int Mp, int ldp, RowScale
 }
 
 // SiLU(gate) * up from the gate/up partials (col 2f = gate, 2f+1 = up), scaled by the pending RMSNorm
-// row scale, as hi/lo fragments (K = F).  grid (ceil(F/8/64), M), 64 threads x 8 outputs
+// row scale, as fragments (K = F).  grid (ceil(F/8/64), M), 64 threads x 8 outputs
 __global__ __launch_bounds__(64) void k_silu_frag(const float *P, int S, int Mp, int ldp, RowScale rs, u32x4 *Xf,
                                                   int MT, int F) {
     const int r = blockIdx.y, g = blockIdx.x * 64 + threadIdx.x;
@@ -1159,7 +1162,7 @@ void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int N
     const dim3 grid(nwb * S);
 #define KOALA_GEMM(MTV, RSV, IDX)                                                                                \
     {                                                                                                            \
-        const size_t sm = (size_t)2 * 4 * MTV * RSV * 2 * 64 * 16;                                               \
+        const size_t sm = (size_t)2 * 4 * MTV * RSV * 64 * 16;                                                   \
         if (!g_attr_done[IDX]) {                                                                                 \
             (void)hipFuncSetAttribute((const void *)k_gemm_packed<MTV, RSV>,                                     \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);                      \
@@ -1243,7 +1246,7 @@ BigShape big_shape(int Npad, int K, int rows, int n_cu, bool one_split) {
                 if (one_split ? S != 1 : (fs >= 1 && fs <= 4 && fs <= nkt && S != fs)) continue;
                 const int wgs = ((units + 4 * U - 1) / (4 * U)) * n_pm * S, rounds = (wgs + n_cu - 1) / n_cu;
                 const double tiles = (double)((nkt + S - 1) / S);
-                const double wg = tiles * (64.0 * tmpl * U / 0.8 + 400.0) + 6000.0 + 30.0 * tmpl * U;
+                const double wg = tiles * (32.0 * tmpl * U / 0.8 + 400.0) + 6000.0 + 30.0 * tmpl * U;
                 const double partials = S > 1 ? 2.0 * S * (double)rows * Npad * 4.0 / 4.0e12 * 2.2e9 : 0.0;
                 const double hbm = (double)n_pm * Npad * K * 2.0 / 5.0e12 * 2.2e9;   // every tile block streams the weights
                 const double cost = std::max(rounds * wg, hbm) + partials;
@@ -1258,7 +1261,7 @@ template <int U, int MTW, int EPI>
 static void launch_gemm_big(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT,
                             const BigShape &b, const GemmEpi &e, hipEvent_t ev_start, hipEvent_t ev_stop) {
     // two tile buffers + the sink of the touches + the rows' scales, cache slots and sequences
-    const size_t sm = (size_t)2 * 2 * MTW * 2 * 64 * 16 + 4 * 256 + 3 * MTW * 16 * 4;
+    const size_t sm = (size_t)2 * 2 * MTW * 64 * 16 + 4 * 256 + 3 * MTW * 16 * 4;
     static bool done = false;
     if (!done) {
         (void)hipFuncSetAttribute((const void *)k_gemm_big<U, MTW, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1315,6 +1318,13 @@ void gemm_big_swiglu(hipStream_t st, const void *Wp, const void *Xf, int K, int 
     e.sums = ns.sums; e.nparts = ns.nparts; e.srows = ns.srows; e.Kn = ns.K; e.eps = ns.eps;
     e.rows = rows; e.Xo = (uint32_t *)Xo; e.F = F;
     dispatch_gemm_big<EPI_SWIGLU>(st, Wp, Xf, nullptr, pad64(2 * F), K, MTT, b, e, ev_start, ev_stop);
+}
+
+void weights_to_f16(hipStream_t st, void *w, size_t n_elements) {
+    const size_t n16 = n_elements / 8;
+    if (n16 == 0) return;
+    const int grid = (int)std::min<size_t>((n16 + 255) / 256, 4096);
+    k_weights_to_f16<<<grid, 256, 0, st>>>((u32x4 *)w, n16);
 }
 
 void fold(hipStream_t st, float *x, int ldx, const float *P, int S, int Mp, int ldp, int mode, int M, int N,
@@ -1375,7 +1385,7 @@ void reduce_out(hipStream_t st, const float *P, int S, int Mp, int ldp, float *o
 // The key splits of one (sequence, head, row group) are merged inside the kernel: every workgroup writes
 // its partial result (output, running max, sum) through to memory, then adds one to a counter; the
 // workgroup that finds the counter at nsplit - 1 reads all partial results back, merges them in split
-// order (deterministic) and writes the rows as hi/lo fragments of the O projection's input.  Nobody waits
+// order (deterministic) and writes the rows as fragments of the O projection's input.  Nobody waits
 // for anybody.  The counter is reset by that last workgroup, so it is zero again at the next launch.
 // =====================================================================================================
 namespace {
@@ -1431,7 +1441,7 @@ struct AttnArgs {
     float *o_part, *ml;   // [row][head][split][DH], [row][head][split][max, sum]
     unsigned opart_bytes, ml_bytes;
     int *counters;        // [batch][n_heads][row groups], zero between launches
-    u32x4 *Xf;            // merged output: hi/lo fragments, K = n_heads * DH, MT_out activation tiles
+    u32x4 *Xf;            // merged output: GEMM input fragments, K = n_heads * DH, MT_out activation tiles
     int MT_out;
     int rows_per_seq, MTQ, n_heads, cap, nsplit, batch, ngroups;
 };

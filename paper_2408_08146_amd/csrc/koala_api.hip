@@ -196,7 +196,7 @@ bool big_gemm_enabled() {
 
 // the many-row GEMM addresses both operands with 32-bit byte offsets
 bool big_fits32(int Npad, int K, int MT) {
-    return (double)Npad * K * 2.0 < 4.0e9 && (double)(K / 32) * MT * 2048.0 < 4.0e9;
+    return (double)Npad * K * 2.0 < 4.0e9 && (double)(K / 32) * MT * 1024.0 < 4.0e9;
 }
 
 // Split-K GEMM on the fragments in Xf (default: c->xf): partial sums of X * W^T into c->part; returns the split count.
@@ -876,6 +876,14 @@ koala_status koala_generate_sample(koala_ctx *c, void *hip_stream, const float *
     if (c && !uniforms) return fail(c, KOALA_E_NULL, "uniforms are required");
     return generate_impl(c, hip_stream, feat_in, tok_in, m, ctx_len0, max_new, 1, uniforms, max_iters, temperature,
                          out_tokens, stats);
+}
+
+koala_status koala_weights_to_half(void *hip_stream, void *packed, size_t n_elements) {
+    if (!packed) return KOALA_E_NULL;
+    if (n_elements % 8) return KOALA_E_SHAPE;
+    if ((uintptr_t)packed & 15) return KOALA_E_ALIGN;
+    kb::weights_to_f16((hipStream_t)hip_stream, packed, n_elements);
+    return hipGetLastError() == hipSuccess ? KOALA_OK : KOALA_E_DEVICE;
 }
 
 koala_status koala_measure_stream_read(void *hip_stream, const void *buffer, size_t bytes, void *sink, int repeats,

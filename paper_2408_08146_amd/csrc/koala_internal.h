@@ -180,7 +180,9 @@ namespace kb {
 inline int mt_of(int rows) { return rows <= 16 ? 1 : rows <= 32 ? 2 : 4 * ((rows + 63) / 64); }
 inline int pad64(int n) { return (n + 63) / 64 * 64; }
 
-inline size_t xf_bytes(int K, int MT) { return (size_t)(K / 32) * MT * 2 * 1024; }
+inline size_t xf_bytes(int K, int MT) { return (size_t)(K / 32) * MT * 1024; }
+// a packed bf16 weight matrix of n_elements values (a multiple of 8) to the fp16 the GEMMs multiply with, in place
+void weights_to_f16(hipStream_t st, void *w, size_t n_elements);
 
 // Pending RMSNorm row scale: 1/sqrt(sum_c sums[c][row] / K + eps); sums == nullptr means scale 1.
 struct NormScale {

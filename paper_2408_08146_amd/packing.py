@@ -1,5 +1,6 @@
 """Put named weight tensors into the device layout the library expects
-(pure data movement: concatenation, row interleaving, dtype views)."""
+(pure data movement: concatenation, row interleaving, dtype views; the one change of number format, the Linear
+weights of the bfloat16 path to fp16, is a library call)."""
 from __future__ import annotations
 
 import numpy as np
@@ -27,8 +28,15 @@ def fragment_major(w):
     return v.permute(0, 3, 1, 4, 5, 2, 6).contiguous().reshape(-1)
 
 
+def device_matrix(w):
+    """A row-major bfloat16 [N, K] Linear weight on the device in the form koala_bind takes: fragment-major,
+    then handed once to the library, which rewrites it as fp16 (koala_weights_to_half)."""
+    from .binding import weights_to_f16
+    return weights_to_f16(fragment_major(w))
+
+
 def _mat(w, dtype):
-    return fragment_major(w) if dtype == "bf16" else w.contiguous()
+    return device_matrix(w) if dtype == "bf16" else w.contiguous()
 
 
 def rotary_pair_interleave(w, head_dim):

@@ -43,20 +43,20 @@ def test_many_row_gemm_has_no_spills_and_no_register_copies_in_its_tile_loop():
         assert scratch == 0, f"{name} spills {scratch} bytes per lane"
         body = lines[s:end]
         assert not any("scratch_" in l for l in body), f"{name} uses scratch memory"
-        # a tile = the code from its barrier to the last of its 4 * U * MTW MFMAs (the kernel's name carries U, MTW)
+        # a tile = the code from its barrier to the last of its 2 * U * MTW MFMAs (the kernel's name carries U, MTW)
         U, MTW = (int(v) for v in re.search(r"k_gemm_bigILi(\d+)ELi(\d+)E", name).groups())
-        per_tile = 4 * U * MTW
+        per_tile = 2 * U * MTW
         tiles = 0
         for b in (i for i, l in enumerate(body) if l.strip() == "s_barrier"):
             seen, e = 0, b + 1
             while e < len(body) and seen < per_tile and body[e].strip() != "s_barrier":
-                seen += "v_mfma_f32_16x16x32_bf16" in body[e]
+                seen += "v_mfma_f32_16x16x32_f16" in body[e]
                 e += 1
             if seen < per_tile:
                 continue                      # the barrier before the epilogue
             tiles += 1
             tile = body[b:e]
-            assert sum("ds_read_b128" in l for l in tile) == 4 * MTW
+            assert sum("ds_read_b128" in l for l in tile) == 2 * MTW
             copies = [l.strip() for l in tile
                       if re.match(r"^\s*v_mov_b32(_e32)?\s+v\d+,\s*v\d+", l)
                       or re.match(r"^\s*v_accvgpr_read", l)
