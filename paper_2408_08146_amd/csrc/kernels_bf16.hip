@@ -1071,11 +1071,11 @@ void launch_gemm_rows(hipStream_t st, const void *Wp, const void *Xf, int Npad, 
 template <int U, int EPI>
 void dispatch_gemm_rows_u(hipStream_t st, const void *Wp, const void *Xf, int Npad, int K, int MTT, int S,
                           const GemmEpi &e, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    // tiles in flight per wave: two, or one where the registers do not hold a second (seven groups, four tiles)
-    constexpr int PF = U >= 7 ? 1 : 2;
+    // tiles in flight per wave: two, or one where the registers do not hold a second (four tiles with more than
+    // four groups)
     if (MTT == 1) launch_gemm_rows<U, 1, 1, 8, 2, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
-    else if (MTT == 2) launch_gemm_rows<U, 2, 1, 8, PF, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
-    else launch_gemm_rows<U, 4, 1, 8, 1, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
+    else if (MTT == 2) launch_gemm_rows<U, 2, 1, 8, 2, EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
+    else launch_gemm_rows<U, 4, 1, 8, (U <= 4 ? 2 : 1), EPI>(st, Wp, Xf, Npad, K, S, e, ev_start, ev_stop);
 }
 
 // 16-row groups per workgroup for an S = 1 launch over Npad rows: the smallest supported count that covers the
