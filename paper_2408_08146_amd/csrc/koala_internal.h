@@ -65,7 +65,7 @@ struct koala_ctx {
     int attn_ns;                   // key splits of the attention kernels (fixed at create)
     float *med_logits;                                   // [D * max_batch][V] per-depth logits of Medusa-style heads (sampled drafting)
     float *acc_q, *acc_d;                                // [max_batch][V] distributions of the stochastic acceptance walk
-    // bf16 path: GEMM input as hi/lo bf16 MFMA fragments, and the split-K partial sums
+    // bf16 path: GEMM input as fp16 MFMA fragments, and the split-K partial sums
     void *xf, *xf2;   // xf2: input of the down projection (written by the gate/up projection's epilogue)
     float *part;
     size_t xf_bytes, part_bytes;
@@ -172,7 +172,7 @@ void accept_sample(hipStream_t st, const TreeTables &tt, int T, int D, int V, fl
 }  // namespace ks
 
 // ---------------------------------------------------------------------------------------------
-// launchers implemented in kernels_bf16.hip (fragment-major bf16 weights, hi/lo bf16 activations)
+// launchers implemented in kernels_bf16.hip (fragment-major weights and activations in fp16)
 // ---------------------------------------------------------------------------------------------
 namespace kb {
 
@@ -193,7 +193,7 @@ struct NormScale {
 
 int gemm_splits(int Npad, int K, int MTT = 0);
 int rows_splits(int Npad, int K);              // split count of gemm_rows_partial   // MTT: activation tiles of the call (0: at most four)
-// P[S][MTT*16][Npad] = partial sums of X * W^T, X given as hi/lo fragments [K/32][MTT][2][64] x 16 B
+// P[S][MTT*16][Npad] = partial sums of X * W^T, X given as fp16 fragments [K/32][MTT][64] x 16 B
 // ev_start/ev_stop (either may be null) are attached to the dispatch: they take the kernel's own begin and end times
 void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S,
                  hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
@@ -201,7 +201,7 @@ void gemm_packed(hipStream_t st, const void *Wp, const void *Xf, float *P, int N
 // turn; n_cu = compute units of the device, which sets the groups per workgroup), MTT = 1, 2 or 4:
 // _partial: P[S][MTT*16][Npad] partial sums, like gemm_packed;  _qkv (S = 1): row scale, rotary embedding,
 // queries as attention fragments qf, keys/values into their cache slots (W_q, W_k rows pair-interleaved);  _swiglu (S = 1): row
-// scale, SiLU(gate) * up as hi/lo fragments Xo of the down projection's input
+// scale, SiLU(gate) * up as fragments Xo of the down projection's input
 void gemm_rows_partial(hipStream_t st, const void *Wp, const void *Xf, float *P, int Npad, int K, int MTT, int S,
                        hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 void gemm_rows_qkv(hipStream_t st, const void *Wp, const void *Xf, int K, int MTT, const NormScale &ns, int rows,
