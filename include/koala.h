@@ -48,6 +48,14 @@
  * significant bits, fp16 holds eleven), and it is that form koala_bind takes.
  * The embedding table, the RMSNorm gains and the KV caches stay bfloat16,
  * row-major / linear.
+ *
+ * Arithmetic of the KOALA_BF16 path.  Every projection multiplies fp16 by fp16
+ * and accumulates in fp32: its input (the normalised hidden state times the
+ * norm's gain, the attention output, SiLU(gate) * up) is rounded to fp16 where
+ * the producing kernel writes it, and a value beyond +-65504 saturates there.
+ * Attention multiplies the bfloat16 cache rows with queries and probabilities
+ * carried as bfloat16 hi + lo pairs; softmax, normalisation, residual stream,
+ * logits and features are fp32.
  */
 #ifndef KOALA_H
 #define KOALA_H

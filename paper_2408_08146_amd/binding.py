@@ -20,6 +20,9 @@ _STATUS = {0: "KOALA_OK", -1: "KOALA_E_NULL", -2: "KOALA_E_SHAPE", -3: "KOALA_E_
            -7: "KOALA_E_DEVICE"}
 
 
+STATUS_BY_NAME = {name: code for code, name in _STATUS.items()}
+
+
 class KoalaError(RuntimeError):
     def __init__(self, status, msg=""):
         self.status = status
@@ -129,6 +132,12 @@ def weights_to_f16(packed, stream=None):
     if rc != 0:
         raise KoalaError(rc, "koala_weights_to_half failed")
     return packed.view(torch.float16)
+
+
+def weights_to_half_status(ptr, n_elements, stream=None):
+    """The raw status of koala_weights_to_half for a device address and an element count (tests of its argument
+    checks use this; everyone else wants weights_to_f16)."""
+    return load_library().koala_weights_to_half(_stream(stream), C.c_void_p(ptr), n_elements)
 
 
 def measure_stream_read(buffer, repeats=5, stream=None):

@@ -158,3 +158,33 @@ def test_results_do_not_depend_on_what_the_workspace_held(name, batch):
         again = case.gpu_verify(tt)
         np.testing.assert_array_equal(first[1], again[1])
         np.testing.assert_array_equal(first[0], again[0])
+
+
+def test_weights_to_half_is_exact_and_rejects_bad_arguments():
+    """koala_weights_to_half re-encodes bfloat16 values as fp16 in place: bit for bit what a conversion through
+    fp32 with round-to-nearest-even gives, and the same number wherever fp16 can hold it (magnitudes 2^-14 ..
+    65504 here; down to 2^-24 the eight significant bits still fit the subnormal grid), for both signs, zeros and
+    the exponent range a weight can have.  Bad sizes, alignments and pointers are refused before any launch."""
+    from paper_2408_08146_amd.binding import weights_to_half_status, STATUS_BY_NAME
+    rng = np.random.default_rng(5)
+    n = 1 << 16
+    vals = np.exp2(rng.uniform(-30.0, 17.0, n)).astype(np.float32) * rng.choice([-1.0, 1.0], n).astype(np.float32)
+    vals[:64] = [0.0, -0.0, 65504.0, -65504.0, 2.0 ** -14, 2.0 ** -24, 2.0 ** -25, 1.0] * 8
+    bits = (vals.view(np.uint32) >> 16).astype(np.uint16)          # any bf16 bit pattern will do: truncate
+    as_f32 = (bits.astype(np.uint32) << 16).view(np.float32)       # the bf16 values
+    with np.errstate(over="ignore"):
+        ref = as_f32.astype(np.float16)                            # numpy: round to nearest even, inf beyond 65504
+    t = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    out = K.weights_to_f16(t)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    np.testing.assert_array_equal(got.view(np.uint16), ref.view(np.uint16))
+    exact = (np.abs(as_f32) >= 2.0 ** -14) & (np.abs(as_f32) <= 65504.0)
+    assert exact.sum() > n // 2
+    np.testing.assert_array_equal(got.astype(np.float32)[exact], as_f32[exact])
+    buf = torch.zeros(64, dtype=torch.bfloat16, device="cuda")
+    assert weights_to_half_status(0, 64) == STATUS_BY_NAME["KOALA_E_NULL"]
+    assert weights_to_half_status(buf.data_ptr(), 12) == STATUS_BY_NAME["KOALA_E_SHAPE"]
+    assert weights_to_half_status(buf.data_ptr() + 2, 8) == STATUS_BY_NAME["KOALA_E_ALIGN"]
+    torch.cuda.synchronize()
+    assert float(buf.float().abs().max().item()) == 0.0
