@@ -1407,6 +1407,16 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *p, size_t bytes) {
 __device__ __forceinline__ void st_sc1(rsrc_t r, size_t off, f32x4 v) {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, AUX_SC1);
 }
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+__device__ __forceinline__ void st_sc1(rsrc_t r, size_t off, u32x2 v) {
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)off, 0, AUX_SC1);
+}
+__device__ __forceinline__ u32x4 ld4u_sc1(rsrc_t r, size_t off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, AUX_SC1);
+}
+__device__ __forceinline__ f32x2 half_pair_to_float(uint32_t p) {
+    return __builtin_convertvector(__builtin_bit_cast(f16x2, p), f32x2);
+}
 __device__ __forceinline__ void st_sc1(rsrc_t r, size_t off, float v) {
     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)off, 0, AUX_SC1);
 }
@@ -1438,7 +1448,7 @@ struct AttnArgs {
     const u32x4 *qf;      // [batch][n_heads][MTQ][KS][hi, lo][64] query fragments
     RowMeta meta;
     const bf16_t *kc, *vc;
-    float *o_part, *ml;   // [row][head][split][DH], [row][head][split][max, sum]
+    float *o_part, *ml;   // [row][head][split][DH] fp16 averages (in a buffer sized for fp32), [row][head][split][max, sum]
     unsigned opart_bytes, ml_bytes;
     int *counters;        // [batch][n_heads][row groups], zero between launches
     u32x4 *Xf;            // merged output: GEMM input fragments, K = n_heads * DH, MT_out activation tiles
@@ -1732,9 +1742,16 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(const u32x4 *qf_in, cons
             const int row = (mt0 + mt) * 16 + li;
             if (row < rows_per_seq) {
                 const size_t r = (size_t)b * rows_per_seq + row;
-                const size_t o = (((r * n_heads + h) * nsplit + s) * DH) * 4;
+                // the output as the split's own softmax average (divided by its sum, so that it is bounded by the
+                // values it averages), in fp16: half the bytes that the merging workgroup has to take in, and the
+                // merged rows are rounded to fp16 for the O projection anyway
+                const size_t o = (((r * n_heads + h) * nsplit + s) * DH) * 2;
+                const float inv_l = l_run[mt] > 0.f ? 1.0f / l_run[mt] : 0.f;
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) st_sc1(ro, o + (dt * 16 + 4 * lg) * 4, acc_o[mt][dt]);
+                for (int dt = 0; dt < DT; ++dt) {
+                    const f32x4 v = acc_o[mt][dt] * inv_l;
+                    st_sc1(ro, o + (dt * 16 + 4 * lg) * 2, (u32x2){half_pair(v[0], v[1]), half_pair(v[2], v[3])});
+                }
                 if (lg == 0) {
                     const size_t pm = (((r * n_heads + h) * nsplit + s) * 2) * 4;
                     st_sc1(rm, pm, m_run[mt]);
@@ -1760,19 +1777,17 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(const u32x4 *qf_in, cons
         const int row = mt0 * 16 + u / (DH / 8), d0 = (u % (DH / 8)) * 8;
         if (row >= rows_per_seq) continue;
         const size_t r = (size_t)b * rows_per_seq + row;
-        const size_t ob = ((r * n_heads + h) * nsplit) * DH * 4 + d0 * 4, mb = ((r * n_heads + h) * nsplit) * 2 * 4;
-        f32x4 oa[KOALA_NSPLIT_MAX], oc[KOALA_NSPLIT_MAX];
+        const size_t ob = ((r * n_heads + h) * nsplit) * DH * 2 + d0 * 2, mb = ((r * n_heads + h) * nsplit) * 2 * 4;
+        u32x4 oh[KOALA_NSPLIT_MAX];   // eight fp16 values of the split's average
         float ms[KOALA_NSPLIT_MAX], ls[KOALA_NSPLIT_MAX];
 #pragma unroll
         for (int q = 0; q < KOALA_NSPLIT_MAX; ++q) {
             if (q < nsplit) {
-                oa[q] = ld4_sc1(ro, ob + (size_t)q * DH * 4);
-                oc[q] = ld4_sc1(ro, ob + (size_t)q * DH * 4 + 16);
+                oh[q] = ld4u_sc1(ro, ob + (size_t)q * DH * 2);
                 ms[q] = ld1_sc1(rm, mb + q * 8);
                 ls[q] = ld1_sc1(rm, mb + q * 8 + 4);
             } else {
-                oa[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                oc[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                oh[q] = (u32x4){0u, 0u, 0u, 0u};
                 ms[q] = -INFINITY;
                 ls[q] = 0.f;
             }
@@ -1780,18 +1795,25 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(const u32x4 *qf_in, cons
         float Mx = -INFINITY;
 #pragma unroll
         for (int q = 0; q < KOALA_NSPLIT_MAX; ++q) Mx = fmaxf(Mx, ms[q]);
-        f32x4 ya = {0.f, 0.f, 0.f, 0.f}, yc = {0.f, 0.f, 0.f, 0.f};
+        float ys[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         float den = 0.f;
 #pragma unroll
         for (int q = 0; q < KOALA_NSPLIT_MAX; ++q) {
-            const float w = (ms[q] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms[q] - Mx);
-            den += w * ls[q];
-            ya += w * oa[q];
-            yc += w * oc[q];
+            // weight of the split's average: its share of the softmax sum
+            const float w = (ms[q] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms[q] - Mx) * ls[q];
+            den += w;
+            const uint32_t d[4] = {oh[q].x, oh[q].y, oh[q].z, oh[q].w};
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                const f32x2 p = half_pair_to_float(d[z]);
+                ys[2 * z] += w * p[0];
+                ys[2 * z + 1] += w * p[1];
+            }
         }
         const float inv = 1.0f / den;
-        const float y[8] = {ya[0] * inv, ya[1] * inv, ya[2] * inv, ya[3] * inv, yc[0] * inv, yc[1] * inv, yc[2] * inv,
-                            yc[3] * inv};
+        float y[8];
+#pragma unroll
+        for (int z = 0; z < 8; ++z) y[z] = ys[z] * inv;
         store_frag8(a.Xf, a.MT_out, (int)r, h * DH + d0, y);
     }
 }
