@@ -1694,75 +1694,63 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_tree(const u32x4 *qf_in, cons
     for (int mt = 0; mt < MT; ++mt) {
         l_run[mt] = lane_groups_sum(l_run[mt]);
     }
-    // ---- merge the waves through LDS (the Q / V regions are free now), halving the number of live states per
-    //      round: waves [n/2, n) hand theirs to waves [0, n/2)
-    float *mo = (float *)smem;                                  // [NWV/2 waves][MT][DT][64][4]
-    float *mm = mo + (size_t)(NWV / 2) * MT * DT * 256;         // [NWV/2 waves][MT][64][2]
+    // ---- merge the waves through LDS (the Q / V regions are free now) in one round: every wave that had a step
+    //      leaves its state there, then each wave combines, for its share of the (row tile, 16 dimensions) pieces,
+    //      the states of all of them (in wave order: deterministic) and writes the piece of this split's partial
+    //      result through to memory: the softmax average of the split's keys (the output divided by its sum, so
+    //      that it is bounded by the values it averages) in fp16, half the bytes that the merging workgroup has to
+    //      take in (the merged rows are rounded to fp16 for the O projection anyway), with the running maximum and
+    //      the sum beside it.
+    float *mo = (float *)smem;                                  // [NWV waves][MT][DT][64][4]
+    float *mm = mo + (size_t)NWV * MT * DT * 256;               // [NWV waves][MT][16 rows][max, sum]
+    // waves 0 .. nact-1 had at least one step (wave w starts at step s + nsplit * w)
+    const int nact = min(NWV, max(0, (nsteps - s + nsplit - 1) / nsplit));
+    __syncthreads();
+    if (wave < nact) {
 #pragma unroll
-    for (int n = NWV; n > 1; n >>= 1) {
-        const int hn = n >> 1;
-        __syncthreads();
-        if (wave >= hn && wave < n) {
-            const int w = wave - hn;
+        for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-                    *(f32x4 *)(mo + ((((size_t)w * MT + mt) * DT + dt) * 64 + l) * 4) = acc_o[mt][dt];
-                mm[((w * MT + mt) * 64 + l) * 2 + 0] = m_run[mt];
-                mm[((w * MT + mt) * 64 + l) * 2 + 1] = l_run[mt];
-            }
-        }
-        __syncthreads();
-        if (wave < hn) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const float mw = mm[((wave * MT + mt) * 64 + l) * 2], lw = mm[((wave * MT + mt) * 64 + l) * 2 + 1];
-                const float M = fmaxf(m_run[mt], mw);
-                const float a0 = (m_run[mt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[mt] - M);
-                const float aw = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-                l_run[mt] = l_run[mt] * a0 + lw * aw;
-                m_run[mt] = M;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const f32x4 o = *(const f32x4 *)(mo + ((((size_t)wave * MT + mt) * DT + dt) * 64 + l) * 4);
-                    acc_o[mt][dt][0] = acc_o[mt][dt][0] * a0 + aw * o[0];
-                    acc_o[mt][dt][1] = acc_o[mt][dt][1] * a0 + aw * o[1];
-                    acc_o[mt][dt][2] = acc_o[mt][dt][2] * a0 + aw * o[2];
-                    acc_o[mt][dt][3] = acc_o[mt][dt][3] * a0 + aw * o[3];
-                }
+            for (int dt = 0; dt < DT; ++dt)
+                *(f32x4 *)(mo + ((((size_t)wave * MT + mt) * DT + dt) * 64 + l) * 4) = acc_o[mt][dt];
+            if (lg == 0) {
+                mm[((wave * MT + mt) * 16 + li) * 2 + 0] = m_run[mt];
+                mm[((wave * MT + mt) * 16 + li) * 2 + 1] = l_run[mt];
             }
         }
     }
-    // ---- wave 0 writes this split's partial result through to memory
+    __syncthreads();
     const rsrc_t ro = make_rsrc(a.o_part, a.opart_bytes), rm = make_rsrc(a.ml, a.ml_bytes);
-    if (wave == 0) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int row = (mt0 + mt) * 16 + li;
-            if (row < rows_per_seq) {
-                const size_t r = (size_t)b * rows_per_seq + row;
-                // the output as the split's own softmax average (divided by its sum, so that it is bounded by the
-                // values it averages), in fp16: half the bytes that the merging workgroup has to take in, and the
-                // merged rows are rounded to fp16 for the O projection anyway
-                const size_t o = (((r * n_heads + h) * nsplit + s) * DH) * 2;
-                const float inv_l = l_run[mt] > 0.f ? 1.0f / l_run[mt] : 0.f;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const f32x4 v = acc_o[mt][dt] * inv_l;
-                    st_sc1(ro, o + (dt * 16 + 4 * lg) * 2, (u32x2){half_pair(v[0], v[1]), half_pair(v[2], v[3])});
-                }
-                if (lg == 0) {
-                    const size_t pm = (((r * n_heads + h) * nsplit + s) * 2) * 4;
-                    st_sc1(rm, pm, m_run[mt]);
-                    st_sc1(rm, pm + 4, l_run[mt]);
-                }
+    for (int p = wave; p < MT * DT; p += NWV) {
+        const int mt = p / DT, dt = p % DT;
+        float M = -INFINITY;
+        for (int w = 0; w < nact; ++w) M = fmaxf(M, mm[((w * MT + mt) * 16 + li) * 2]);
+        float L = 0.f;
+        f32x4 O = {0.f, 0.f, 0.f, 0.f};
+        for (int w = 0; w < nact; ++w) {
+            const float mw = mm[((w * MT + mt) * 16 + li) * 2], lw = mm[((w * MT + mt) * 16 + li) * 2 + 1];
+            const float aw = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+            L += aw * lw;
+            O += aw * *(const f32x4 *)(mo + ((((size_t)w * MT + mt) * DT + dt) * 64 + l) * 4);
+        }
+        const int row = (mt0 + mt) * 16 + li;
+        if (row < rows_per_seq) {
+            const size_t r = (size_t)b * rows_per_seq + row;
+            const size_t o = (((r * n_heads + h) * nsplit + s) * DH) * 2;
+            const f32x4 v = O * (L > 0.f ? 1.0f / L : 0.f);
+            st_sc1(ro, o + (dt * 16 + 4 * lg) * 2, (u32x2){half_pair(v[0], v[1]), half_pair(v[2], v[3])});
+            if (dt == 0 && lg == 0) {
+                const size_t pm = (((r * n_heads + h) * nsplit + s) * 2) * 4;
+                st_sc1(rm, pm, M);
+                st_sc1(rm, pm + 4, L);
             }
         }
-        // the partial results were written through (sc1), so nothing of this wave's is left in a cache to be
-        // written back: it is enough that the stores have been acknowledged before the counter moves
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_s_waitcnt(0);
+    }
+    // the partial results were written through (sc1), so nothing of a wave's is left in a cache to be written back:
+    // it is enough that every wave's stores have been acknowledged before the counter moves
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (wave == 0) {
         if (l == 0) {
             int *cnt = a.counters + ((size_t)b * n_heads + h) * ngroups + grp;
             const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1822,7 +1810,7 @@ template <int DH, int MT, int NWV>
 void launch_attn(hipStream_t st, const AttnArgs &a, int batch) {
     constexpr int KS = DH / 32, DT = DH / 16, VS = DH * 2 + 32;
     const size_t main_b = (size_t)MT * KS * 2 * 64 * 16 + (size_t)NWV * 32 * VS;
-    const size_t merge_b = (size_t)(NWV / 2) * MT * DT * 256 * 4 + (size_t)(NWV / 2) * MT * 64 * 2 * 4;
+    const size_t merge_b = (size_t)NWV * MT * DT * 256 * 4 + (size_t)NWV * MT * 16 * 2 * 4;
     const size_t sm = main_b > merge_b ? main_b : merge_b;
     static bool done = false;
     if (!done) {
