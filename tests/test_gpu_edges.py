@@ -188,3 +188,23 @@ def test_weights_to_half_is_exact_and_rejects_bad_arguments():
     assert weights_to_half_status(buf.data_ptr() + 2, 8) == STATUS_BY_NAME["KOALA_E_ALIGN"]
     torch.cuda.synchronize()
     assert float(buf.float().abs().max().item()) == 0.0
+
+
+def test_activations_beyond_the_fp16_range_saturate_instead_of_overflowing():
+    """GEMM inputs are fp16: a hidden state beyond +-65504 (here embedding rows of +-3e5) is clamped to the largest
+    fp16 value where it is written as a GEMM input, so every projection, the features and the logits stay finite
+    (they differ from the exact result, which is the documented limit of the format)."""
+    from koala_synth import target_weights, eagle_weights
+
+    def weights(cfg):
+        shape = (cfg["vocab"], cfg["hidden"])
+        sign = np.where(np.arange(shape[0] * shape[1]).reshape(shape) % 3 == 0, -1.0, 1.0).astype(np.float32)
+        return (target_weights(cfg, 0, cache=True, overrides={"embed": lambda: 3.0e5 * sign}),
+                eagle_weights(cfg, 0, cache=True))
+
+    case = Case("cfg2_small", n_layers=2, weights=weights)
+    case.fill_kv_normal()
+    case.upload_kv()
+    feat, logits, greedy = case.gpu_verify(case.random_tree_tokens())
+    assert np.isfinite(feat).all() and np.isfinite(logits).all()
+    assert np.abs(logits).max() > 0.0
