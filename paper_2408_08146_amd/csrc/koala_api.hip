@@ -257,7 +257,10 @@ void decoder_layer_bf16(koala_ctx *c, hipStream_t st, int batch, int rows_per_se
     const int rows = batch * rows_per_seq, H = s.hidden, F = s.ffn, MT = kb::mt_of(rows), Mp = MT * 16;
     // key splits of the attention: as many as keep the launch within one workgroup per compute unit (sequences of
     // more than 32 rows take two workgroups per split and head), at most the count the workspace was carved for
-    const int ns = std::max(1, std::min(c->attn_ns, c->n_cu / (s.n_heads * batch * (rows_per_seq > 32 ? 2 : 1))));
+    // and no more than give every one of a workgroup's eight waves one 32-key step of a full cache (more splits
+    // only add partial results for the merging workgroup to take in; the context length itself lives on the device)
+    const int ns_room = std::max(1, std::min(c->attn_ns, c->n_cu / (s.n_heads * batch * (rows_per_seq > 32 ? 2 : 1))));
+    const int ns = std::min(ns_room, std::max(1, ((c->kv.capacity + 31) / 32 + 7) / 8));
     const bool fused = MT <= 4;
     fold_pending(c, st, rows, MT, lw[0]);
     int S;

@@ -44,9 +44,10 @@ def test_cfg2_full_width_verify(case):
     _, slogits, _ = case.oracle_verify(tt)
     serr = rel_err_rows(logits, slogits).max()
     print(f"full-width verify vs storage-rounding oracle: max logit error {serr:.2e}")
-    # what is left is the rounding of every GEMM input to fp16 (eleven significant bits): below 1e-3 after two
-    # layers, 3.7e-3 after all 32
-    assert serr < (1e-3 if case.cfg["n_layers"] <= 2 else 5e-3)
+    # what is left is the rounding of every GEMM input to fp16: up to 2^-11 = 4.9e-4 of a value, nine times on the
+    # way through two layers and the LM head (about 1.5e-3 if the nine add up like independent errors; measured
+    # 1.0e-3), 3.7e-3 measured after all 32 layers
+    assert serr < (2e-3 if case.cfg["n_layers"] <= 2 else 5e-3)
     for c in case.tc:
         c.store = None
 
